@@ -1,0 +1,212 @@
+"""ctypes front end of the CPU oracle (oracle/sr_oracle.c).
+
+TEST INFRASTRUCTURE: only tests/, __graft_entry__.smoke() and the
+cpu_baseline leg of bench.py may import this module.  It shares no code with
+the HIP library and imports nothing from the product package.
+
+BF16 data are numpy uint16 arrays holding the bit patterns; FP32 data are
+numpy float32 arrays.  All arrays must be C-contiguous.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+FLAG_FP32_MOMENTS = 1
+FLAG_RNE_MOMENTS = 2
+
+STREAM_PARAM, STREAM_M, STREAM_V, STREAM_CAST = 0, 1, 2, 3
+
+
+class Scalars(C.Structure):
+    _fields_ = [(n, C.c_float) for n in
+                ("beta1", "beta2", "omb1", "omb2", "rbc1", "rbc2", "lr", "eps", "lw", "clip")]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        u16p, u32p, f32p = (C.POINTER(C.c_uint16), C.POINTER(C.c_uint32), C.POINTER(C.c_float))
+        L.ref_philox4x32_10.argtypes = [u32p, u32p, u32p]
+        L.ref_philox4x32_10.restype = None
+        L.ref_r16.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint32]
+        L.ref_r16.restype = C.c_uint32
+        L.ref_r16_many.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint64,
+                                   C.c_uint32, u16p]
+        L.ref_r16_many.restype = None
+        L.ref_sr_round.argtypes = [C.c_float, C.c_uint32]
+        L.ref_sr_round.restype = C.c_uint16
+        L.ref_rne_round.argtypes = [C.c_float]
+        L.ref_rne_round.restype = C.c_uint16
+        L.ref_sr_round_many.argtypes = [f32p, u32p, C.c_uint64, u16p]
+        L.ref_sr_round_many.restype = None
+        L.ref_sr_round_all_draws.argtypes = [f32p, u16p]
+        L.ref_sr_round_all_draws.restype = None
+        L.ref_sr_cast_f32_bf16.argtypes = [f32p, u16p, C.c_uint64, C.c_uint64, C.c_uint32,
+                                           C.c_uint32, C.c_uint64, C.c_int]
+        L.ref_sr_cast_f32_bf16.restype = None
+        L.ref_adamw_scalars.argtypes = [C.c_float] * 5 + [C.c_uint32, f32p, C.c_float,
+                                                          C.POINTER(Scalars)]
+        L.ref_adamw_scalars.restype = None
+        L.ref_adamw_unrounded.argtypes = [u16p, u16p, C.c_void_p, C.c_void_p, C.c_uint64,
+                                          C.POINTER(Scalars), C.c_uint32, f32p, f32p, f32p]
+        L.ref_adamw_unrounded.restype = None
+        L.ref_sr_adamw_tensor.argtypes = [u16p, u16p, C.c_void_p, C.c_void_p, C.c_uint64,
+                                          C.c_uint32, C.c_uint64, C.POINTER(Scalars),
+                                          C.c_uint32, C.c_uint64, C.c_uint32, C.c_int]
+        L.ref_sr_adamw_tensor.restype = None
+        L.ref_grad_global_norm.argtypes = [C.POINTER(u16p), C.POINTER(C.c_uint64), C.c_uint32]
+        L.ref_grad_global_norm.restype = C.c_float
+        L.ref_max_threads.argtypes = []
+        L.ref_max_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _u16(a):
+    assert a.dtype == np.uint16 and a.flags.c_contiguous
+    return a.ctypes.data_as(C.POINTER(C.c_uint16))
+
+
+def _f32(a):
+    assert a.dtype == np.float32 and a.flags.c_contiguous
+    return a.ctypes.data_as(C.POINTER(C.c_float))
+
+
+def _u32(a):
+    assert a.dtype == np.uint32 and a.flags.c_contiguous
+    return a.ctypes.data_as(C.POINTER(C.c_uint32))
+
+
+# ------------------------------------------------------------------ plumbing
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Exact decode of BF16 bit patterns (uint16) to float32 (format definition)."""
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def max_threads() -> int:
+    return int(lib().ref_max_threads())
+
+
+# ----------------------------------------------------------------------- RNG
+
+def philox4x32_10(ctr, key):
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    out = np.zeros(4, dtype=np.uint32)
+    lib().ref_philox4x32_10(_u32(c), _u32(k), _u32(out))
+    return out
+
+
+def r16(seed, step, tensor_id, i, stream):
+    return int(lib().ref_r16(seed, step, tensor_id, i, stream))
+
+
+def r16_many(seed, step, tensor_id, i0, n, stream) -> np.ndarray:
+    out = np.empty(n, dtype=np.uint16)
+    lib().ref_r16_many(seed, step, tensor_id, i0, n, stream, _u16(out))
+    return out
+
+
+# ------------------------------------------------------------------ rounding
+
+def sr_round(y, r):
+    return int(lib().ref_sr_round(C.c_float(float(y)), int(r)))
+
+
+def rne_round(y):
+    return int(lib().ref_rne_round(C.c_float(float(y))))
+
+
+def sr_round_many(y: np.ndarray, r: np.ndarray) -> np.ndarray:
+    y = np.ascontiguousarray(y, dtype=np.float32)
+    r = np.ascontiguousarray(r, dtype=np.uint32)
+    out = np.empty(y.shape, dtype=np.uint16)
+    lib().ref_sr_round_many(_f32(y), _u32(r), y.size, _u16(out))
+    return out
+
+
+def sr_round_all_draws(y_bits: int) -> np.ndarray:
+    """Q_SR of the binary32 value with encoding `y_bits` for every draw 0..65535."""
+    y = np.array([y_bits], dtype=np.uint32).view(np.float32)
+    out = np.empty(65536, dtype=np.uint16)
+    lib().ref_sr_round_all_draws(_f32(y), _u16(out))
+    return out
+
+
+def sr_cast_f32_bf16(src: np.ndarray, seed, step, tensor_id, elem_offset=0, nthreads=0):
+    src = np.ascontiguousarray(src, dtype=np.float32)
+    dst = np.empty(src.shape, dtype=np.uint16)
+    lib().ref_sr_cast_f32_bf16(_f32(src), _u16(dst), src.size, seed, step, tensor_id,
+                               elem_offset, nthreads)
+    return dst
+
+
+# --------------------------------------------------------------------- AdamW
+
+def adamw_scalars(lr, beta1, beta2, eps, weight_decay, step, norm=None, max_norm=0.0) -> Scalars:
+    s = Scalars()
+    if norm is None:
+        nptr = None
+    else:
+        nv = C.c_float(float(norm))
+        nptr = C.pointer(nv)
+    lib().ref_adamw_scalars(lr, beta1, beta2, eps, weight_decay, step, nptr, max_norm, C.byref(s))
+    return s
+
+
+def _moment_ptr(a, flags):
+    if flags & FLAG_FP32_MOMENTS:
+        assert a.dtype == np.float32 and a.flags.c_contiguous
+    else:
+        assert a.dtype == np.uint16 and a.flags.c_contiguous
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def adamw_unrounded(p, g, m, v, scalars: Scalars, flags=0):
+    n = p.size
+    y = np.empty(n, np.float32)
+    m1 = np.empty(n, np.float32)
+    v1 = np.empty(n, np.float32)
+    lib().ref_adamw_unrounded(_u16(p), _u16(g), _moment_ptr(m, flags), _moment_ptr(v, flags), n,
+                              C.byref(scalars), flags, _f32(y), _f32(m1), _f32(v1))
+    return y, m1, v1
+
+
+def sr_adamw_tensor(p, g, m, v, tensor_id, scalars: Scalars, step, seed, flags=0,
+                    elem_offset=0, nthreads=0):
+    """One tensor, in place over p, m, v (numpy arrays)."""
+    assert p.size == g.size == m.size == v.size
+    lib().ref_sr_adamw_tensor(_u16(p), _u16(g), _moment_ptr(m, flags), _moment_ptr(v, flags),
+                              p.size, tensor_id, elem_offset, C.byref(scalars), step, seed,
+                              flags, nthreads)
+
+
+def sr_adamw_step(tensors, hyper, step, seed, flags=0, norm=None, max_norm=0.0, nthreads=0):
+    """Multi-tensor step: `tensors` is a list of dicts with numpy arrays p, g, m, v and
+    optional tensor_id (default: list index) and elem_offset (default 0).
+    hyper = dict(lr, beta1, beta2, eps, weight_decay)."""
+    s = adamw_scalars(hyper["lr"], hyper["beta1"], hyper["beta2"], hyper["eps"],
+                      hyper["weight_decay"], step, norm, max_norm)
+    for idx, t in enumerate(tensors):
+        sr_adamw_tensor(t["p"], t["g"], t["m"], t["v"], t.get("tensor_id", idx), s, step, seed,
+                        flags, t.get("elem_offset", 0), nthreads)
+    return s
+
+
+def grad_global_norm(grads) -> float:
+    n = len(grads)
+    ptrs = (C.POINTER(C.c_uint16) * max(n, 1))()
+    sizes = (C.c_uint64 * max(n, 1))()
+    for i, g in enumerate(grads):
+        ptrs[i] = _u16(g)
+        sizes[i] = g.size
+    return float(lib().ref_grad_global_norm(ptrs, sizes, n))

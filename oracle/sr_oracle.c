@@ -1,0 +1,367 @@
+/*
+ * CPU oracle for the SR-AdamW update path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain definition that the GPU library is checked
+ * against.  Nothing in the product path may call it, link it or fall back
+ * to it; it shares no source, header, table or constant with the HIP code.
+ *
+ * What it follows (arXiv 2502.20566, "Stochastic Rounding for LLM Training:
+ * Theory and Practice"):
+ *   - stochastic rounding Q_SR: Eq.(2), Section 2.1 -- written out as the
+ *     interval definition on VALUES (frexp/ldexp/floor in double), not as
+ *     the add-noise-and-truncate trick the GPU uses (Section 3, "dithering");
+ *   - the coupling of the random draw to the outcome: proof of the Lemma on
+ *     the SR perturbation, Appendix B (round up when the draw falls below the
+ *     fractional position q), in the equivalent integer form
+ *     "away from zero iff r16 + k >= 65536";
+ *   - AdamW with SR on the write-back: Algorithm 1, lines 5-10, Section 3,
+ *     with eps outside the root (the standard AdamW denominator; line 10 as
+ *     printed takes a second root of an already rooted quantity);
+ *   - shared randomness across replicas: Algorithm 1 lines 9/11, realised as
+ *     a stateless counter RNG (Philox4x32-10, Salmon et al., SC'11) keyed on
+ *     (seed, step, tensor id, element index, output stream): no rank and no
+ *     launch geometry enters the key.
+ *
+ * Arithmetic contract of the update: IEEE binary32, round to nearest even,
+ * one rounding per listed operation, no fused multiply-add, correctly
+ * rounded sqrt and divide, no flushing of subnormals.  Build with
+ *   gcc -O2 -ffp-contract=off -fno-fast-math -fopenmp
+ * (x86-64 scalar SSE arithmetic: float expressions are evaluated in float).
+ *
+ * Pins (tests/test_oracle_*.py): exhaustive SR counts over all 2^16 draws,
+ * exact unbiasedness and second moment, Philox known-answer vectors of the
+ * Random123 distribution, 10^4-seed mean test, the random-walk example of
+ * Section 2.2, Adam step-1 closed form, exact-rational evaluation of
+ * Algorithm 1 on tiny inputs, torch.optim.AdamW on FP32 state, exact norms.
+ * No function here is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+#include <stdlib.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define REF_FLAG_FP32_MOMENTS 1u
+#define REF_FLAG_RNE_MOMENTS  2u
+
+/* ---------------------------------------------------------------- RNG --- */
+
+/* Philox4x32 with 10 rounds.  One round maps (c0,c1,c2,c3) under key (k0,k1)
+ * to (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1, lo(M0*c0)); the key is
+ * advanced by the two Weyl constants between rounds. */
+void ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) { k0 += W0; k1 += W1; }
+        uint64_t prod0 = M0 * (uint64_t)c0;
+        uint64_t prod1 = M1 * (uint64_t)c2;
+        uint32_t n0 = (uint32_t)(prod1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)prod1;
+        uint32_t n2 = (uint32_t)(prod0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)prod0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The 16 random bits of element `i` (index within its tensor, 64-bit) of
+ * output stream `stream` (0 = parameter, 1 = first moment, 2 = second moment,
+ * 3 = standalone cast).  Eight consecutive elements share one Philox block:
+ * counter = (block low word, stream<<29 | block high bits, tensor id, step),
+ * key = the two halves of the seed; element j = i mod 8 takes the low (j even)
+ * or high (j odd) half of output word j/2. */
+uint32_t ref_r16(uint64_t seed, uint32_t step, uint32_t tensor_id, uint64_t i, uint32_t stream)
+{
+    uint64_t blk = i >> 3;
+    uint32_t ctr[4], key[2], w[4];
+    ctr[0] = (uint32_t)(blk & 0xFFFFFFFFu);
+    ctr[1] = (stream << 29) | (uint32_t)(blk >> 32);
+    ctr[2] = tensor_id;
+    ctr[3] = step;
+    key[0] = (uint32_t)(seed & 0xFFFFFFFFu);
+    key[1] = (uint32_t)(seed >> 32);
+    ref_philox4x32_10(ctr, key, w);
+    unsigned j = (unsigned)(i & 7u);
+    return (w[j >> 1] >> (16u * (j & 1u))) & 0xFFFFu;
+}
+
+/* out[n] = r16 of elements i0 .. i0+n-1 (for distribution tests). */
+void ref_r16_many(uint64_t seed, uint32_t step, uint32_t tensor_id, uint64_t i0, uint64_t n,
+                  uint32_t stream, uint16_t* out)
+{
+    for (uint64_t i = 0; i < n; ++i)
+        out[i] = (uint16_t)ref_r16(seed, step, tensor_id, i0 + i, stream);
+}
+
+/* ------------------------------------------------------ BF16 encoding --- */
+
+static float bf16_bits_to_float(uint16_t h)
+{
+    /* BF16 is the upper half of the binary32 encoding: decoding is exact. */
+    uint32_t b = (uint32_t)h << 16;
+    float f; memcpy(&f, &b, 4); return f;
+}
+
+static uint16_t float_on_bf16_grid_to_bits(float f)
+{
+    /* Only ever called with a value that IS a BF16 value (or +-inf): the low
+     * half of the encoding is zero, nothing is rounded here. */
+    uint32_t b; memcpy(&b, &f, 4);
+    if (b & 0xFFFFu) abort();
+    return (uint16_t)(b >> 16);
+}
+
+/* ------------------------------------------------ stochastic rounding --- */
+
+/* Q_SR of Eq.(2) for binary32 -> BF16 with the draw r16 in [0, 65535].
+ *   a  = |y|;  lo = largest BF16 magnitude <= a;  hi = next BF16 magnitude;
+ *   k  = 65536 (a - lo)/(hi - lo)   (an integer: exactly 2^16 binary32
+ *        values lie in [lo, hi) at uniform spacing, subnormal range included);
+ *   magnitude = hi  iff  r16 + k >= 65536,  else lo;  sign of y is kept.
+ * So P(away from zero) = k/65536 = (a - lo)/(hi - lo), which is Eq.(2) for
+ * either sign, and a value already on the BF16 grid (k = 0) never moves.
+ * Above the largest finite BF16, hi = 2^128 is emitted as infinity.
+ * Infinities pass through; a NaN becomes the quiet NaN with the same sign
+ * and the same upper payload bits. */
+uint16_t ref_sr_round(float y, uint32_t r16)
+{
+    uint32_t ybits; memcpy(&ybits, &y, 4);
+    if (isnan(y)) return (uint16_t)((ybits >> 16) | 0x0040u);
+    if (isinf(y)) return (uint16_t)(ybits >> 16);
+
+    double a = fabs((double)y);
+    double lo, hi;
+    if (a == 0.0) {
+        lo = 0.0; hi = ldexp(1.0, -133);
+    } else {
+        int e;
+        (void)frexp(a, &e);              /* a = f * 2^e with f in [0.5, 1) */
+        int q = e - 8;                   /* BF16 keeps 8 significant bits  */
+        if (q < -133) q = -133;          /* fixed spacing below 2^-126      */
+        double spacing = ldexp(1.0, q);
+        lo = floor(a / spacing) * spacing;
+        hi = lo + spacing;
+    }
+    double k = 65536.0 * (a - lo) / (hi - lo);
+    if (k != floor(k) || k < 0.0 || k > 65535.0) abort();   /* exact by construction */
+    double mag = ((double)r16 + k >= 65536.0) ? hi : lo;
+    float out = (mag >= ldexp(1.0, 128)) ? INFINITY : (float)mag;   /* (float)mag is exact */
+    out = copysignf(out, y);
+    return float_on_bf16_grid_to_bits(out);
+}
+
+/* Round-to-nearest-even to BF16 by value (Eq.(1), ties to the even
+ * significand): the deterministic comparison rounding. */
+uint16_t ref_rne_round(float y)
+{
+    uint32_t ybits; memcpy(&ybits, &y, 4);
+    if (isnan(y)) return (uint16_t)((ybits >> 16) | 0x0040u);
+    if (isinf(y)) return (uint16_t)(ybits >> 16);
+    double a = fabs((double)y);
+    double mag = 0.0;
+    if (a != 0.0) {
+        int e; (void)frexp(a, &e);
+        int q = e - 8; if (q < -133) q = -133;
+        double spacing = ldexp(1.0, q);
+        double n = floor(a / spacing);
+        double rem = a / spacing - n;            /* exact: a/spacing has <= 24 bits */
+        if (rem > 0.5 || (rem == 0.5 && fmod(n, 2.0) == 1.0)) n += 1.0;
+        mag = n * spacing;
+    }
+    float out = (mag >= ldexp(1.0, 128)) ? INFINITY : (float)mag;
+    out = copysignf(out, y);
+    return float_on_bf16_grid_to_bits(out);
+}
+
+void ref_sr_round_many(const float* y, const uint32_t* r16, uint64_t n, uint16_t* out)
+{
+    for (uint64_t i = 0; i < n; ++i) out[i] = ref_sr_round(y[i], r16[i]);
+}
+
+/* All 65536 draws for one input, out[r] = Q_SR(*y; r).  The input is passed
+ * by address so that a signalling-NaN encoding reaches the function intact. */
+void ref_sr_round_all_draws(const float* y, uint16_t* out)
+{
+    for (uint32_t r = 0; r < 65536u; ++r) out[r] = ref_sr_round(*y, r);
+}
+
+/* Standalone cast: dst[i] = Q_SR(src[i]; r16(seed, step, tensor_id, elem_offset + i, stream 3)). */
+void ref_sr_cast_f32_bf16(const float* src, uint16_t* dst, uint64_t n,
+                          uint64_t seed, uint32_t step, uint32_t tensor_id,
+                          uint64_t elem_offset, int nthreads)
+{
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+    #pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < (int64_t)n; ++i) {
+        uint32_t r = ref_r16(seed, step, tensor_id, elem_offset + (uint64_t)i, 3u);
+        dst[i] = ref_sr_round(src[i], r);
+    }
+}
+
+/* ------------------------------------------------------------- AdamW --- */
+
+typedef struct {
+    float beta1, beta2;   /* as given                                            */
+    float omb1, omb2;     /* 1 - beta, formed in double, rounded once            */
+    float rbc1, rbc2;     /* 1/(1 - beta^t), formed in double, rounded once      */
+    float lr, eps;        /* as given                                            */
+    float lw;             /* lr * weight_decay, formed in double, rounded once   */
+    float clip;           /* gradient scale c (1 when clipping is off)           */
+} ref_scalars_t;
+
+static double pow_uint(double base, uint32_t e)
+{
+    /* beta^t by binary exponentiation in double */
+    double result = 1.0;
+    while (e) {
+        if (e & 1u) result *= base;
+        base *= base;
+        e >>= 1;
+    }
+    return result;
+}
+
+/* Scalars of one step (Algorithm 1, lines 5-8 and 10).  `norm` is the global
+ * gradient norm or NULL for no clipping; with clipping the gradient is scaled
+ * by c = min(1, max_norm/(norm + 1e-6)) in binary32 arithmetic. */
+void ref_adamw_scalars(float lr, float beta1, float beta2, float eps, float weight_decay,
+                       uint32_t step, const float* norm, float max_norm, ref_scalars_t* s)
+{
+    s->beta1 = beta1; s->beta2 = beta2;
+    s->omb1 = (float)(1.0 - (double)beta1);
+    s->omb2 = (float)(1.0 - (double)beta2);
+    s->rbc1 = (float)(1.0 / (1.0 - pow_uint((double)beta1, step)));
+    s->rbc2 = (float)(1.0 / (1.0 - pow_uint((double)beta2, step)));
+    s->lr = lr; s->eps = eps;
+    s->lw = (float)((double)lr * (double)weight_decay);
+    s->clip = 1.0f;
+    if (norm) {
+        float denom = *norm + 1e-6f;
+        float c = max_norm / denom;
+        if (c > 1.0f) c = 1.0f;
+        s->clip = c;
+    }
+}
+
+/* One element of Algorithm 1 lines 5-10 before the write-back rounding:
+ * returns the unrounded new parameter y and the unrounded moments m1, v1. */
+static void adamw_element(const ref_scalars_t* s, float p, float g, float m, float v,
+                          float* y_out, float* m1_out, float* v1_out)
+{
+    float g1 = g * s->clip;
+    /* line 5: m <- beta1 m + (1 - beta1) g */
+    float t1 = s->beta1 * m;
+    float t2 = s->omb1 * g1;
+    float m1 = t1 + t2;
+    /* line 6: v <- beta2 v + (1 - beta2) g^2 */
+    float gg = g1 * g1;
+    float t3 = s->beta2 * v;
+    float t4 = s->omb2 * gg;
+    float v1 = t3 + t4;
+    /* lines 7-8: bias corrections (as multiplications by host reciprocals) */
+    float mh = m1 * s->rbc1;
+    float vh = v1 * s->rbc2;
+    /* line 10: x - (alpha mhat/(sqrt(vhat) + eps) + alpha lambda x) */
+    float d = sqrtf(vh) + s->eps;
+    float u = mh / d;
+    float a = s->lr * u;
+    float b = s->lw * p;
+    float sum = a + b;
+    float y = p - sum;
+    *y_out = y; *m1_out = m1; *v1_out = v1;
+}
+
+/* Unrounded results (for the FP32-intermediate checks). m, v are BF16 bit
+ * patterns unless REF_FLAG_FP32_MOMENTS. */
+void ref_adamw_unrounded(const uint16_t* p, const uint16_t* g, const void* m, const void* v,
+                         uint64_t numel, const ref_scalars_t* s, uint32_t flags,
+                         float* y, float* m1, float* v1)
+{
+    const int fp32m = (flags & REF_FLAG_FP32_MOMENTS) != 0;
+    for (uint64_t i = 0; i < numel; ++i) {
+        float mi = fp32m ? ((const float*)m)[i] : bf16_bits_to_float(((const uint16_t*)m)[i]);
+        float vi = fp32m ? ((const float*)v)[i] : bf16_bits_to_float(((const uint16_t*)v)[i]);
+        adamw_element(s, bf16_bits_to_float(p[i]), bf16_bits_to_float(g[i]), mi, vi,
+                      &y[i], &m1[i], &v1[i]);
+    }
+}
+
+/* One tensor of one step, in place over p, m, v.
+ *   BF16 moments (default): p, m, v all written back with SR, streams 0, 1, 2;
+ *   REF_FLAG_FP32_MOMENTS : m, v are binary32 and stored unrounded, SR on p only;
+ *   REF_FLAG_RNE_MOMENTS  : BF16 moments written back with round-to-nearest-even
+ *                           (the paper's own setting: SR on line 10 only).
+ * Element i of the tensor uses RNG index elem_offset + i. */
+void ref_sr_adamw_tensor(uint16_t* p, const uint16_t* g, void* m, void* v,
+                         uint64_t numel, uint32_t tensor_id, uint64_t elem_offset,
+                         const ref_scalars_t* s, uint32_t step, uint64_t seed,
+                         uint32_t flags, int nthreads)
+{
+    const int fp32m = (flags & REF_FLAG_FP32_MOMENTS) != 0;
+    const int rnem  = (flags & REF_FLAG_RNE_MOMENTS) != 0;
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+    #pragma omp parallel for schedule(static)
+    for (int64_t ii = 0; ii < (int64_t)numel; ++ii) {
+        uint64_t i = (uint64_t)ii;
+        uint64_t gi = elem_offset + i;
+        float pi = bf16_bits_to_float(p[i]);
+        float gr = bf16_bits_to_float(g[i]);
+        float mi = fp32m ? ((float*)m)[i] : bf16_bits_to_float(((uint16_t*)m)[i]);
+        float vi = fp32m ? ((float*)v)[i] : bf16_bits_to_float(((uint16_t*)v)[i]);
+        float y, m1, v1;
+        adamw_element(s, pi, gr, mi, vi, &y, &m1, &v1);
+        p[i] = ref_sr_round(y, ref_r16(seed, step, tensor_id, gi, 0u));
+        if (fp32m) {
+            ((float*)m)[i] = m1;
+            ((float*)v)[i] = v1;
+        } else if (rnem) {
+            ((uint16_t*)m)[i] = ref_rne_round(m1);
+            ((uint16_t*)v)[i] = ref_rne_round(v1);
+        } else {
+            ((uint16_t*)m)[i] = ref_sr_round(m1, ref_r16(seed, step, tensor_id, gi, 1u));
+            ((uint16_t*)v)[i] = ref_sr_round(v1, ref_r16(seed, step, tensor_id, gi, 2u));
+        }
+    }
+}
+
+/* ------------------------------------------------------ gradient norm --- */
+
+/* Global L2 norm over a list of BF16 gradient tensors: sum of squares in
+ * long double with Neumaier compensation, tensors in list order, elements in
+ * index order; norm = (float)sqrt((double)S). */
+float ref_grad_global_norm(const uint16_t* const* g, const uint64_t* numel, uint32_t n_tensors)
+{
+    long double sum = 0.0L, comp = 0.0L;
+    for (uint32_t t = 0; t < n_tensors; ++t) {
+        const uint16_t* gt = g[t];
+        for (uint64_t i = 0; i < numel[t]; ++i) {
+            long double x = (long double)bf16_bits_to_float(gt[i]);
+            long double term = x * x;                 /* exact: 16-bit product */
+            long double s2 = sum + term;
+            if (fabsl(sum) >= fabsl(term)) comp += (sum - s2) + term;
+            else                           comp += (term - s2) + sum;
+            sum = s2;
+        }
+    }
+    double S = (double)(sum + comp);
+    return (float)sqrt(S);
+}
+
+int ref_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
