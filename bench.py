@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the SR-AdamW update path on one MI355X.
+
+A step is one pass of the whole hot path over a resident synthetic parameter set: (global
+gradient norm when the config clips) + the fused SR-AdamW update of every tensor.  Default
+workload: the 6.7B flat-buffer configuration (BF16 p/g/m/v, SR on all three write-backs,
+moments warm-started by 100 seeded steps).  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--warm-steps N]
+                  [--cpu-seconds S] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published peak
+
+
+def algorithmic_bytes_per_element(cfg) -> int:
+    # BF16 p,g,m,v read + p,m,v written = 14; FP32 moments: 2+2+4+4 read, 2+4+4 written = 22;
+    # the norm pass reads the gradients once more.
+    b = 22 if cfg.fp32_moments else 14
+    return b + (2 if cfg.clip is not None else 0)
+
+
+def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds):
+    """Time the CPU oracle (as it stands) on a bounded window of the same workload and check the
+    GPU against it on that window.  `state` holds flat device tensors p, g, m, v (first tensor)."""
+    import numpy as np
+    from oracle import ref
+    p, g, m, v = state
+    flags = ref.FLAG_FP32_MOMENTS if cfg.fp32_moments else 0
+    threads = min(ref.max_threads(), os.cpu_count() or 1)
+
+    def window(lo, n):
+        def cp(t):
+            s = t[lo:lo + n]
+            return W.bf16_to_u16_numpy(s) if s.dtype == torch.bfloat16 else s.cpu().numpy().copy()
+        return dict(p=cp(p), g=cp(g), m=cp(m), v=cp(v), tensor_id=0, elem_offset=lo)
+
+    # calibrate on 2^21 elements, then size the sample for about `seconds` of CPU work
+    n0 = min(1 << 21, p.numel())
+    w0 = window(0, n0)
+    t0 = time.perf_counter()
+    ref.sr_adamw_step([w0], cfg.hyper, step_no, seed, flags, nthreads=threads)
+    rate0 = n0 / (time.perf_counter() - t0)
+    n = int(min(p.numel(), max(n0, rate0 * seconds), 1 << 30))
+    n -= n % 8
+    lo = ((p.numel() - n) // 2) & ~7                      # a window from the middle of the buffer
+    w = window(lo, n)
+    t0 = time.perf_counter()
+    ref.sr_adamw_step([w], cfg.hyper, step_no, seed, flags, nthreads=threads)
+    dt = time.perf_counter() - t0
+    return dict(value=n / dt, unit="params/s", cores=threads, kind="oracle",
+                sample=f"{n} contiguous elements from the middle of the buffer, one step "
+                       f"(step {step_no}), {dt:.1f} s"), (lo, n, w)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5)
+    ap.add_argument("--warm-steps", type=int, default=None, help="seeded steps that warm the moments")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                 "run it with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2502_20566_amd import binding as B
+    from paper_2502_20566_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the update path has no CPU fallback")
+    B.lib()                                               # fail loudly if the library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = W.config(args.config)
+    warm = cfg.warm_steps if args.warm_steps is None else args.warm_steps
+
+    params = W.make_params(cfg.shapes, dev, W.data_seed(cfg.index, 0), cfg.param_std)
+    ms, vs = W.make_moments(cfg.shapes, dev, cfg.fp32_moments)
+    grads = [torch.empty_like(p) for p in params]
+    tl = B.TensorList(params, grads, ms, vs, cfg.fp32_moments)
+    flags = B.SR_FLAG_FP32_MOMENTS if cfg.fp32_moments else 0
+    norm = torch.zeros(1, dtype=torch.float32, device=dev)
+    ws = torch.empty(max(tl.workspace_bytes(), 256), dtype=torch.uint8, device=dev)
+    numel = tl.total_numel
+
+    def one_step(t):
+        if cfg.clip is not None:
+            B.grad_global_norm(tl, norm, ws)
+            B.sr_adamw_step(tl, cfg.hyper, t, cfg.seed, flags, norm, cfg.clip)
+        else:
+            B.sr_adamw_step(tl, cfg.hyper, t, cfg.seed, flags)
+
+    # warm-start of the moments: seeded steps with fresh gradients (a seed per step)
+    t = 0
+    for _ in range(warm):
+        t += 1
+        W.fill_grads(grads, W.data_seed(cfg.index, t), cfg.grad_std, cfg.outlier_frac, cfg.outlier_std)
+        one_step(t)
+    t += 1
+    W.fill_grads(grads, W.data_seed(cfg.index, t), cfg.grad_std, cfg.outlier_frac, cfg.outlier_std)
+    torch.cuda.synchronize()
+
+    # CPU oracle on a bounded window (needs the state BEFORE the step it reproduces)
+    cpu = None
+    check = None
+    if not args.no_cpu_baseline:
+        cpu, check = cpu_baseline(W, B, torch, cfg, (params[0], grads[0], ms[0], vs[0]), t, cfg.seed,
+                                  args.cpu_seconds)
+        if cfg.clip is not None:
+            cpu["sample"] += " (oracle timed without the clip scale)"
+
+    # the step the oracle reproduced, then the parity check of that window
+    parity = "not checked"
+    if check is not None and cfg.clip is None:
+        one_step(t)
+        torch.cuda.synchronize()
+        lo, n, w = check
+        got_p = W.bf16_to_u16_numpy(params[0][lo:lo + n])
+        bad = int((got_p != w["p"]).sum())
+        if not cfg.fp32_moments:
+            bad += int((W.bf16_to_u16_numpy(ms[0][lo:lo + n]) != w["m"]).sum())
+            bad += int((W.bf16_to_u16_numpy(vs[0][lo:lo + n]) != w["v"]).sum())
+        parity = "bit-exact" if bad == 0 else f"{bad} mismatches"
+        del got_p
+        t += 1
+
+    for _ in range(args.warmup):
+        one_step(t)
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps, inputs resident, HIP events on the launch stream per step
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        ev0[i].record()
+        one_step(t + i)
+        ev1[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    ms_per_step = wall * 1e3 / args.steps
+    dev_ms = [a.elapsed_time(b) for a, b in zip(ev0, ev1)]
+    dev_avg_ms = float(np.mean(dev_ms))
+
+    bpe = algorithmic_bytes_per_element(cfg)
+    value = numel * args.steps / wall
+    achieved = bpe * numel / (dev_avg_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_config{cfg.index}.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("hbm_bytes_per_step")
+
+    out = {
+        "metric": "sr_adamw_params_updated_per_sec",
+        "value": value,
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"config {cfg.index}: {cfg.name}", "numel": numel, "tensors": len(params),
+                   "moments": "fp32" if cfg.fp32_moments else "bf16", "clip": cfg.clip,
+                   "warm_steps": warm, "bytes_per_element": bpe},
+        "hbm_GBps": bpe * numel / (ms_per_step * 1e-3) / 1e9,
+        "pct_of_hbm_peak": 100.0 * bpe * numel / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "kernel": "adamw_kernel", "avg_launch_ms": dev_avg_ms,
+                     "min_launch_ms": float(np.min(dev_ms))},
+        "cpu_baseline": cpu,
+        "parity_sample": parity,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

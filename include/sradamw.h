@@ -1,0 +1,142 @@
+/*
+ * sradamw.h -- C ABI of the MI355X (gfx950) SR-AdamW update library.
+ *
+ * The library implements the optimizer step of BF16+SR training
+ * (arXiv 2502.20566, Algorithm 1, Section 3): an AdamW update computed in
+ * binary32 over BF16 parameters, gradients and moments whose write-backs to
+ * BF16 are stochastically rounded (Eq.(2), Section 2.1), with the random bits
+ * taken from a stateless counter generator so that every data-parallel
+ * replica rounds identically (Algorithm 1, lines 9 and 11).
+ *
+ * Conventions for every entry point
+ *   - Pointers named d_* and every pointer inside sr_tensor_t are DEVICE
+ *     pointers owned by the caller; all other pointers are HOST pointers that
+ *     are read before the call returns and may be freed right after it.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on it: no host synchronisation, no device
+ *     allocation, no hidden state.  Results are ordered by the stream.
+ *   - Return value: SR_OK (0) or a negative SR_ERR_* code.  Arguments are
+ *     validated on the host first; on an argument error nothing is enqueued.
+ *   - Outputs depend only on the input bits, the hyper-parameters, `step`,
+ *     `seed`, `tensor_id` and the element's index elem_offset + i -- never on
+ *     launch geometry, list order, how a list is split over calls, pointer
+ *     alignment or the rank that runs it.
+ */
+#ifndef SRADAMW_H
+#define SRADAMW_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SR_OK              0
+#define SR_ERR_NULL      (-1)  /* a required pointer is NULL                              */
+#define SR_ERR_ARG       (-2)  /* step == 0, beta outside [0,1), eps < 0, non-finite
+                                  hyper-parameter, max_norm <= 0 with clipping, unknown
+                                  flag, non-zero reserved field, index range overflow     */
+#define SR_ERR_WORKSPACE (-3)  /* workspace NULL, misaligned (8 bytes) or too small       */
+#define SR_ERR_ALIGN     (-4)  /* a BF16 pointer not 2-byte / an FP32 pointer not 4-byte
+                                  aligned (16-byte misalignment is NOT an error: such
+                                  tensors take the element-wise path, same results)       */
+#define SR_ERR_HIP       (-5)  /* a launch failed; see sr_last_hip_error()                */
+
+/* flags of sr_adamw_step */
+#define SR_FLAG_FP32_MOMENTS 1u /* m, v are binary32 and stored unrounded; SR on p only
+                                   (the full-precision optimizer states of Section 3, last
+                                   paragraph, and of the ablation in Appendix C)           */
+#define SR_FLAG_RNE_MOMENTS  2u /* BF16 m, v written back with round-to-nearest-even,
+                                   Eq.(1): the paper's own setting, SR on line 10 only.
+                                   Ignored together with SR_FLAG_FP32_MOMENTS.             */
+
+/* One tensor of the multi-tensor list. */
+typedef struct sr_tensor {
+    void*       p;           /* BF16 [numel], in/out: parameters x_t                      */
+    const void* g;           /* BF16 [numel], in    : reduced gradient (Alg.1 line 4)     */
+    void*       m;           /* BF16 or binary32 [numel], in/out: first moment            */
+    void*       v;           /* same type as m, in/out: second moment                     */
+    uint64_t    numel;       /* may be 0 (tensor skipped); may exceed 2^32                */
+    uint64_t    elem_offset; /* index of element 0 in the RNG counter; 0 for a whole
+                                tensor, the shard's start for a slice of a larger one     */
+    uint32_t    tensor_id;   /* RNG counter word; keep it stable across steps and ranks   */
+    uint32_t    reserved;    /* must be 0                                                 */
+} sr_tensor_t;
+
+/* Hyper-parameters of Algorithm 1: alpha_t, beta_1, beta_2, epsilon, lambda. */
+typedef struct sr_hyper {
+    float lr, beta1, beta2, eps, weight_decay;
+} sr_hyper_t;
+
+/*
+ * Stochastic rounding of binary32 to BF16, Eq.(2) of Section 2.1, in the
+ * add-uniform-noise-then-truncate form of Section 3:
+ *   d_dst[i] = Q_SR(d_src[i]) with the 16 random bits of element i taken from
+ *   Philox4x32-10(counter = (i>>3 low word, 3<<29 | i>>3 high bits, tensor_id,
+ *   step), key = seed) -- slice i&7 of the 128 output bits.
+ * A value v between adjacent BF16 values lo < hi becomes hi with probability
+ * (v-lo)/(hi-lo); BF16 values are unchanged; a magnitude above the largest
+ * BF16 may round to infinity; infinities pass; NaN becomes a quiet NaN with
+ * the same sign.  d_src: binary32 [n] (4-byte aligned), d_dst: BF16 [n]
+ * (2-byte aligned), both device, must not overlap.  n == 0 is a no-op.
+ */
+int sr_cast_f32_bf16(const float* d_src, void* d_dst, uint64_t n,
+                     uint64_t seed, uint32_t step, uint32_t tensor_id, void* stream);
+
+/*
+ * Global L2 norm of the gradients of a tensor list (the quantity a gradient
+ * clip needs; the paper's training frameworks clip, Algorithm 1 does not
+ * mention it): *d_norm_out = (float) sqrt( sum over all tensors and elements
+ * of g^2 ), squares and sum in binary64, two passes (per-workgroup partial
+ * sums into the workspace, then one workgroup), fixed summation tree, no
+ * atomics.  Uses only .g and .numel of each entry (host array of n_tensors
+ * entries).  d_norm_out: device scalar, 4-byte aligned.  d_workspace: device
+ * scratch of at least sr_workspace_bytes(n_tensors, total numel) bytes,
+ * 8-byte aligned; its contents after the call are unspecified.  An empty
+ * list writes 0.
+ */
+int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_norm_out,
+                     void* d_workspace, uint64_t workspace_bytes, void* stream);
+
+/*
+ * One AdamW step with stochastically rounded write-backs over a tensor list
+ * (Algorithm 1, lines 5-10; eps outside the root).  Per element, in binary32
+ * with one rounding per operation and no fused multiply-add:
+ *   g' = g c                       c = 1, or min(1, max_norm/(norm + 1e-6)) when clipping
+ *   m' = beta1 m + (1-beta1) g'    v' = beta2 v + (1-beta2) g'^2
+ *   u  = (m' rbc1) / (sqrt(v' rbc2) + eps)          rbc_i = 1/(1 - beta_i^step)
+ *   y  = p - (lr u + (lr weight_decay) p)
+ *   p <- Q_SR(y), m <- Q_SR(m'), v <- Q_SR(v')      (RNG streams 0, 1, 2 of element i:
+ *        counter word 1 = stream<<29 | high bits of (elem_offset+i)>>3)
+ * 1-beta, rbc and lr*weight_decay are formed in binary64 on the host and
+ * rounded once.  The update uses the unrounded m', v'.  p, m, v are updated
+ * in place; distinct tensors must not overlap.
+ *   tensors      host array of n_tensors entries (n_tensors == 0: no-op)
+ *   step         t >= 1
+ *   flags        SR_FLAG_* bits
+ *   d_grad_norm  NULL = no clipping; else device scalar holding the global
+ *                gradient norm (as written by grad_global_norm on the same
+ *                stream); gradients are scaled in registers, d g is not rewritten
+ *   max_norm     > 0, used only with d_grad_norm
+ */
+int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper_t* hyper,
+                  uint32_t step, uint64_t seed, uint32_t flags,
+                  const float* d_grad_norm, float max_norm, void* stream);
+
+/* Bytes of device workspace grad_global_norm needs for a list of n_tensors
+ * tensors with total_numel elements in all (an upper bound, multiple of 256). */
+uint64_t sr_workspace_bytes(uint32_t n_tensors, uint64_t total_numel);
+
+/* Static description of an SR_ERR_* code. */
+const char* sr_strerror(int code);
+
+/* hipError_t value of the most recent SR_ERR_HIP on the calling thread (0 if none). */
+int sr_last_hip_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int sr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SRADAMW_H */

@@ -1,0 +1,172 @@
+"""ctypes binding of libsradamw.so (C ABI in include/sradamw.h).
+
+Argument marshalling only: every step of the update runs in the HIP kernels.
+PyTorch supplies device memory and streams.  There is no CPU fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch  # imported before the library so that one HIP runtime serves both
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsradamw.so")
+
+SR_OK = 0
+SR_ERR_NULL, SR_ERR_ARG, SR_ERR_WORKSPACE, SR_ERR_ALIGN, SR_ERR_HIP = -1, -2, -3, -4, -5
+SR_FLAG_FP32_MOMENTS = 1
+SR_FLAG_RNE_MOMENTS = 2
+
+EXPORTS = ("sr_cast_f32_bf16", "grad_global_norm", "sr_adamw_step", "sr_workspace_bytes",
+           "sr_strerror", "sr_last_hip_error", "sr_version")
+
+
+class SrTensor(C.Structure):
+    _fields_ = [("p", C.c_void_p), ("g", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
+                ("numel", C.c_uint64), ("elem_offset", C.c_uint64),
+                ("tensor_id", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class SrHyper(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("weight_decay", C.c_float)]
+
+
+class SrError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().sr_strerror(code).decode()
+        if code == SR_ERR_HIP:
+            msg += f" [hipError {lib().sr_last_hip_error()}]"
+        super().__init__(f"{where}: {msg} ({code})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -m paper_2502_20566_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -c 'import __graft_entry__ as g; g.build()'`; "
+                               "there is no CPU fallback")
+        L = C.CDLL(LIB_PATH)
+        L.sr_cast_f32_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint32,
+                                       C.c_uint32, C.c_void_p]
+        L.sr_cast_f32_bf16.restype = C.c_int
+        L.grad_global_norm.argtypes = [C.POINTER(SrTensor), C.c_uint32, C.c_void_p, C.c_void_p,
+                                       C.c_uint64, C.c_void_p]
+        L.grad_global_norm.restype = C.c_int
+        L.sr_adamw_step.argtypes = [C.POINTER(SrTensor), C.c_uint32, C.POINTER(SrHyper), C.c_uint32,
+                                    C.c_uint64, C.c_uint32, C.c_void_p, C.c_float, C.c_void_p]
+        L.sr_adamw_step.restype = C.c_int
+        L.sr_workspace_bytes.argtypes = [C.c_uint32, C.c_uint64]
+        L.sr_workspace_bytes.restype = C.c_uint64
+        L.sr_strerror.argtypes = [C.c_int]
+        L.sr_strerror.restype = C.c_char_p
+        L.sr_last_hip_error.argtypes = []
+        L.sr_last_hip_error.restype = C.c_int
+        L.sr_version.argtypes = []
+        L.sr_version.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _check_dev(t: torch.Tensor, dtype, name: str):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+
+
+class TensorList:
+    """A marshalled multi-tensor list (host array of sr_tensor_t).  Build once, reuse every
+    step; it keeps the torch tensors alive."""
+
+    def __init__(self, params: Sequence[torch.Tensor], grads: Sequence[torch.Tensor],
+                 ms: Sequence[torch.Tensor], vs: Sequence[torch.Tensor], fp32_moments: bool = False,
+                 tensor_ids: Optional[Sequence[int]] = None,
+                 elem_offsets: Optional[Sequence[int]] = None):
+        n = len(params)
+        if not (len(grads) == len(ms) == len(vs) == n):
+            raise ValueError("params, grads, ms, vs must have the same length")
+        mdt = torch.float32 if fp32_moments else torch.bfloat16
+        self.fp32_moments = fp32_moments
+        self.n = n
+        self.array = (SrTensor * max(n, 1))()
+        self.keep = (list(params), list(grads), list(ms), list(vs))
+        self.total_numel = 0
+        for i in range(n):
+            p, g, m, v = params[i], grads[i], ms[i], vs[i]
+            _check_dev(p, torch.bfloat16, f"params[{i}]")
+            _check_dev(g, torch.bfloat16, f"grads[{i}]")
+            _check_dev(m, mdt, f"ms[{i}]")
+            _check_dev(v, mdt, f"vs[{i}]")
+            if not (p.numel() == g.numel() == m.numel() == v.numel()):
+                raise ValueError(f"tensor {i}: p, g, m, v differ in size")
+            e = self.array[i]
+            e.p, e.g, e.m, e.v = p.data_ptr(), g.data_ptr(), m.data_ptr(), v.data_ptr()
+            e.numel = p.numel()
+            e.elem_offset = 0 if elem_offsets is None else int(elem_offsets[i])
+            e.tensor_id = i if tensor_ids is None else int(tensor_ids[i])
+            e.reserved = 0
+            self.total_numel += p.numel()
+
+    def workspace_bytes(self) -> int:
+        return int(lib().sr_workspace_bytes(self.n, self.total_numel))
+
+
+def sr_workspace_bytes(n_tensors: int, total_numel: int) -> int:
+    return int(lib().sr_workspace_bytes(n_tensors, total_numel))
+
+
+def sr_cast_f32_bf16(src: torch.Tensor, dst: torch.Tensor, seed: int, step: int, tensor_id: int = 0,
+                     stream=None) -> None:
+    _check_dev(src, torch.float32, "src")
+    _check_dev(dst, torch.bfloat16, "dst")
+    if src.numel() != dst.numel():
+        raise ValueError("src and dst differ in size")
+    rc = lib().sr_cast_f32_bf16(src.data_ptr(), dst.data_ptr(), src.numel(), seed, step, tensor_id,
+                                _stream_handle(stream))
+    if rc != SR_OK:
+        raise SrError(rc, "sr_cast_f32_bf16")
+
+
+def grad_global_norm(tl: TensorList, norm_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    """norm_out: float32 device tensor with one element; workspace: device tensor (any dtype) of
+    at least tl.workspace_bytes() bytes."""
+    _check_dev(norm_out, torch.float32, "norm_out")
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous device tensor")
+    rc = lib().grad_global_norm(tl.array, tl.n, norm_out.data_ptr(), workspace.data_ptr(),
+                                workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if rc != SR_OK:
+        raise SrError(rc, "grad_global_norm")
+
+
+def sr_adamw_step(tl: TensorList, hyper: dict, step: int, seed: int, flags: int = 0,
+                  grad_norm: Optional[torch.Tensor] = None, max_norm: float = 0.0, stream=None) -> None:
+    """hyper = dict(lr, beta1, beta2, eps, weight_decay).  grad_norm: float32 device scalar from
+    grad_global_norm, or None for no clipping."""
+    if bool(flags & SR_FLAG_FP32_MOMENTS) != tl.fp32_moments:
+        raise ValueError("SR_FLAG_FP32_MOMENTS does not match the moment dtype of the list")
+    h = SrHyper(hyper["lr"], hyper["beta1"], hyper["beta2"], hyper["eps"], hyper["weight_decay"])
+    nptr = None
+    if grad_norm is not None:
+        _check_dev(grad_norm, torch.float32, "grad_norm")
+        nptr = grad_norm.data_ptr()
+    rc = lib().sr_adamw_step(tl.array, tl.n, C.byref(h), step, seed, flags, nptr, max_norm,
+                             _stream_handle(stream))
+    if rc != SR_OK:
+        raise SrError(rc, "sr_adamw_step")

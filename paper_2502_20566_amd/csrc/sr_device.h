@@ -1,0 +1,94 @@
+// Device primitives for gfx950: BF16 pair pack/unpack, the Philox4x32-10 counter generator in
+// registers, and stochastic rounding of binary32 to BF16 (arXiv 2502.20566, Eq.(2), in the
+// dithering form of Section 3: add 16 uniform bits below the kept mantissa, drop the low half).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sr {
+
+// RNG output streams (top three bits of counter word 1).
+enum : uint32_t { STREAM_P = 0, STREAM_M = 1, STREAM_V = 2, STREAM_CAST = 3 };
+
+struct u32x4 { uint32_t w[4]; };
+
+// Philox4x32, 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11).  A round replaces
+// (c0,c1,c2,c3) by (hi(B*c2)^c1^k0, lo(B*c2), hi(A*c0)^c3^k1, lo(A*c0)) and then steps the key by
+// the two Weyl increments.  The 32x32->64 products compile to one v_mad_u64_u32 each; key words
+// are wave-uniform and stay in scalar registers.
+__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1)
+{
+    constexpr uint32_t A = 0xD2511F53u, B = 0xCD9E8D57u;
+    constexpr uint32_t KA = 0x9E3779B9u, KB = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t pa = (uint64_t)A * c0;
+        const uint64_t pb = (uint64_t)B * c2;
+        const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)pb;
+        c3 = (uint32_t)pa;
+        c0 = n0;
+        c2 = n2;
+        k0 += KA;
+        k1 += KB;
+    }
+    return u32x4{{c0, c1, c2, c3}};
+}
+
+// The 128 random bits of 8-element block `gblk` (= element index >> 3) of one output stream.
+__device__ __forceinline__ u32x4 block_bits(uint64_t gblk, uint32_t stream, uint32_t tensor_id,
+                                            uint32_t step, uint32_t seed_lo, uint32_t seed_hi)
+{
+    return philox4x32_10((uint32_t)gblk, (stream << 29) | (uint32_t)(gblk >> 32), tensor_id, step,
+                         seed_lo, seed_hi);
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xFFFF0000u); }
+
+// (t1 & 0xFFFF0000) | (t0 >> 16) as one byte permute: bytes 3,2 of t1 above bytes 3,2 of t0.
+__device__ __forceinline__ uint32_t pack_high_halves(uint32_t t0, uint32_t t1)
+{
+    return __builtin_amdgcn_perm(t1, t0, 0x07060302u);
+}
+
+// Two stochastic roundings at once.  `bits` holds the draws of both elements (low half for y0,
+// high half for y1).  bits(y) + r16 carries into the kept half exactly when the 16 dropped
+// mantissa bits f satisfy f + r16 >= 65536, i.e. with probability f/65536 = (|y|-lo)/(hi-lo):
+// binary32 encodings of one sign are ordered like their magnitudes, BF16 values are the
+// encodings with f = 0, so the carry moves the kept half from lo to the next BF16 value hi --
+// across binade edges, in the subnormal range, and from the largest finite value to infinity.
+// Infinities have f = 0 and never move.  NaNs must not take this path (the carry could turn a
+// NaN encoding into an infinity or flip the sign): see sr_pair_nan_safe.
+__device__ __forceinline__ uint32_t sr_pair(float y0, float y1, uint32_t bits)
+{
+    const uint32_t t0 = __float_as_uint(y0) + (bits & 0xFFFFu);
+    const uint32_t t1 = __float_as_uint(y1) + (bits >> 16);
+    return pack_high_halves(t0, t1);
+}
+
+// Same with the NaN rule: a NaN input gives the quiet NaN with the same sign and upper payload.
+__device__ __forceinline__ uint32_t sr_pair_nan_safe(float y0, float y1, uint32_t bits)
+{
+    uint32_t t0 = __float_as_uint(y0) + (bits & 0xFFFFu);
+    uint32_t t1 = __float_as_uint(y1) + (bits >> 16);
+    if (y0 != y0) t0 = __float_as_uint(y0) | 0x00400000u;
+    if (y1 != y1) t1 = __float_as_uint(y1) | 0x00400000u;
+    return pack_high_halves(t0, t1);
+}
+
+// Round-to-nearest-even of binary32 to BF16 (Eq.(1)), two at once; NaN as above.
+__device__ __forceinline__ uint32_t rne_one(float y)
+{
+    const uint32_t b = __float_as_uint(y);
+    const uint32_t t = b + 0x7FFFu + ((b >> 16) & 1u);
+    return (y != y) ? (b | 0x00400000u) : t;
+}
+__device__ __forceinline__ uint32_t rne_pair(float y0, float y1)
+{
+    return pack_high_halves(rne_one(y0), rne_one(y1));
+}
+
+}  // namespace sr

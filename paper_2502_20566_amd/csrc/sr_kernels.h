@@ -1,0 +1,426 @@
+// Kernels of the SR-AdamW update path for gfx950 (wave64): the fused multi-tensor update
+// (Algorithm 1 lines 5-10 of arXiv 2502.20566 with stochastically rounded write-backs), the
+// standalone SR cast, and the two-pass global gradient norm.
+//
+// Work decomposition shared by all kernels: a tensor is cut into 8-element blocks aligned to the
+// RNG counter (block index = element index >> 3, so one Philox call serves one 128-bit BF16
+// vector); a lane owns whole blocks; a workgroup owns one chunk of consecutive blocks of ONE
+// tensor; the chunk -> tensor map is a small prefix table that travels in the kernel argument
+// segment (scalar loads, no device-side table to upload or keep alive).
+#pragma once
+#include "sr_device.h"
+
+namespace sr {
+
+constexpr int kThreads = 256;          // 4 waves per workgroup
+constexpr int kMaxBatch = 64;          // tensors per update launch (argument segment <= 4 KiB)
+constexpr int kNormMaxBatch = 160;     // tensors per norm launch
+constexpr int kNormIters = 16;         // blocks per lane in the norm's first pass
+constexpr int kNormChunkElems = kThreads * 8 * kNormIters;
+constexpr int kFinalThreads = 1024;
+
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+enum : uint32_t { DESC_VEC = 1u };     // all pointers 16-byte aligned and elem_offset % 8 == 0
+
+struct TensorDesc {
+    uint16_t* p;
+    const uint16_t* g;
+    void* m;
+    void* v;
+    uint64_t numel;
+    uint64_t elem_offset;
+    uint32_t tensor_id;
+    uint32_t flags;
+};
+
+struct StepScalars {
+    float beta1, beta2, omb1, omb2, rbc1, rbc2, lr, eps, lw, max_norm;
+    const float* d_norm;
+    uint32_t seed_lo, seed_hi, step, n_tensors;
+};
+
+struct AdamwBatch {
+    StepScalars s;
+    uint32_t chunk_start[kMaxBatch + 1];   // first chunk of tensor i; [n_tensors] = total
+    uint32_t pad_;
+    TensorDesc t[kMaxBatch];
+};
+static_assert(sizeof(AdamwBatch) <= 4096, "kernel argument segment");
+
+struct NormDesc { const uint16_t* g; uint64_t numel; };
+struct NormBatch {
+    uint32_t n_tensors;
+    uint32_t partial_base;                 // index of this launch's first partial sum
+    uint32_t chunk_start[kNormMaxBatch + 1];
+    uint32_t pad_;
+    NormDesc t[kNormMaxBatch];
+};
+static_assert(sizeof(NormBatch) <= 4096, "kernel argument segment");
+
+// ------------------------------------------------------------------ memory access helpers
+
+template <bool NT>
+__device__ __forceinline__ v4u load_v4(const void* ptr)
+{
+    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const v4u*>(ptr));
+    return *reinterpret_cast<const v4u*>(ptr);
+}
+template <bool NT>
+__device__ __forceinline__ void store_v4(void* ptr, v4u x)
+{
+    if (NT) __builtin_nontemporal_store(x, reinterpret_cast<v4u*>(ptr));
+    else *reinterpret_cast<v4u*>(ptr) = x;
+}
+
+// Eight BF16 values starting at element l0 of `base` as four packed pairs.  `full`: the block lies
+// inside the tensor and is 16-byte aligned.  Otherwise element-wise, with zeros outside [0, numel).
+template <bool NT>
+__device__ __forceinline__ v4u load8_bf16(const uint16_t* base, int64_t l0, uint64_t numel, bool full)
+{
+    if (full) return load_v4<NT>(base + l0);
+    uint32_t h[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t l = l0 + j;
+        h[j] = (l >= 0 && (uint64_t)l < numel) ? (uint32_t)base[l] : 0u;
+    }
+    v4u r;
+    r.x = h[0] | (h[1] << 16); r.y = h[2] | (h[3] << 16);
+    r.z = h[4] | (h[5] << 16); r.w = h[6] | (h[7] << 16);
+    return r;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store8_bf16(uint16_t* base, int64_t l0, uint64_t numel, bool full, v4u x)
+{
+    if (full) { store_v4<NT>(base + l0, x); return; }
+    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t l = l0 + j;
+        if (l >= 0 && (uint64_t)l < numel) base[l] = (uint16_t)(w[j >> 1] >> (16 * (j & 1)));
+    }
+}
+
+template <bool NT>
+__device__ __forceinline__ void load8_f32(const float* base, int64_t l0, uint64_t numel, bool full, float (&out)[8])
+{
+    if (full) {
+        const v4u a = load_v4<NT>(base + l0), b = load_v4<NT>(base + l0 + 4);
+        out[0] = __uint_as_float(a.x); out[1] = __uint_as_float(a.y);
+        out[2] = __uint_as_float(a.z); out[3] = __uint_as_float(a.w);
+        out[4] = __uint_as_float(b.x); out[5] = __uint_as_float(b.y);
+        out[6] = __uint_as_float(b.z); out[7] = __uint_as_float(b.w);
+        return;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t l = l0 + j;
+        out[j] = (l >= 0 && (uint64_t)l < numel) ? base[l] : 0.0f;
+    }
+}
+
+template <bool NT>
+__device__ __forceinline__ void store8_f32(float* base, int64_t l0, uint64_t numel, bool full, const float (&x)[8])
+{
+    if (full) {
+        v4u a, b;
+        a.x = __float_as_uint(x[0]); a.y = __float_as_uint(x[1]);
+        a.z = __float_as_uint(x[2]); a.w = __float_as_uint(x[3]);
+        b.x = __float_as_uint(x[4]); b.y = __float_as_uint(x[5]);
+        b.z = __float_as_uint(x[6]); b.w = __float_as_uint(x[7]);
+        store_v4<NT>(base + l0, a);
+        store_v4<NT>(base + l0 + 4, b);
+        return;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t l = l0 + j;
+        if (l >= 0 && (uint64_t)l < numel) base[l] = x[j];
+    }
+}
+
+__device__ __forceinline__ void unpack8(v4u x, float (&out)[8])
+{
+    out[0] = bf16_lo(x.x); out[1] = bf16_hi(x.x);
+    out[2] = bf16_lo(x.y); out[3] = bf16_hi(x.y);
+    out[4] = bf16_lo(x.z); out[5] = bf16_hi(x.z);
+    out[6] = bf16_lo(x.w); out[7] = bf16_hi(x.w);
+}
+
+// Eight stochastic roundings with the 128 bits of one Philox block.
+template <bool NAN_SAFE>
+__device__ __forceinline__ v4u sr8(const float (&y)[8], const u32x4& r)
+{
+    v4u o;
+    if (NAN_SAFE) {
+        o.x = sr_pair_nan_safe(y[0], y[1], r.w[0]); o.y = sr_pair_nan_safe(y[2], y[3], r.w[1]);
+        o.z = sr_pair_nan_safe(y[4], y[5], r.w[2]); o.w = sr_pair_nan_safe(y[6], y[7], r.w[3]);
+    } else {
+        o.x = sr_pair(y[0], y[1], r.w[0]); o.y = sr_pair(y[2], y[3], r.w[1]);
+        o.z = sr_pair(y[4], y[5], r.w[2]); o.w = sr_pair(y[6], y[7], r.w[3]);
+    }
+    return o;
+}
+
+__device__ __forceinline__ bool any_nan8(const float (&y)[8])
+{
+    bool n = false;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) n |= (y[j] != y[j]);
+    return n;
+}
+
+// Largest i in [0, n) with start[i] <= chunk (start[] ascending, start[0] = 0).  Wave-uniform.
+__device__ __forceinline__ uint32_t find_tensor(const uint32_t* start, uint32_t n, uint32_t chunk)
+{
+    uint32_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (start[mid] <= chunk) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// ---------------------------------------------------------------------------- fused update
+
+// Registers of one 8-element block on its way through the update.
+template <bool FP32M>
+struct BlockRegs {
+    v4u p, g, mq, vq;          // packed BF16 pairs (mq, vq unused with FP32M)
+    float mf[8], vf[8];        // binary32 moments (FP32M only)
+};
+
+// Algorithm 1 lines 5-10 on the eight elements of one block, then the write-back roundings.
+// In: R as loaded.  Out: R.p (and R.mq, R.vq, or R.mf, R.vf) hold what is to be stored.
+template <bool FP32M, bool RNEM, bool CLIP>
+__device__ __forceinline__ void update_block(BlockRegs<FP32M>& R, const StepScalars& S, float c,
+                                             uint64_t gblk, uint32_t tensor_id)
+{
+    float p[8], g[8], m[8], v[8], y[8];
+    unpack8(R.p, p);
+    unpack8(R.g, g);
+    if (FP32M) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { m[j] = R.mf[j]; v[j] = R.vf[j]; }
+    } else {
+        unpack8(R.mq, m);
+        unpack8(R.vq, v);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        // one rounding per operation, in this order (no contraction: built with -ffp-contract=off)
+        const float g1 = CLIP ? g[j] * c : g[j];
+        const float t1 = S.beta1 * m[j];
+        const float t2 = S.omb1 * g1;
+        const float m1 = t1 + t2;
+        const float gg = g1 * g1;
+        const float t3 = S.beta2 * v[j];
+        const float t4 = S.omb2 * gg;
+        const float v1 = t3 + t4;
+        const float mh = m1 * S.rbc1;
+        const float vh = v1 * S.rbc2;
+        const float d = __builtin_sqrtf(vh) + S.eps;
+        const float q = mh / d;
+        const float a = S.lr * q;
+        const float w = S.lw * p[j];
+        const float s = a + w;
+        y[j] = p[j] - s;
+        m[j] = m1;
+        v[j] = v1;
+    }
+    // A NaN in m' or v' always makes y NaN, so one test covers all three outputs.
+    const bool nan = any_nan8(y);
+    const u32x4 rp = block_bits(gblk, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
+    R.p = nan ? sr8<true>(y, rp) : sr8<false>(y, rp);
+    if (FP32M) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { R.mf[j] = m[j]; R.vf[j] = v[j]; }
+    } else if (RNEM) {
+        R.mq.x = rne_pair(m[0], m[1]); R.mq.y = rne_pair(m[2], m[3]);
+        R.mq.z = rne_pair(m[4], m[5]); R.mq.w = rne_pair(m[6], m[7]);
+        R.vq.x = rne_pair(v[0], v[1]); R.vq.y = rne_pair(v[2], v[3]);
+        R.vq.z = rne_pair(v[4], v[5]); R.vq.w = rne_pair(v[6], v[7]);
+    } else {
+        const u32x4 rm = block_bits(gblk, STREAM_M, tensor_id, S.step, S.seed_lo, S.seed_hi);
+        const u32x4 rv = block_bits(gblk, STREAM_V, tensor_id, S.step, S.seed_lo, S.seed_hi);
+        R.mq = nan ? sr8<true>(m, rm) : sr8<false>(m, rm);
+        R.vq = nan ? sr8<true>(v, rv) : sr8<false>(v, rv);
+    }
+}
+
+template <bool FP32M, bool NT>
+__device__ __forceinline__ void load_block(BlockRegs<FP32M>& R, const TensorDesc& T, int64_t l0, bool full)
+{
+    R.p = load8_bf16<NT>(T.p, l0, T.numel, full);
+    R.g = load8_bf16<NT>(T.g, l0, T.numel, full);
+    if (FP32M) {
+        load8_f32<NT>(static_cast<const float*>(T.m), l0, T.numel, full, R.mf);
+        load8_f32<NT>(static_cast<const float*>(T.v), l0, T.numel, full, R.vf);
+    } else {
+        R.mq = load8_bf16<NT>(static_cast<const uint16_t*>(T.m), l0, T.numel, full);
+        R.vq = load8_bf16<NT>(static_cast<const uint16_t*>(T.v), l0, T.numel, full);
+    }
+}
+
+template <bool FP32M, bool NT>
+__device__ __forceinline__ void store_block(const BlockRegs<FP32M>& R, const TensorDesc& T, int64_t l0, bool full)
+{
+    store8_bf16<NT>(T.p, l0, T.numel, full, R.p);
+    if (FP32M) {
+        store8_f32<NT>(static_cast<float*>(T.m), l0, T.numel, full, R.mf);
+        store8_f32<NT>(static_cast<float*>(T.v), l0, T.numel, full, R.vf);
+    } else {
+        store8_bf16<NT>(static_cast<uint16_t*>(T.m), l0, T.numel, full, R.mq);
+        store8_bf16<NT>(static_cast<uint16_t*>(T.v), l0, T.numel, full, R.vq);
+    }
+}
+
+// FP32M: binary32 moments stored unrounded (SR on p only).  RNEM: BF16 moments rounded to nearest.
+// CLIP: scale gradients by min(1, max_norm/(norm + 1e-6)).  U: blocks per lane.  NT: nontemporal
+// loads and stores.
+template <bool FP32M, bool RNEM, bool CLIP, int U, bool NT>
+__global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
+{
+    const uint32_t chunk = blockIdx.x;
+    const uint32_t ti = find_tensor(B.chunk_start, B.s.n_tensors, chunk);
+    const TensorDesc& T = B.t[ti];
+    const uint64_t numel = T.numel;
+    const uint64_t G0 = T.elem_offset;
+    const uint64_t gblk0 = G0 >> 3;
+    const uint64_t nblk = ((G0 + numel - 1) >> 3) - gblk0 + 1;     // host guarantees numel > 0
+    const bool vec = (T.flags & DESC_VEC) != 0;
+    const uint32_t tensor_id = T.tensor_id;
+    const StepScalars& S = B.s;
+
+    float c = 1.0f;
+    if (CLIP) {
+        c = S.max_norm / (*S.d_norm + 1e-6f);
+        if (c > 1.0f) c = 1.0f;
+    }
+
+    const uint64_t bfirst = (uint64_t)(chunk - B.chunk_start[ti]) * (uint64_t)(kThreads * U) + threadIdx.x;
+    const uint64_t blast = bfirst + (uint64_t)(U - 1) * kThreads;
+
+    // Fast path: every block of this lane is a whole, 16-byte aligned vector inside the tensor
+    // (with DESC_VEC, elem_offset is a multiple of 8, so block b starts at element 8 b).
+    if (vec && ((blast << 3) + 8 <= numel)) {
+        BlockRegs<FP32M> R[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            load_block<FP32M, NT>(R[u], T, (int64_t)((bfirst + (uint64_t)u * kThreads) << 3), true);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t b = bfirst + (uint64_t)u * kThreads;
+            update_block<FP32M, RNEM, CLIP>(R[u], S, c, gblk0 + b, tensor_id);
+            store_block<FP32M, NT>(R[u], T, (int64_t)(b << 3), true);
+        }
+        return;
+    }
+
+    // General path: tensor tails, misaligned pointers, element offsets that are not multiples
+    // of 8.  Same arithmetic and the same counter blocks, element-wise memory access.
+    for (int u = 0; u < U; ++u) {
+        const uint64_t b = bfirst + (uint64_t)u * kThreads;
+        if (b >= nblk) break;
+        const int64_t l0 = (int64_t)((gblk0 + b) << 3) - (int64_t)G0;
+        const bool full = vec && ((uint64_t)l0 + 8 <= numel);
+        BlockRegs<FP32M> R;
+        load_block<FP32M, false>(R, T, l0, full);
+        update_block<FP32M, RNEM, CLIP>(R, S, c, gblk0 + b, tensor_id);
+        store_block<FP32M, false>(R, T, l0, full);
+    }
+}
+
+// ----------------------------------------------------------------------- standalone SR cast
+
+template <int U, bool NT>
+__global__ __launch_bounds__(kThreads) void cast_kernel(const float* __restrict__ src,
+                                                        uint16_t* __restrict__ dst, uint64_t n,
+                                                        uint32_t seed_lo, uint32_t seed_hi,
+                                                        uint32_t step, uint32_t tensor_id, uint32_t vec)
+{
+    const uint64_t nblk = (n + 7) >> 3;
+    const uint64_t bfirst = (uint64_t)blockIdx.x * (uint64_t)(kThreads * U) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t b = bfirst + (uint64_t)u * kThreads;
+        if (b >= nblk) continue;
+        const int64_t l0 = (int64_t)(b << 3);
+        const bool full = vec && ((uint64_t)l0 + 8 <= n);
+        float y[8];
+        load8_f32<NT>(src, l0, n, full, y);
+        const u32x4 r = block_bits(b, STREAM_CAST, tensor_id, step, seed_lo, seed_hi);
+        const v4u o = any_nan8(y) ? sr8<true>(y, r) : sr8<false>(y, r);
+        store8_bf16<NT>(dst, l0, n, full, o);
+    }
+}
+
+// ------------------------------------------------------------------------- gradient norm
+
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
+    return x;                                   // lane 0 holds the wave's sum
+}
+
+// Pass 1: one binary64 partial sum of squares per chunk.  g is widened to binary64 before
+// squaring, so tiny or huge gradients neither underflow nor overflow, and each square is exact.
+__global__ __launch_bounds__(kThreads) void sumsq_partial_kernel(const NormBatch B, double* __restrict__ partials)
+{
+    __shared__ double wsum[kThreads / 64];
+    const uint32_t chunk = blockIdx.x;
+    const uint32_t ti = find_tensor(B.chunk_start, B.n_tensors, chunk);
+    const uint16_t* g = B.t[ti].g;
+    const uint64_t numel = B.t[ti].numel;
+    const bool vec = (reinterpret_cast<uintptr_t>(g) & 15u) == 0;
+    const uint64_t nblk = (numel + 7) >> 3;
+    const uint64_t bfirst = (uint64_t)(chunk - B.chunk_start[ti]) * (uint64_t)(kThreads * kNormIters) + threadIdx.x;
+
+    double acc = 0.0;
+#pragma unroll 4
+    for (int it = 0; it < kNormIters; ++it) {
+        const uint64_t b = bfirst + (uint64_t)it * kThreads;
+        if (b >= nblk) break;
+        const int64_t l0 = (int64_t)(b << 3);
+        const bool full = vec && ((uint64_t)l0 + 8 <= numel);
+        float x[8];
+        unpack8(load8_bf16<false>(g, l0, numel, full), x);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const double xd = (double)x[j];
+            acc = __builtin_fma(xd, xd, acc);   // product exact (8-bit significands): one rounding
+        }
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double s = wsum[0];
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) s += wsum[w];
+        partials[B.partial_base + chunk] = s;
+    }
+}
+
+// Pass 2: one workgroup adds the partial sums in a fixed order and writes (float) sqrt(S).
+__global__ __launch_bounds__(kFinalThreads) void sumsq_final_kernel(const double* __restrict__ partials,
+                                                                   uint32_t n_partials, float* __restrict__ out)
+{
+    __shared__ double wsum[kFinalThreads / 64];
+    double acc = 0.0;
+    for (uint32_t i = threadIdx.x; i < n_partials; i += kFinalThreads) acc += partials[i];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double s = 0.0;
+#pragma unroll
+        for (int w = 0; w < kFinalThreads / 64; ++w) s += wsum[w];
+        *out = (float)__builtin_sqrt(s);
+    }
+}
+
+}  // namespace sr

@@ -1,0 +1,249 @@
+// Host side of the C ABI declared in include/sradamw.h: argument validation, the scalars of one
+// step (formed in binary64, rounded once), packing of the multi-tensor chunk tables into kernel
+// argument batches, and the launches on the caller's stream.  No device memory is allocated and
+// nothing synchronises with the host.
+#include "../../include/sradamw.h"
+#include "sr_kernels.h"
+
+#include <cmath>
+#include <cstring>
+
+namespace {
+
+using namespace sr;
+
+thread_local int g_last_hip_error = 0;
+
+inline int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return SR_ERR_HIP;
+}
+
+inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// beta^t by repeated squaring in binary64.
+double pow_uint(double base, uint32_t e)
+{
+    double r = 1.0;
+    for (; e; e >>= 1) {
+        if (e & 1u) r *= base;
+        base *= base;
+    }
+    return r;
+}
+
+// Tunables of the fused update: blocks per lane and nontemporal access.
+constexpr int kU = 2;
+constexpr bool kNT = true;
+constexpr uint64_t kBlocksPerChunk = (uint64_t)kThreads * kU;
+constexpr int kCastU = 2;
+constexpr uint32_t kMaxGrid = 0x7FFFFFFFu;
+
+template <bool FP32M, bool RNEM, bool CLIP>
+hipError_t launch_adamw(const AdamwBatch& batch, uint32_t n_chunks, hipStream_t stream)
+{
+    hipLaunchKernelGGL((adamw_kernel<FP32M, RNEM, CLIP, kU, kNT>), dim3(n_chunks), dim3(kThreads), 0, stream, batch);
+    return hipGetLastError();
+}
+
+hipError_t launch_adamw_variant(bool fp32m, bool rnem, bool clip, const AdamwBatch& b, uint32_t n, hipStream_t s)
+{
+    if (fp32m) return clip ? launch_adamw<true, false, true>(b, n, s) : launch_adamw<true, false, false>(b, n, s);
+    if (rnem)  return clip ? launch_adamw<false, true, true>(b, n, s) : launch_adamw<false, true, false>(b, n, s);
+    return clip ? launch_adamw<false, false, true>(b, n, s) : launch_adamw<false, false, false>(b, n, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int sr_version(void) { return 100; }
+
+int sr_last_hip_error(void) { return g_last_hip_error; }
+
+const char* sr_strerror(int code)
+{
+    switch (code) {
+        case SR_OK:            return "ok";
+        case SR_ERR_NULL:      return "a required pointer is NULL";
+        case SR_ERR_ARG:       return "invalid argument (step, hyper-parameter, flag, reserved field or index range)";
+        case SR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case SR_ERR_ALIGN:     return "tensor pointer not aligned to its element size";
+        case SR_ERR_HIP:       return "HIP launch failed (see sr_last_hip_error)";
+        default:               return "unknown error code";
+    }
+}
+
+uint64_t sr_workspace_bytes(uint32_t n_tensors, uint64_t total_numel)
+{
+    const uint64_t chunks = total_numel / (uint64_t)kNormChunkElems + (uint64_t)n_tensors + 1;
+    return (chunks * sizeof(double) + 255u) & ~(uint64_t)255u;
+}
+
+int sr_cast_f32_bf16(const float* d_src, void* d_dst, uint64_t n, uint64_t seed, uint32_t step,
+                     uint32_t tensor_id, void* stream)
+{
+    if (n == 0) return SR_OK;
+    if (!d_src || !d_dst) return SR_ERR_NULL;
+    if (!aligned(d_src, 4) || !aligned(d_dst, 2)) return SR_ERR_ALIGN;
+    const uint64_t nblk = (n + 7) >> 3;
+    const uint64_t per_wg = (uint64_t)kThreads * kCastU;
+    const uint64_t grid = (nblk + per_wg - 1) / per_wg;
+    if (grid > kMaxGrid) return SR_ERR_ARG;
+    const uint32_t vec = (aligned(d_src, 16) && aligned(d_dst, 16)) ? 1u : 0u;
+    hipLaunchKernelGGL((cast_kernel<kCastU, kNT>), dim3((uint32_t)grid), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), d_src, static_cast<uint16_t*>(d_dst), n,
+                       (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), step, tensor_id, vec);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SR_OK : hip_fail(e);
+}
+
+int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_norm_out,
+                     void* d_workspace, uint64_t workspace_bytes, void* stream)
+{
+    if (!d_norm_out) return SR_ERR_NULL;
+    if (n_tensors && !tensors) return SR_ERR_NULL;
+    if (!aligned(d_norm_out, 4)) return SR_ERR_ALIGN;
+    uint64_t total_chunks = 0;
+    for (uint32_t i = 0; i < n_tensors; ++i) {
+        if (tensors[i].numel == 0) continue;
+        if (!tensors[i].g) return SR_ERR_NULL;
+        if (!aligned(tensors[i].g, 2)) return SR_ERR_ALIGN;
+        if (tensors[i].numel > (uint64_t)kMaxGrid * kNormChunkElems) return SR_ERR_ARG;
+        total_chunks += (tensors[i].numel + kNormChunkElems - 1) / kNormChunkElems;
+    }
+    if (total_chunks > 0xFFFFFFFFull) return SR_ERR_ARG;
+    if (total_chunks) {
+        if (!d_workspace || !aligned(d_workspace, 8)) return SR_ERR_WORKSPACE;
+        if (workspace_bytes < total_chunks * sizeof(double)) return SR_ERR_WORKSPACE;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    double* partials = static_cast<double*>(d_workspace);
+
+    NormBatch batch;
+    std::memset(&batch, 0, sizeof(batch));
+    uint32_t nb = 0, chunks_in_batch = 0, base = 0;
+    auto flush = [&]() -> hipError_t {
+        if (nb == 0) return hipSuccess;
+        batch.n_tensors = nb;
+        batch.partial_base = base;
+        batch.chunk_start[nb] = chunks_in_batch;
+        hipLaunchKernelGGL(sumsq_partial_kernel, dim3(chunks_in_batch), dim3(kThreads), 0, s, batch, partials);
+        base += chunks_in_batch;
+        nb = 0; chunks_in_batch = 0;
+        return hipGetLastError();
+    };
+    for (uint32_t i = 0; i < n_tensors; ++i) {
+        const uint64_t numel = tensors[i].numel;
+        if (numel == 0) continue;
+        const uint32_t nch = (uint32_t)((numel + kNormChunkElems - 1) / kNormChunkElems);
+        if (nb == kNormMaxBatch || (uint64_t)chunks_in_batch + nch > kMaxGrid) {
+            const hipError_t e = flush();
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        batch.t[nb].g = static_cast<const uint16_t*>(tensors[i].g);
+        batch.t[nb].numel = numel;
+        batch.chunk_start[nb] = chunks_in_batch;
+        chunks_in_batch += nch;
+        ++nb;
+    }
+    hipError_t e = flush();
+    if (e != hipSuccess) return hip_fail(e);
+    hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(kFinalThreads), 0, s, partials, (uint32_t)total_chunks, d_norm_out);
+    e = hipGetLastError();
+    return e == hipSuccess ? SR_OK : hip_fail(e);
+}
+
+int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper_t* hyper,
+                  uint32_t step, uint64_t seed, uint32_t flags, const float* d_grad_norm,
+                  float max_norm, void* stream)
+{
+    if (!hyper) return SR_ERR_NULL;
+    if (n_tensors && !tensors) return SR_ERR_NULL;
+    if (step == 0) return SR_ERR_ARG;
+    if (flags & ~(SR_FLAG_FP32_MOMENTS | SR_FLAG_RNE_MOMENTS)) return SR_ERR_ARG;
+    const sr_hyper_t h = *hyper;
+    if (!std::isfinite(h.lr) || !std::isfinite(h.eps) || !std::isfinite(h.weight_decay) ||
+        !std::isfinite(h.beta1) || !std::isfinite(h.beta2)) return SR_ERR_ARG;
+    if (!(h.beta1 >= 0.0f && h.beta1 < 1.0f) || !(h.beta2 >= 0.0f && h.beta2 < 1.0f)) return SR_ERR_ARG;
+    if (h.eps < 0.0f) return SR_ERR_ARG;
+    const bool clip = d_grad_norm != nullptr;
+    if (clip) {
+        if (!std::isfinite(max_norm) || !(max_norm > 0.0f)) return SR_ERR_ARG;
+        if (!aligned(d_grad_norm, 4)) return SR_ERR_ALIGN;
+    }
+    const bool fp32m = (flags & SR_FLAG_FP32_MOMENTS) != 0;
+    const bool rnem = !fp32m && (flags & SR_FLAG_RNE_MOMENTS) != 0;
+    const uintptr_t moment_align = fp32m ? 4 : 2;
+
+    // Validate the whole list before anything is enqueued.
+    for (uint32_t i = 0; i < n_tensors; ++i) {
+        const sr_tensor_t& t = tensors[i];
+        if (t.reserved != 0) return SR_ERR_ARG;
+        if (t.numel == 0) continue;
+        if (!t.p || !t.g || !t.m || !t.v) return SR_ERR_NULL;
+        if (!aligned(t.p, 2) || !aligned(t.g, 2) || !aligned(t.m, moment_align) || !aligned(t.v, moment_align))
+            return SR_ERR_ALIGN;
+        if (t.elem_offset + t.numel < t.numel) return SR_ERR_ARG;          // index range wraps
+        const uint64_t nblk = ((t.elem_offset + t.numel - 1) >> 3) - (t.elem_offset >> 3) + 1;
+        if ((nblk + kBlocksPerChunk - 1) / kBlocksPerChunk > kMaxGrid) return SR_ERR_ARG;
+    }
+
+    AdamwBatch batch;
+    std::memset(&batch, 0, sizeof(batch));
+    StepScalars& S = batch.s;
+    S.beta1 = h.beta1;
+    S.beta2 = h.beta2;
+    S.omb1 = (float)(1.0 - (double)h.beta1);
+    S.omb2 = (float)(1.0 - (double)h.beta2);
+    S.rbc1 = (float)(1.0 / (1.0 - pow_uint((double)h.beta1, step)));
+    S.rbc2 = (float)(1.0 / (1.0 - pow_uint((double)h.beta2, step)));
+    S.lr = h.lr;
+    S.eps = h.eps;
+    S.lw = (float)((double)h.lr * (double)h.weight_decay);
+    S.max_norm = max_norm;
+    S.d_norm = d_grad_norm;
+    S.seed_lo = (uint32_t)(seed & 0xFFFFFFFFu);
+    S.seed_hi = (uint32_t)(seed >> 32);
+    S.step = step;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t nb = 0, chunks_in_batch = 0;
+    auto flush = [&]() -> hipError_t {
+        if (nb == 0) return hipSuccess;
+        S.n_tensors = nb;
+        batch.chunk_start[nb] = chunks_in_batch;
+        const hipError_t e = launch_adamw_variant(fp32m, rnem, clip, batch, chunks_in_batch, s);
+        nb = 0; chunks_in_batch = 0;
+        return e;
+    };
+    for (uint32_t i = 0; i < n_tensors; ++i) {
+        const sr_tensor_t& t = tensors[i];
+        if (t.numel == 0) continue;
+        const uint64_t nblk = ((t.elem_offset + t.numel - 1) >> 3) - (t.elem_offset >> 3) + 1;
+        const uint32_t nch = (uint32_t)((nblk + kBlocksPerChunk - 1) / kBlocksPerChunk);
+        if (nb == kMaxBatch || (uint64_t)chunks_in_batch + nch > kMaxGrid) {
+            const hipError_t e = flush();
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        TensorDesc& d = batch.t[nb];
+        d.p = static_cast<uint16_t*>(t.p);
+        d.g = static_cast<const uint16_t*>(t.g);
+        d.m = t.m;
+        d.v = t.v;
+        d.numel = t.numel;
+        d.elem_offset = t.elem_offset;
+        d.tensor_id = t.tensor_id;
+        const bool vec = (t.elem_offset & 7u) == 0 && aligned(t.p, 16) && aligned(t.g, 16) &&
+                         aligned(t.m, 16) && aligned(t.v, 16);
+        d.flags = vec ? DESC_VEC : 0u;
+        batch.chunk_start[nb] = chunks_in_batch;
+        chunks_in_batch += nch;
+        ++nb;
+    }
+    const hipError_t e = flush();
+    return e == hipSuccess ? SR_OK : hip_fail(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,137 @@
+"""The C-ABI library loads, exports what include/sradamw.h declares, and rejects bad arguments
+on the host before anything is launched (no compute call is made here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+import torch
+
+from paper_2502_20566_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HAVE_GPU = torch.cuda.is_available()
+_keep = []
+
+
+def buf(nbytes: int, misalign: int = 0) -> int:
+    """An address for a tensor argument.  On a GPU machine it is real device memory (so that a
+    validation bug could not turn into a wild access); without a GPU nothing can be launched
+    and a made-up aligned address serves."""
+    if HAVE_GPU:
+        t = torch.zeros(nbytes + 64, dtype=torch.uint8, device="cuda")
+        _keep.append(t)
+        return t.data_ptr() + misalign
+    return 0x7F0000001000 + 0x100000 * len(_keep) + misalign
+
+
+def tensor(numel=64, **kw):
+    t = B.SrTensor()
+    t.p, t.g, t.m, t.v = buf(2 * numel), buf(2 * numel), buf(4 * numel), buf(4 * numel)
+    t.numel, t.elem_offset, t.tensor_id, t.reserved = numel, 0, 0, 0
+    for k, v in kw.items():
+        setattr(t, k, v)
+    return t
+
+
+def step(tensors, hyper=None, step=1, seed=0, flags=0, norm=None, max_norm=0.0):
+    arr = (B.SrTensor * max(len(tensors), 1))(*tensors)
+    h = B.SrHyper(*(hyper or (1e-3, 0.9, 0.95, 1e-8, 0.1)))
+    return B.lib().sr_adamw_step(arr, len(tensors), C.byref(h), step, seed, flags, norm, max_norm, None)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "sradamw.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(\w+)\s*\([^;{]*\)\s*;", header))
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name)
+    assert L.sr_version() >= 100
+    assert C.sizeof(B.SrTensor) == 56 and C.sizeof(B.SrHyper) == 20
+
+
+def test_strerror_covers_all_codes():
+    L = B.lib()
+    msgs = {c: L.sr_strerror(c).decode() for c in (0, -1, -2, -3, -4, -5, -99)}
+    assert len(set(msgs.values())) == 7 and msgs[0] == "ok"
+
+
+def test_workspace_bytes_bounds_the_partials():
+    L = B.lib()
+    chunk = 256 * 8 * 16
+    for n_t, numel in [(0, 0), (1, 1), (3, chunk), (388, 2651591680), (1, 6658465792)]:
+        w = L.sr_workspace_bytes(n_t, numel)
+        assert w % 256 == 0 and w >= 8 * (numel // chunk + n_t)
+
+
+def test_adamw_argument_errors():
+    t = tensor()
+    assert step([t], step=0) == B.SR_ERR_ARG
+    assert step([t], hyper=(1e-3, 1.0, 0.95, 1e-8, 0.1)) == B.SR_ERR_ARG
+    assert step([t], hyper=(1e-3, 0.9, -0.1, 1e-8, 0.1)) == B.SR_ERR_ARG
+    assert step([t], hyper=(1e-3, 0.9, 0.95, -1e-8, 0.1)) == B.SR_ERR_ARG
+    assert step([t], hyper=(float("nan"), 0.9, 0.95, 1e-8, 0.1)) == B.SR_ERR_ARG
+    assert step([t], hyper=(1e-3, 0.9, 0.95, float("inf"), 0.1)) == B.SR_ERR_ARG
+    assert step([t], hyper=(1e-3, 0.9, 0.95, 1e-8, float("nan"))) == B.SR_ERR_ARG
+    assert step([t], flags=4) == B.SR_ERR_ARG
+    assert step([tensor(reserved=1)]) == B.SR_ERR_ARG
+    assert step([tensor(elem_offset=2 ** 64 - 8)]) == B.SR_ERR_ARG
+    nrm = buf(4)
+    assert step([t], norm=nrm, max_norm=0.0) == B.SR_ERR_ARG
+    assert step([t], norm=nrm, max_norm=float("nan")) == B.SR_ERR_ARG
+    assert step([t], norm=nrm + 2, max_norm=1.0) == B.SR_ERR_ALIGN
+
+
+def test_adamw_null_and_alignment_errors():
+    assert step([tensor(p=None)]) == B.SR_ERR_NULL
+    assert step([tensor(v=None)]) == B.SR_ERR_NULL
+    t = tensor()
+    assert step([tensor(g=t.g + 1)]) == B.SR_ERR_ALIGN
+    assert step([tensor(m=t.m + 2)], flags=B.SR_FLAG_FP32_MOMENTS) == B.SR_ERR_ALIGN
+    L = B.lib()
+    h = B.SrHyper(1e-3, 0.9, 0.95, 1e-8, 0.1)
+    assert L.sr_adamw_step(None, 1, C.byref(h), 1, 0, 0, None, 0.0, None) == B.SR_ERR_NULL
+    arr = (B.SrTensor * 1)(t)
+    assert L.sr_adamw_step(arr, 1, None, 1, 0, 0, None, 0.0, None) == B.SR_ERR_NULL
+    # a bad entry anywhere in the list rejects the whole call
+    assert step([tensor(), tensor(), tensor(g=None)]) == B.SR_ERR_NULL
+
+
+def test_adamw_empty_inputs_are_no_ops():
+    assert step([]) == B.SR_OK
+    assert step([tensor(numel=0, p=None, g=None, m=None, v=None)]) == B.SR_OK
+
+
+def test_cast_argument_errors():
+    L = B.lib()
+    assert L.sr_cast_f32_bf16(None, None, 0, 0, 1, 0, None) == B.SR_OK
+    assert L.sr_cast_f32_bf16(None, buf(16), 8, 0, 1, 0, None) == B.SR_ERR_NULL
+    assert L.sr_cast_f32_bf16(buf(32), None, 8, 0, 1, 0, None) == B.SR_ERR_NULL
+    assert L.sr_cast_f32_bf16(buf(32, 2), buf(16), 4, 0, 1, 0, None) == B.SR_ERR_ALIGN
+    assert L.sr_cast_f32_bf16(buf(32), buf(16, 1), 4, 0, 1, 0, None) == B.SR_ERR_ALIGN
+
+
+def test_norm_argument_errors():
+    L = B.lib()
+    t = tensor(numel=100000)
+    arr = (B.SrTensor * 1)(t)
+    out, ws = buf(4), buf(4096)
+    assert L.grad_global_norm(arr, 1, None, ws, 4096, None) == B.SR_ERR_NULL
+    assert L.grad_global_norm(None, 1, out, ws, 4096, None) == B.SR_ERR_NULL
+    assert L.grad_global_norm(arr, 1, out, None, 4096, None) == B.SR_ERR_WORKSPACE
+    assert L.grad_global_norm(arr, 1, out, ws, 8, None) == B.SR_ERR_WORKSPACE       # 4 chunks need 32 bytes
+    assert L.grad_global_norm(arr, 1, out, ws + 4, 4096, None) == B.SR_ERR_WORKSPACE
+    assert L.grad_global_norm(arr, 1, out + 2, ws, 4096, None) == B.SR_ERR_ALIGN
+    arr[0].g = None
+    assert L.grad_global_norm(arr, 1, out, ws, 4096, None) == B.SR_ERR_NULL
+
+
+def test_binding_rejects_host_tensors_and_wrong_dtypes():
+    x = torch.zeros(8, dtype=torch.float32)
+    y = torch.zeros(8, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        B.sr_cast_f32_bf16(x, y, 0, 1)
+    with pytest.raises(ValueError):
+        B.TensorList([y], [y], [y], [y])

@@ -1,0 +1,427 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Bar: BF16 outputs and SR decisions bit-exact (the tolerance of at
+most 1 BF16 ulp on at most 1e-6 of the elements is written in `assert_bf16_parity`; expected
+residue is zero), FP32 moments and the norm within relative 1e-6 (expected: identical bits).
+NaNs produced by arithmetic are compared as NaNs (IEEE 754 leaves their sign and payload open);
+NaNs that are merely cast keep specified bits and are compared exactly.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2502_20566_amd import binding as B
+from paper_2502_20566_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+# ------------------------------------------------------------------ helpers
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        return W.bf16_to_u16_numpy(t)
+    return t.detach().cpu().numpy().copy()
+
+
+def bf16_dev(bits: np.ndarray) -> torch.Tensor:
+    return W.u16_numpy_to_bf16(np.ascontiguousarray(bits, dtype=np.uint16), DEV)
+
+
+def is_nan16(a):
+    return ((a & 0x7F80) == 0x7F80) & ((a & 0x007F) != 0)
+
+
+def assert_bf16_parity(got: np.ndarray, want: np.ndarray, what: str, exact_nan: bool = False):
+    assert got.shape == want.shape
+    if not exact_nan:
+        gn, wn = is_nan16(got), is_nan16(want)
+        assert bool(np.all(gn == wn)), f"{what}: NaN positions differ"
+        got, want = np.where(gn, 0, got), np.where(wn, 0, want)
+    diff = got != want
+    n_bad = int(diff.sum())
+    if n_bad == 0:
+        return
+    # tolerance of the contract: <= 1 BF16 ulp on <= 1e-6 of the elements
+    ulp = np.abs(got[diff].astype(np.int32) - want[diff].astype(np.int32))
+    first = np.flatnonzero(diff)[:5]
+    assert n_bad <= 1e-6 * got.size and int(ulp.max()) <= 1, \
+        f"{what}: {n_bad} of {got.size} differ (max {int(ulp.max())} ulp), first at {first}"
+
+
+def assert_f32_parity(got: np.ndarray, want: np.ndarray, what: str):
+    both_nan = np.isnan(got) & np.isnan(want)
+    ok = both_nan | (got == want) | (np.abs(got - want) <= 1e-6 * np.abs(want))
+    assert bool(np.all(ok)), f"{what}: {int((~ok).sum())} of {got.size} outside rel 1e-6"
+
+
+class Pair:
+    """The same optimizer state on the device (library) and on the host (oracle)."""
+
+    def __init__(self, params, ms, vs, fp32_moments, tensor_ids=None, elem_offsets=None):
+        self.fp32 = fp32_moments
+        self.p, self.m, self.v = params, ms, vs
+        self.g = [torch.empty_like(p) for p in params]
+        self.ids = list(range(len(params))) if tensor_ids is None else list(tensor_ids)
+        self.offs = [0] * len(params) if elem_offsets is None else list(elem_offsets)
+        self.tl = B.TensorList(self.p, self.g, self.m, self.v, fp32_moments, self.ids, self.offs)
+        self.host = [dict(p=to_np(p), m=to_np(m), v=to_np(v), tensor_id=i, elem_offset=o)
+                     for p, m, v, i, o in zip(params, ms, vs, self.ids, self.offs)]
+        self.norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+        self.ws = torch.empty(max(self.tl.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
+
+    def step(self, hyper, t, seed, clip=None, flags=0, check_norm=True):
+        for h, g in zip(self.host, self.g):
+            h["g"] = to_np(g)
+        if self.fp32:
+            flags |= B.SR_FLAG_FP32_MOMENTS
+        norm_val = None
+        if clip is not None:
+            B.grad_global_norm(self.tl, self.norm, self.ws)
+            norm_val = float(self.norm.item())
+            if check_norm:
+                want = ref.grad_global_norm([h["g"] for h in self.host])
+                assert norm_val == want or abs(norm_val - want) <= 1e-6 * want, (norm_val, want)
+            B.sr_adamw_step(self.tl, hyper, t, seed, flags, self.norm, clip)
+        else:
+            B.sr_adamw_step(self.tl, hyper, t, seed, flags)
+        torch.cuda.synchronize()
+        # the oracle takes the same FP32 norm bits the device used
+        ref.sr_adamw_step(self.host, hyper, t, seed, flags, norm=norm_val,
+                          max_norm=0.0 if clip is None else clip)
+
+    def compare(self, what):
+        for i, h in enumerate(self.host):
+            assert_bf16_parity(to_np(self.p[i]), h["p"], f"{what} p[{i}]")
+            if self.fp32:
+                assert_f32_parity(to_np(self.m[i]), h["m"], f"{what} m[{i}]")
+                assert_f32_parity(to_np(self.v[i]), h["v"], f"{what} v[{i}]")
+            else:
+                assert_bf16_parity(to_np(self.m[i]), h["m"], f"{what} m[{i}]")
+                assert_bf16_parity(to_np(self.v[i]), h["v"], f"{what} v[{i}]")
+
+
+def make_pair(cfg: W.Config, shapes=None):
+    shapes = cfg.shapes if shapes is None else shapes
+    params = W.make_params(shapes, DEV, W.data_seed(cfg.index, 0), cfg.param_std)
+    ms, vs = W.make_moments(shapes, DEV, cfg.fp32_moments)
+    return Pair(params, ms, vs, cfg.fp32_moments)
+
+
+def run_config(cfg: W.Config, shapes, steps):
+    pair = make_pair(cfg, shapes)
+    for t in range(1, steps + 1):
+        W.fill_grads(pair.g, W.data_seed(cfg.index, t), cfg.grad_std, cfg.outlier_frac, cfg.outlier_std)
+        pair.step(cfg.hyper, t, cfg.seed, clip=cfg.clip)
+        pair.compare(f"{cfg.name} step {t}")
+    return pair
+
+
+# ------------------------------------------------------------- sr_cast_f32_bf16
+
+def gpu_cast(x: torch.Tensor, seed, step, tid):
+    out = torch.empty(x.numel(), dtype=torch.bfloat16, device=DEV)
+    B.sr_cast_f32_bf16(x, out, seed, step, tid)
+    torch.cuda.synchronize()
+    return to_np(out)
+
+
+def test_cast_config1_workload_bit_exact():
+    x = W.make_cast_input(1 << 20, DEV, W.data_seed(1, 0))
+    got = gpu_cast(x, 0, 1, 0)
+    want = ref.sr_cast_f32_bf16(x.cpu().numpy(), 0, 1, 0)
+    assert_bf16_parity(got, want, "cast config 1", exact_nan=True)
+    assert bool(np.all(got == want))
+    # a different seed, step or tensor id draws differently
+    for args in ((1, 1, 0), (0, 2, 0), (0, 1, 1)):
+        other = gpu_cast(x, *args)
+        assert bool(np.all(other == ref.sr_cast_f32_bf16(x.cpu().numpy(), *args)))
+        assert 0.2 < float((other != got).mean()) < 0.5
+
+
+@pytest.mark.parametrize("n", [1, 7, 8, 9, 63, 4097, 2 * 256 * 8 * 3 + 5])
+def test_cast_ragged_sizes_and_misaligned_views(n):
+    base = W.make_cast_input(n + 16, DEV, 77)
+    for off in (0, 1, 3):
+        x = base[off:off + n]
+        out_base = torch.zeros(n + 16, dtype=torch.bfloat16, device=DEV)
+        for ooff in (0, 1):
+            dst = out_base[ooff:ooff + n]
+            out_base.zero_()
+            B.sr_cast_f32_bf16(x, dst, 5, 3, 2)
+            torch.cuda.synchronize()
+            want = ref.sr_cast_f32_bf16(x.cpu().numpy(), 5, 3, 2)
+            assert bool(np.all(to_np(dst) == want))
+            # nothing outside the destination range was written
+            whole = to_np(out_base)
+            assert not whole[:ooff].any() and not whole[ooff + n:].any()
+
+
+def test_cast_special_values_exact_bits():
+    specials = [0x00000000, 0x80000000, 0x7F800000, 0xFF800000, 0x7FC00000, 0xFFC00000, 0x7F800001,
+                0xFF80FFFF, 0x7FFFFFFF, 0x7FA12345, 0x7F7FFFFF, 0xFF7FFFFF, 0x7F7F0001, 0x00000001,
+                0x80000001, 0x007FFFFF, 0x00800000, 0x0000FFFF, 0x00010000, 0x3F800000, 0x3F80FFFF,
+                0x3FFFFFFF, 0xBFFFFFFF, 0x7F7F8000]
+    bits = np.array(specials * 1024, dtype=np.uint32)
+    x = torch.from_numpy(bits.view(np.int32)).to(DEV).view(torch.float32)
+    for seed in (0, 1, 2):
+        got = gpu_cast(x, seed, 1, 0)
+        want = ref.sr_cast_f32_bf16(bits.view(np.float32), seed, 1, 0)
+        assert bool(np.all(got == want))
+    # +-FLT_MAX overflows to infinity for nearly every draw
+    fm = got.reshape(1024, len(specials))[:, specials.index(0x7F7FFFFF)]
+    assert (fm == 0x7F80).mean() > 0.99
+
+
+def test_cast_unbiased_on_device():
+    # E[Q_SR(x)] = x with the device's own draws: 4096 elements of one value, many steps
+    x = torch.full((1 << 16,), 1.0 + 2.0 ** -7 * 0.3, dtype=torch.float32, device=DEV)
+    got = gpu_cast(x, 123, 9, 4)
+    vals = ref.bf16_bits_to_f32(got).astype(np.float64)
+    k = int(x[:1].view(torch.int32).item() & 0xFFFF)
+    q = k / 65536.0
+    assert abs(vals.mean() - float(x[0])) <= 5 * 2.0 ** -7 * np.sqrt(q * (1 - q) / vals.size)
+
+
+def test_cast_empty():
+    x = torch.empty(0, dtype=torch.float32, device=DEV)
+    out = torch.empty(0, dtype=torch.bfloat16, device=DEV)
+    B.sr_cast_f32_bf16(x, out, 0, 1, 0)
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ sr_adamw_step
+
+def test_adamw_config1_flat_bit_exact():
+    cfg = W.config(1)
+    pair = run_config(cfg, cfg.shapes, 1)
+    # at step 1 from zero moments every parameter with a non-zero gradient moves by about lr
+    moved = (to_np(pair.p[0]) != W.bf16_to_u16_numpy(
+        W.make_params(cfg.shapes, DEV, W.data_seed(1, 0), cfg.param_std)[0])).mean()
+    assert moved > 0.5
+
+
+def test_adamw_gpt_list_ten_steps_bit_exact():
+    # config 2 recipe on a small GPT shape list: 2 + 12*3 + 2 = 40 tensors, ragged sizes
+    cfg = W.config(2)
+    shapes = W.gpt_shapes(72, 3, 200, 1003, 33)
+    pair = run_config(cfg, shapes, 10)
+    assert len(pair.host) == 40
+
+
+def test_adamw_more_tensors_than_one_launch_batch():
+    cfg = W.config(2)
+    shapes = W.gpt_shapes(24, 12, 40, 101, 16)          # 148 tensors -> three launches
+    assert len(shapes) == 148
+    run_config(cfg, shapes, 3)
+
+
+def test_adamw_clip_with_outliers_bit_exact():
+    cfg = W.config(3)
+    shapes = W.gpt_shapes(64, 2, 256, 5003, 64)
+    pair = run_config(cfg, shapes, 10)
+    assert float(pair.norm.item()) > 10.0                  # clipping is strongly active
+
+
+def test_adamw_fp32_moments_clip_bit_exact():
+    cfg = W.config(4)
+    shapes = W.gpt_shapes(80, 2, 320, 4099, 64)
+    pair = run_config(cfg, shapes, 5)
+    # FP32 moments agree to the bit, not just to 1e-6
+    for i, h in enumerate(pair.host):
+        assert bool(np.all(to_np(pair.m[i]) == h["m"])) and bool(np.all(to_np(pair.v[i]) == h["v"]))
+
+
+def test_adamw_warm_state_flat_bit_exact():
+    # config 5 recipe at 2^22 + 5 elements: warm moments, SR on all three outputs
+    cfg = W.config(5)
+    shapes = [("flat", ((1 << 22) + 5,), "weight")]
+    run_config(cfg, shapes, 6)
+
+
+def test_adamw_rne_moments_variant():
+    cfg = W.config(2)
+    shapes = W.gpt_shapes(40, 1, 96, 301, 16)
+    pair = make_pair(cfg, shapes)
+    for t in range(1, 4):
+        W.fill_grads(pair.g, W.data_seed(2, t), cfg.grad_std)
+        pair.step(cfg.hyper, t, 3, flags=B.SR_FLAG_RNE_MOMENTS)
+        pair.compare(f"rne moments step {t}")
+
+
+def _random_state(n, seed, fp32=False):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    p = (torch.randn(n, device=DEV, generator=g) * 0.02).to(torch.bfloat16)
+    gr = (torch.randn(n, device=DEV, generator=g) * 1e-3).to(torch.bfloat16)
+    m = torch.randn(n, device=DEV, generator=g) * 1e-3
+    v = torch.rand(n, device=DEV, generator=g) * 1e-6
+    if not fp32:
+        m, v = m.to(torch.bfloat16), v.to(torch.bfloat16)
+    return p, gr, m, v
+
+
+@pytest.mark.parametrize("fp32", [False, True])
+def test_adamw_ragged_misaligned_and_offset_tensors(fp32):
+    """Sizes around the 8-element block and the chunk size, views that start 2 bytes off a
+    16-byte boundary, element offsets that are not multiples of 8: same bits as the oracle."""
+    sizes = [1, 7, 8, 9, 15, 17, 1000, 4096, 4097, 2 * 256 * 8 + 3, 40000]
+    params, grads, ms, vs, offs = [], [], [], [], []
+    for i, n in enumerate(sizes):
+        shift = i % 3                                     # 0: aligned, 1 or 2 elements off
+        p, g, m, v = _random_state(n + 8, 100 + i, fp32)
+        params.append(p[shift:shift + n]); grads.append(g[shift:shift + n])
+        mshift = shift if i % 2 == 0 else (shift + 1) % 3   # moments sometimes aligned differently
+        ms.append(m[mshift:mshift + n]); vs.append(v[shift:shift + n])
+        offs.append([0, 8, 5, 1 << 33, (1 << 35) + 3][i % 5])
+    guards = [(t, to_np(t)) for t in params]
+    pair = Pair(params, ms, vs, fp32, tensor_ids=[7 * i + 1 for i in range(len(sizes))], elem_offsets=offs)
+    for g_dst, g_src in zip(pair.g, grads):
+        g_dst.copy_(g_src)
+    hyper = dict(lr=3e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    for t in (1, 2):
+        pair.step(hyper, t, seed=0xDEADBEEFCAFE, clip=0.01)
+        pair.compare(f"ragged step {t}")
+    del guards
+
+
+def test_adamw_does_not_write_outside_its_tensors():
+    n = 1003
+    bufs = [torch.full((n + 32,), 1.5, dtype=torch.bfloat16, device=DEV) for _ in range(4)]
+    p, g, m, v = (b[9:9 + n] for b in bufs)
+    tl = B.TensorList([p], [g], [m], [v])
+    B.sr_adamw_step(tl, dict(lr=1e-2, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1), 1, 0)
+    torch.cuda.synchronize()
+    for b in (bufs[0], bufs[2], bufs[3]):
+        outside = torch.cat([b[:9], b[9 + n:]])
+        assert bool((outside == 1.5).all())
+    assert bool((bufs[1] == 1.5).all())                    # gradients are never written
+
+
+def test_adamw_geometry_and_list_independence():
+    """Shared randomness (Algorithm 1 lines 9, 11): results depend on (seed, step, tensor id,
+    element index) only -- not on list order, on how the list is split over calls, on a tensor
+    being passed as shards with element offsets, or on running it twice from the same state."""
+    sizes = [5000, 123, 8192, 77, 30001]
+    hyper = dict(lr=6e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+
+    def fresh():
+        return [_random_state(n, 500 + i) for i, n in enumerate(sizes)]
+
+    def run(order_calls, shard=False):
+        st = fresh()
+        for call in order_calls:
+            ps, gs, ms, vs, ids, offs = [], [], [], [], [], []
+            for i in call:
+                p, g, m, v = st[i]
+                if shard and sizes[i] > 4000:
+                    cut = 2051                            # shard boundary inside an 8-block
+                    for lo, hi in ((0, cut), (cut, sizes[i])):
+                        ps.append(p[lo:hi]); gs.append(g[lo:hi]); ms.append(m[lo:hi]); vs.append(v[lo:hi])
+                        ids.append(i); offs.append(lo)
+                else:
+                    ps.append(p); gs.append(g); ms.append(m); vs.append(v); ids.append(i); offs.append(0)
+            tl = B.TensorList(ps, gs, ms, vs, False, ids, offs)
+            B.sr_adamw_step(tl, hyper, 3, 42)
+        torch.cuda.synchronize()
+        return [[to_np(x) for x in (p, m, v)] for p, _, m, v in st]
+
+    base = run([[0, 1, 2, 3, 4]])
+    for variant in (run([[4, 3, 2, 1, 0]]), run([[2, 0], [4], [1, 3]]), run([[0, 1, 2, 3, 4]], shard=True),
+                    run([[0, 1, 2, 3, 4]])):
+        for a, b in zip(base, variant):
+            for x, y in zip(a, b):
+                assert bool(np.all(x == y))
+
+
+def test_adamw_non_finite_and_extreme_inputs():
+    """Infinities, NaNs, huge and subnormal values in every input: same outputs as the oracle
+    (NaNs compared as NaNs), no flush to zero, overflow goes to infinity."""
+    vals = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x007F, 0x0080, 0x7F7F, 0xFF7F, 0x7F80, 0xFF80,
+                     0x7FC0, 0xFFC1, 0x3F80, 0xBF80, 0x0100, 0x7E00, 0x1234, 0x9234, 0x4000, 0x3C23],
+                    dtype=np.uint16)
+    rng = np.random.default_rng(0)
+    n = 1 << 15
+    cols = [vals[rng.integers(0, vals.size, n)] for _ in range(4)]
+    cols[3] = cols[3] & 0x7FFF                             # second moment: non-negative patterns
+    # half of the elements keep ordinary values in some inputs so that mixed cases occur
+    ordinary = _random_state(n, 9)
+    mix = rng.random((4, n)) < 0.5
+    tensors = []
+    for c, o, mk in zip(cols, ordinary, mix):
+        tensors.append(bf16_dev(np.where(mk, c, to_np(o))))
+    p, g, m, v = tensors
+    pair = Pair([p], [m], [v], False)
+    pair.g[0].copy_(g)
+    hyper = dict(lr=1e-2, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    pair.step(hyper, 2, seed=17)
+    pair.compare("extreme inputs")
+    out = to_np(pair.p[0])
+    assert is_nan16(out).any() and (out == 0x7F80).any()
+
+
+def test_adamw_zero_lr_keeps_parameters():
+    p, g, m, v = _random_state(10000, 3)
+    before = to_np(p)
+    tl = B.TensorList([p], [g], [m], [v])
+    B.sr_adamw_step(tl, dict(lr=0.0, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0), 1, 5)
+    torch.cuda.synchronize()
+    assert bool(np.all(to_np(p) == before))
+
+
+# ------------------------------------------------------------------ grad_global_norm
+
+def _gpu_norm(grads):
+    z = [torch.empty_like(g) for g in grads]
+    tl = B.TensorList(z, grads, z, z)
+    out = torch.full((1,), -1.0, dtype=torch.float32, device=DEV)
+    ws = torch.empty(max(tl.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
+    B.grad_global_norm(tl, out, ws)
+    torch.cuda.synchronize()
+    return float(out.item())
+
+
+def test_norm_exact_cases_on_device():
+    ints = torch.randint(-3, 4, (1000003,), device=DEV).to(torch.bfloat16)
+    S = int((ints.to(torch.int64) ** 2).sum().item())
+    assert _gpu_norm([ints[:400001], ints[400001:]]) == float(np.float32(np.sqrt(np.float64(S))))
+    a = torch.full((1 << 16,), -0.0078125, dtype=torch.bfloat16, device=DEV)
+    assert _gpu_norm([a]) == 0.0078125 * 256.0
+    tiny = torch.full((1 << 20,), 2.0 ** -10, dtype=torch.bfloat16, device=DEV)
+    big = torch.tensor([4096.0], dtype=torch.bfloat16, device=DEV)
+    assert _gpu_norm([big, tiny]) == float(np.float32(np.sqrt(np.float64(2 ** 24 + 1))))
+    assert _gpu_norm([]) == 0.0
+    assert _gpu_norm([tiny[:0]]) == 0.0
+
+
+def test_norm_no_underflow_or_overflow_of_squares():
+    small = torch.full((4096,), 1e-30, dtype=torch.bfloat16, device=DEV)     # squares < FP32 range
+    want = ref.grad_global_norm([to_np(small)])
+    assert want > 0 and _gpu_norm([small]) == want
+    huge = torch.full((4096,), 1e30, dtype=torch.bfloat16, device=DEV)       # squares > FP32 range
+    want = ref.grad_global_norm([to_np(huge)])
+    assert np.isfinite(want) and _gpu_norm([huge]) == want
+
+
+def test_norm_matches_oracle_on_gpt_list_and_misaligned_views():
+    cfg = W.config(3)
+    shapes = W.gpt_shapes(64, 2, 256, 5003, 64)
+    grads = W.make_grads(shapes, DEV, W.data_seed(3, 1), cfg.grad_std, cfg.outlier_frac, cfg.outlier_std)
+    want = ref.grad_global_norm([to_np(g) for g in grads])
+    got = _gpu_norm(grads)
+    assert got == want or abs(got - want) <= 1e-6 * want
+    views = [g[1:] for g in grads if g.numel() > 1]
+    want = ref.grad_global_norm([to_np(g) for g in views])
+    got = _gpu_norm(views)
+    assert got == want or abs(got - want) <= 1e-6 * want
+    # non-finite gradients give a non-finite norm
+    grads[3][5] = float("inf")
+    assert np.isinf(_gpu_norm(grads))
+    grads[3][5] = float("nan")
+    assert np.isnan(_gpu_norm(grads))
+
+
+def test_norm_is_reproducible():
+    g = W.make_grads(W.gpt_shapes(64, 2, 256, 5003, 64), DEV, 5, 1e-3)
+    assert len({_gpu_norm(g) for _ in range(3)}) == 1
