@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--warm-steps", type=int, default=None, help="seeded steps that warm the moments")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region, do one device copy of 2^30 bytes (a dispatch of "
+                         "known traffic that scales the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -157,6 +160,13 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     dev_ms = [a.elapsed_time(b) for a, b in zip(ev0, ev1)]
     dev_avg_ms = float(np.mean(dev_ms))
+
+    if args.calibrate_copy:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                                    # 2^30 bytes read, 2^30 bytes written
+        torch.cuda.synchronize()
 
     bpe = algorithmic_bytes_per_element(cfg)
     value = numel * args.steps / wall

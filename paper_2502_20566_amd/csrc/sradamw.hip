@@ -34,10 +34,16 @@ double pow_uint(double base, uint32_t e)
 }
 
 // Tunables of the fused update: blocks per lane and nontemporal access.
-constexpr int kU = 2;
-constexpr bool kNT = true;
+#ifndef SR_TUNE_U
+#define SR_TUNE_U 1
+#endif
+#ifndef SR_TUNE_NT
+#define SR_TUNE_NT 1
+#endif
+constexpr int kU = SR_TUNE_U;
+constexpr bool kNT = SR_TUNE_NT != 0;
 constexpr uint64_t kBlocksPerChunk = (uint64_t)kThreads * kU;
-constexpr int kCastU = 2;
+constexpr int kCastU = 1;
 constexpr uint32_t kMaxGrid = 0x7FFFFFFFu;
 
 template <bool FP32M, bool RNEM, bool CLIP>
@@ -129,7 +135,7 @@ int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_no
         batch.n_tensors = nb;
         batch.partial_base = base;
         batch.chunk_start[nb] = chunks_in_batch;
-        hipLaunchKernelGGL(sumsq_partial_kernel, dim3(chunks_in_batch), dim3(kThreads), 0, s, batch, partials);
+        hipLaunchKernelGGL(sumsq_partial_kernel, dim3(chunks_in_batch), dim3(kNormThreads), 0, s, batch, partials);
         base += chunks_in_batch;
         nb = 0; chunks_in_batch = 0;
         return hipGetLastError();

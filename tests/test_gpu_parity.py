@@ -140,7 +140,7 @@ def test_cast_config1_workload_bit_exact():
         assert 0.2 < float((other != got).mean()) < 0.5
 
 
-@pytest.mark.parametrize("n", [1, 7, 8, 9, 63, 4097, 2 * 256 * 8 * 3 + 5])
+@pytest.mark.parametrize("n", [1, 7, 8, 9, 63, 511, 512, 513, 4097, 2 * 256 * 8 * 3 + 5])
 def test_cast_ragged_sizes_and_misaligned_views(n):
     base = W.make_cast_input(n + 16, DEV, 77)
     for off in (0, 1, 3):
@@ -266,7 +266,7 @@ def _random_state(n, seed, fp32=False):
 def test_adamw_ragged_misaligned_and_offset_tensors(fp32):
     """Sizes around the 8-element block and the chunk size, views that start 2 bytes off a
     16-byte boundary, element offsets that are not multiples of 8: same bits as the oracle."""
-    sizes = [1, 7, 8, 9, 15, 17, 1000, 4096, 4097, 2 * 256 * 8 + 3, 40000]
+    sizes = [1, 7, 8, 9, 15, 17, 511, 512, 513, 1000, 4096, 4097, 2 * 256 * 8 + 3, 40000]
     params, grads, ms, vs, offs = [], [], [], [], []
     for i, n in enumerate(sizes):
         shift = i % 3                                     # 0: aligned, 1 or 2 elements off
