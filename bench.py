@@ -171,10 +171,13 @@ def main():
     bpe = algorithmic_bytes_per_element(cfg)
     value = numel * args.steps / wall
     achieved = bpe * numel / (dev_avg_ms * 1e-3) / 1e9
+    # HBM bytes per launch measured with rocprofv3 PMC counters (see the summary under profiles/)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_config{cfg.index}.json")
+    tpath = os.path.join(ROOT, "profiles", f"adamw_kernel_config{cfg.index}_hbm_traffic.txt")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_step")
+        for line in open(tpath):
+            if line.startswith("hbm_bytes_per_launch"):
+                traffic = int(line.split("=")[1])
 
     out = {
         "metric": "sr_adamw_params_updated_per_sec",

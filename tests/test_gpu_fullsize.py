@@ -1,0 +1,163 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times.  Configs 2 and 3: every element of every tensor against the oracle.  Configs 4 and
+5: the GPU updates the whole parameter set; the oracle follows seeded windows of it through every
+step (the update is element-wise and the RNG is random-access, so a window with its element offset
+is self-contained), including windows that straddle element index 2^32.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2502_20566_amd import binding as B
+from paper_2502_20566_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def to_np(t):
+    if t.dtype == torch.bfloat16:
+        return W.bf16_to_u16_numpy(t)
+    return t.detach().cpu().numpy().copy()
+
+
+def same_bf16(got, want):
+    """Bit-exact, NaNs compared as NaNs; returns the number of mismatches."""
+    gn = ((got & 0x7F80) == 0x7F80) & ((got & 0x7F) != 0)
+    wn = ((want & 0x7F80) == 0x7F80) & ((want & 0x7F) != 0)
+    return int(((got != want) & ~(gn & wn)).sum())
+
+
+class Windows:
+    """Host copies of slices [lo, lo+n) of some tensors, advanced by the oracle."""
+
+    def __init__(self, params, ms, vs, picks, fp32):
+        self.picks = picks                      # list of (tensor index, lo, n)
+        self.fp32 = fp32
+        self.host = [dict(p=to_np(params[i][lo:lo + n]), m=to_np(ms[i][lo:lo + n]),
+                          v=to_np(vs[i][lo:lo + n]), tensor_id=i, elem_offset=lo)
+                     for i, lo, n in picks]
+
+    def step(self, grads, hyper, t, seed, norm, max_norm):
+        for h, (i, lo, n) in zip(self.host, self.picks):
+            h["g"] = to_np(grads[i][lo:lo + n])
+        flags = ref.FLAG_FP32_MOMENTS if self.fp32 else 0
+        ref.sr_adamw_step(self.host, hyper, t, seed, flags, norm=norm, max_norm=max_norm)
+
+    def mismatches(self, params, ms, vs):
+        bad = 0
+        for h, (i, lo, n) in zip(self.host, self.picks):
+            bad += same_bf16(to_np(params[i][lo:lo + n]), h["p"])
+            if self.fp32:
+                gm, gv = to_np(ms[i][lo:lo + n]), to_np(vs[i][lo:lo + n])
+                bad += int((~((gm == h["m"]) | (np.abs(gm - h["m"]) <= 1e-6 * np.abs(h["m"])))).sum())
+                bad += int((~((gv == h["v"]) | (np.abs(gv - h["v"]) <= 1e-6 * np.abs(h["v"])))).sum())
+            else:
+                bad += same_bf16(to_np(ms[i][lo:lo + n]), h["m"])
+                bad += same_bf16(to_np(vs[i][lo:lo + n]), h["v"])
+        return bad
+
+
+def setup(cfg):
+    params = W.make_params(cfg.shapes, DEV, W.data_seed(cfg.index, 0), cfg.param_std)
+    ms, vs = W.make_moments(cfg.shapes, DEV, cfg.fp32_moments)
+    grads = [torch.empty_like(p) for p in params]
+    tl = B.TensorList(params, grads, ms, vs, cfg.fp32_moments)
+    norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+    ws = torch.empty(max(tl.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
+    return params, grads, ms, vs, tl, norm, ws
+
+
+def gpu_step(cfg, tl, t, norm, ws):
+    flags = B.SR_FLAG_FP32_MOMENTS if cfg.fp32_moments else 0
+    if cfg.clip is not None:
+        B.grad_global_norm(tl, norm, ws)
+        B.sr_adamw_step(tl, cfg.hyper, t, cfg.seed, flags, norm, cfg.clip)
+        torch.cuda.synchronize()
+        return float(norm.item())
+    B.sr_adamw_step(tl, cfg.hyper, t, cfg.seed, flags)
+    torch.cuda.synchronize()
+    return None
+
+
+def full_compare(cfg, steps, check_norm_with_oracle):
+    params, grads, ms, vs, tl, norm, ws = setup(cfg)
+    host = [dict(p=to_np(p), m=to_np(m), v=to_np(v)) for p, m, v in zip(params, ms, vs)]
+    for t in range(1, steps + 1):
+        W.fill_grads(grads, W.data_seed(cfg.index, t), cfg.grad_std, cfg.outlier_frac, cfg.outlier_std)
+        for h, g in zip(host, grads):
+            h["g"] = to_np(g)
+        nv = gpu_step(cfg, tl, t, norm, ws)
+        if nv is not None and check_norm_with_oracle:
+            want = ref.grad_global_norm([h["g"] for h in host])
+            assert nv == want or abs(nv - want) <= 1e-6 * want, (t, nv, want)
+        ref.sr_adamw_step(host, cfg.hyper, t, cfg.seed, 0, norm=nv, max_norm=cfg.clip or 0.0)
+        bad = 0
+        for i, h in enumerate(host):
+            bad += same_bf16(to_np(params[i]), h["p"]) + same_bf16(to_np(ms[i]), h["m"]) + same_bf16(to_np(vs[i]), h["v"])
+        assert bad == 0, f"{cfg.name} step {t}: {bad} mismatching values"
+    return params, host
+
+
+def test_config2_full_buffers_ten_steps():
+    cfg = W.config(2)
+    p0 = W.make_params(cfg.shapes, DEV, W.data_seed(2, 0), cfg.param_std)
+    params, host = full_compare(cfg, 10, False)
+    # parameters keep moving under SR (no stagnation); report how many updates were sub-spacing
+    wte_before = ref.bf16_bits_to_f32(to_np(p0[0])).astype(np.float64)
+    wte_after = ref.bf16_bits_to_f32(host[0]["p"]).astype(np.float64)
+    assert float((wte_after != wte_before).mean()) > 0.05
+
+
+def test_config3_full_buffers_clip():
+    full_compare(W.config(3), 3, True)
+
+
+def test_config4_full_size_windows_fp32_moments_clip():
+    cfg = W.config(4)
+    params, grads, ms, vs, tl, norm, ws = setup(cfg)
+    rng = np.random.default_rng(4)
+    picks = []
+    for i in list(range(0, len(params), 29)) + [len(params) - 1]:
+        n = params[i].numel()
+        w = min(n, 1 << 15)
+        picks += [(i, 0, w), (i, n - w, w)]
+        if n > (1 << 20):
+            lo = int(rng.integers(0, n - (1 << 16)))
+            picks.append((i, lo, 1 << 16))
+    win = Windows(params, ms, vs, picks, True)
+    for t in range(1, cfg.steps + 1):
+        W.fill_grads(grads, W.data_seed(4, t), cfg.grad_std)
+        nv = gpu_step(cfg, tl, t, norm, ws)
+        # the norm against a binary64 reduction by an independent library routine
+        s = 0.0
+        for g in grads:
+            s += float(g.double().pow(2).sum().item())
+        want = float(np.float32(np.sqrt(s)))
+        assert nv == want or abs(nv - want) <= 1e-6 * want, (t, nv, want)
+        win.step(grads, cfg.hyper, t, cfg.seed, nv, cfg.clip)
+        assert win.mismatches(params, ms, vs) == 0, f"config 4 step {t}"
+
+
+def test_config5_full_size_windows_through_warm_start():
+    cfg = W.config(5)
+    params, grads, ms, vs, tl, norm, ws = setup(cfg)
+    n = params[0].numel()
+    assert n == 6658465792
+    rng = np.random.default_rng(5)
+    w = 1 << 17
+    picks = [(0, 0, w), (0, n - w, w), (0, (1 << 32) - w // 2, w), (0, (1 << 32) + 3, w - 5),
+             (0, (1 << 32) - 1, 2), (0, 3 * (1 << 31) - 77, w), (0, n - 7, 7), (0, 12345, 999)]
+    picks += [(0, int(rng.integers(0, n - w)), w) for _ in range(16)]
+    win = Windows(params, ms, vs, picks, False)
+    steps = cfg.warm_steps + 1
+    for t in range(1, steps + 1):
+        W.fill_grads(grads, W.data_seed(5, t), cfg.grad_std)
+        gpu_step(cfg, tl, t, norm, ws)
+        win.step(grads, cfg.hyper, t, cfg.seed, None, 0.0)
+        if t in (1, 2, 50, steps):
+            assert win.mismatches(params, ms, vs) == 0, f"config 5 step {t}"
+    # after the warm start the second moment is alive and updates are far below a BF16 spacing
+    v_end = ref.bf16_bits_to_f32(win.host[0]["v"])
+    assert float((v_end > 0).mean()) > 0.99
