@@ -80,6 +80,20 @@ __device__ __forceinline__ void store_v4(void* ptr, v4u x)
     else *reinterpret_cast<v4u*>(ptr) = x;
 }
 
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+template <bool NT>
+__device__ __forceinline__ v2u load_v2(const void* ptr)
+{
+    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const v2u*>(ptr));
+    return *reinterpret_cast<const v2u*>(ptr);
+}
+template <bool NT>
+__device__ __forceinline__ void store_v2(void* ptr, v2u x)
+{
+    if (NT) __builtin_nontemporal_store(x, reinterpret_cast<v2u*>(ptr));
+    else *reinterpret_cast<v2u*>(ptr) = x;
+}
+
 // Eight BF16 values starting at element l0 of `base` as four packed pairs.  `full`: the block lies
 // inside the tensor and is 16-byte aligned.  Otherwise element-wise, with zeros outside [0, numel).
 template <bool NT>
@@ -199,11 +213,52 @@ struct BlockRegs {
     float mf[8], vf[8];        // binary32 moments (FP32M only)
 };
 
-// Algorithm 1 lines 5-10 on the eight elements of one block, then the write-back roundings.
+// The 128 random bits of each output stream of one block (rm, rv only for SR'd BF16 moments).
+struct BlockBits { u32x4 rp, rm, rv; };
+
+template <bool FP32M, bool RNEM>
+__device__ __forceinline__ BlockBits draw_block_bits(const StepScalars& S, uint64_t gblk, uint32_t tensor_id)
+{
+    BlockBits b;
+    b.rp = block_bits(gblk, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
+    if (!FP32M && !RNEM) {
+        b.rm = block_bits(gblk, STREAM_M, tensor_id, S.step, S.seed_lo, S.seed_hi);
+        b.rv = block_bits(gblk, STREAM_V, tensor_id, S.step, S.seed_lo, S.seed_hi);
+    }
+    return b;
+}
+
+// Algorithm 1 lines 5-10 for one element.  In: p, g, m, v.  Out: y = unrounded new parameter,
+// m and v replaced by the unrounded new moments.  One rounding per operation, in this order (no
+// contraction: the library is built with -ffp-contract=off; sqrt and divide are correctly rounded).
+template <bool CLIP>
+__device__ __forceinline__ void update_elem(const StepScalars& S, float c, float p, float g, float& m, float& v, float& y)
+{
+    const float g1 = CLIP ? g * c : g;
+    const float t1 = S.beta1 * m;
+    const float t2 = S.omb1 * g1;
+    const float m1 = t1 + t2;
+    const float gg = g1 * g1;
+    const float t3 = S.beta2 * v;
+    const float t4 = S.omb2 * gg;
+    const float v1 = t3 + t4;
+    const float mh = m1 * S.rbc1;
+    const float vh = v1 * S.rbc2;
+    const float d = __builtin_sqrtf(vh) + S.eps;
+    const float q = mh / d;
+    const float a = S.lr * q;
+    const float w = S.lw * p;
+    const float sum = a + w;
+    y = p - sum;
+    m = m1;
+    v = v1;
+}
+
+// The update on the eight elements of one block, then the write-back roundings.
 // In: R as loaded.  Out: R.p (and R.mq, R.vq, or R.mf, R.vf) hold what is to be stored.
 template <bool FP32M, bool RNEM, bool CLIP>
 __device__ __forceinline__ void update_block(BlockRegs<FP32M>& R, const StepScalars& S, float c,
-                                             uint64_t gblk, uint32_t tensor_id)
+                                             const BlockBits& bits)
 {
     float p[8], g[8], m[8], v[8], y[8];
     unpack8(R.p, p);
@@ -216,31 +271,10 @@ __device__ __forceinline__ void update_block(BlockRegs<FP32M>& R, const StepScal
         unpack8(R.vq, v);
     }
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        // one rounding per operation, in this order (no contraction: built with -ffp-contract=off)
-        const float g1 = CLIP ? g[j] * c : g[j];
-        const float t1 = S.beta1 * m[j];
-        const float t2 = S.omb1 * g1;
-        const float m1 = t1 + t2;
-        const float gg = g1 * g1;
-        const float t3 = S.beta2 * v[j];
-        const float t4 = S.omb2 * gg;
-        const float v1 = t3 + t4;
-        const float mh = m1 * S.rbc1;
-        const float vh = v1 * S.rbc2;
-        const float d = __builtin_sqrtf(vh) + S.eps;
-        const float q = mh / d;
-        const float a = S.lr * q;
-        const float w = S.lw * p[j];
-        const float s = a + w;
-        y[j] = p[j] - s;
-        m[j] = m1;
-        v[j] = v1;
-    }
+    for (int j = 0; j < 8; ++j) update_elem<CLIP>(S, c, p[j], g[j], m[j], v[j], y[j]);
     // A NaN in m' or v' always makes y NaN, so one test covers all three outputs.
     const bool nan = any_nan8(y);
-    const u32x4 rp = block_bits(gblk, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
-    R.p = nan ? sr8<true>(y, rp) : sr8<false>(y, rp);
+    R.p = nan ? sr8<true>(y, bits.rp) : sr8<false>(y, bits.rp);
     if (FP32M) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) { R.mf[j] = m[j]; R.vf[j] = v[j]; }
@@ -250,10 +284,8 @@ __device__ __forceinline__ void update_block(BlockRegs<FP32M>& R, const StepScal
         R.vq.x = rne_pair(v[0], v[1]); R.vq.y = rne_pair(v[2], v[3]);
         R.vq.z = rne_pair(v[4], v[5]); R.vq.w = rne_pair(v[6], v[7]);
     } else {
-        const u32x4 rm = block_bits(gblk, STREAM_M, tensor_id, S.step, S.seed_lo, S.seed_hi);
-        const u32x4 rv = block_bits(gblk, STREAM_V, tensor_id, S.step, S.seed_lo, S.seed_hi);
-        R.mq = nan ? sr8<true>(m, rm) : sr8<false>(m, rm);
-        R.vq = nan ? sr8<true>(v, rv) : sr8<false>(v, rv);
+        R.mq = nan ? sr8<true>(m, bits.rm) : sr8<false>(m, bits.rm);
+        R.vq = nan ? sr8<true>(v, bits.rv) : sr8<false>(v, bits.rv);
     }
 }
 
@@ -307,6 +339,52 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
         if (c > 1.0f) c = 1.0f;
     }
 
+    if constexpr (FP32M) {
+        // Binary32 moments: a lane owns HALF a block (4 elements), so that every access of the
+        // wave is one contiguous run (p, g: 8 bytes per lane; m, v: 16 bytes per lane) and a wave
+        // issues only four loads and three stores.  The two lanes of a block draw the same Philox
+        // block and each uses its half.  A chunk is kThreads*4 elements = kThreads/2 blocks.
+        const uint64_t cl = chunk - B.chunk_start[ti];
+        const uint64_t efirst = cl * (uint64_t)(kThreads * 4);
+        if (vec && efirst + (uint64_t)(kThreads * 4) <= numel) {          // wave-uniform
+            const uint64_t e = efirst + (uint64_t)threadIdx.x * 4;
+            float* mp = static_cast<float*>(T.m) + e;
+            float* vp = static_cast<float*>(T.v) + e;
+            const v2u Pq = load_v2<NT>(T.p + e), Gq = load_v2<NT>(T.g + e);
+            const v4u Mq = load_v4<NT>(mp), Vq = load_v4<NT>(vp);
+            const u32x4 r = block_bits((G0 + e) >> 3, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
+            const bool upper = ((e >> 2) & 1u) != 0;                       // elements 4..7 of the block
+            const uint32_t w0 = upper ? r.w[2] : r.w[0], w1 = upper ? r.w[3] : r.w[1];
+            const float p[4] = {bf16_lo(Pq.x), bf16_hi(Pq.x), bf16_lo(Pq.y), bf16_hi(Pq.y)};
+            const float g[4] = {bf16_lo(Gq.x), bf16_hi(Gq.x), bf16_lo(Gq.y), bf16_hi(Gq.y)};
+            float m[4] = {__uint_as_float(Mq.x), __uint_as_float(Mq.y), __uint_as_float(Mq.z), __uint_as_float(Mq.w)};
+            float v[4] = {__uint_as_float(Vq.x), __uint_as_float(Vq.y), __uint_as_float(Vq.z), __uint_as_float(Vq.w)};
+            float y[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) update_elem<CLIP>(S, c, p[j], g[j], m[j], v[j], y[j]);
+            const bool nan = (y[0] != y[0]) | (y[1] != y[1]) | (y[2] != y[2]) | (y[3] != y[3]);
+            v2u po;
+            if (nan) { po.x = sr_pair_nan_safe(y[0], y[1], w0); po.y = sr_pair_nan_safe(y[2], y[3], w1); }
+            else     { po.x = sr_pair(y[0], y[1], w0);          po.y = sr_pair(y[2], y[3], w1); }
+            v4u mo, vo;
+            mo.x = __float_as_uint(m[0]); mo.y = __float_as_uint(m[1]); mo.z = __float_as_uint(m[2]); mo.w = __float_as_uint(m[3]);
+            vo.x = __float_as_uint(v[0]); vo.y = __float_as_uint(v[1]); vo.z = __float_as_uint(v[2]); vo.w = __float_as_uint(v[3]);
+            store_v2<NT>(T.p + e, po);
+            store_v4<NT>(mp, mo);
+            store_v4<NT>(vp, vo);
+            return;
+        }
+        // General path: the chunk's kThreads/2 blocks, one per lane, element-wise access.
+        const uint64_t b = cl * (uint64_t)(kThreads / 2) + threadIdx.x;
+        if (threadIdx.x >= kThreads / 2 || b >= nblk) return;
+        const int64_t l0 = (int64_t)((gblk0 + b) << 3) - (int64_t)G0;
+        BlockRegs<FP32M> R;
+        load_block<FP32M, false>(R, T, l0, false);
+        update_block<FP32M, RNEM, CLIP>(R, S, c, draw_block_bits<FP32M, RNEM>(S, gblk0 + b, tensor_id));
+        store_block<FP32M, false>(R, T, l0, false);
+        return;
+    }
+
     const uint64_t bfirst = (uint64_t)(chunk - B.chunk_start[ti]) * (uint64_t)(kThreads * U) + threadIdx.x;
     const uint64_t blast = bfirst + (uint64_t)(U - 1) * kThreads;
 
@@ -320,7 +398,7 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint64_t b = bfirst + (uint64_t)u * kThreads;
-            update_block<FP32M, RNEM, CLIP>(R[u], S, c, gblk0 + b, tensor_id);
+            update_block<FP32M, RNEM, CLIP>(R[u], S, c, draw_block_bits<FP32M, RNEM>(S, gblk0 + b, tensor_id));
             store_block<FP32M, NT>(R[u], T, (int64_t)(b << 3), true);
         }
         return;
@@ -335,33 +413,47 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
         const bool full = vec && ((uint64_t)l0 + 8 <= numel);
         BlockRegs<FP32M> R;
         load_block<FP32M, false>(R, T, l0, full);
-        update_block<FP32M, RNEM, CLIP>(R, S, c, gblk0 + b, tensor_id);
+        update_block<FP32M, RNEM, CLIP>(R, S, c, draw_block_bits<FP32M, RNEM>(S, gblk0 + b, tensor_id));
         store_block<FP32M, false>(R, T, l0, full);
     }
 }
 
 // ----------------------------------------------------------------------- standalone SR cast
 
-template <int U, bool NT>
+// A lane owns half a block (4 elements): one 16-byte load and one 8-byte store per lane, every
+// access of the wave contiguous.  The two lanes of a block draw the same Philox block.
+template <bool NT>
 __global__ __launch_bounds__(kThreads) void cast_kernel(const float* __restrict__ src,
                                                         uint16_t* __restrict__ dst, uint64_t n,
                                                         uint32_t seed_lo, uint32_t seed_hi,
                                                         uint32_t step, uint32_t tensor_id, uint32_t vec)
 {
-    const uint64_t nblk = (n + 7) >> 3;
-    const uint64_t bfirst = (uint64_t)blockIdx.x * (uint64_t)(kThreads * U) + threadIdx.x;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint64_t b = bfirst + (uint64_t)u * kThreads;
-        if (b >= nblk) continue;
-        const int64_t l0 = (int64_t)(b << 3);
-        const bool full = vec && ((uint64_t)l0 + 8 <= n);
-        float y[8];
-        load8_f32<NT>(src, l0, n, full, y);
-        const u32x4 r = block_bits(b, STREAM_CAST, tensor_id, step, seed_lo, seed_hi);
-        const v4u o = any_nan8(y) ? sr8<true>(y, r) : sr8<false>(y, r);
-        store8_bf16<NT>(dst, l0, n, full, o);
+    const uint64_t efirst = (uint64_t)blockIdx.x * (uint64_t)(kThreads * 4);
+    if (vec && efirst + (uint64_t)(kThreads * 4) <= n) {                  // wave-uniform
+        const uint64_t e = efirst + (uint64_t)threadIdx.x * 4;
+        const v4u x = load_v4<NT>(src + e);
+        const u32x4 r = block_bits(e >> 3, STREAM_CAST, tensor_id, step, seed_lo, seed_hi);
+        const bool upper = ((e >> 2) & 1u) != 0;
+        const uint32_t w0 = upper ? r.w[2] : r.w[0], w1 = upper ? r.w[3] : r.w[1];
+        const float y0 = __uint_as_float(x.x), y1 = __uint_as_float(x.y);
+        const float y2 = __uint_as_float(x.z), y3 = __uint_as_float(x.w);
+        const bool nan = (y0 != y0) | (y1 != y1) | (y2 != y2) | (y3 != y3);
+        v2u o;
+        if (nan) { o.x = sr_pair_nan_safe(y0, y1, w0); o.y = sr_pair_nan_safe(y2, y3, w1); }
+        else     { o.x = sr_pair(y0, y1, w0);          o.y = sr_pair(y2, y3, w1); }
+        store_v2<NT>(dst + e, o);
+        return;
     }
+    // General path (tail chunk, misaligned pointers): the chunk's kThreads/2 blocks, one per lane.
+    const uint64_t nblk = (n + 7) >> 3;
+    const uint64_t b = (uint64_t)blockIdx.x * (uint64_t)(kThreads / 2) + threadIdx.x;
+    if (threadIdx.x >= kThreads / 2 || b >= nblk) return;
+    const int64_t l0 = (int64_t)(b << 3);
+    float y[8];
+    load8_f32<false>(src, l0, n, false, y);
+    const u32x4 r = block_bits(b, STREAM_CAST, tensor_id, step, seed_lo, seed_hi);
+    const v4u o = any_nan8(y) ? sr8<true>(y, r) : sr8<false>(y, r);
+    store8_bf16<false>(dst, l0, n, false, o);
 }
 
 // ------------------------------------------------------------------------- gradient norm

@@ -42,8 +42,10 @@ double pow_uint(double base, uint32_t e)
 #endif
 constexpr int kU = SR_TUNE_U;
 constexpr bool kNT = SR_TUNE_NT != 0;
-constexpr uint64_t kBlocksPerChunk = (uint64_t)kThreads * kU;
-constexpr int kCastU = 1;
+// Blocks per chunk (= per workgroup): BF16 moments, a lane owns kU blocks; binary32 moments, a lane
+// owns half a block.
+constexpr uint64_t kBlocksPerChunkBf16 = (uint64_t)kThreads * kU;
+constexpr uint64_t kBlocksPerChunkFp32 = (uint64_t)kThreads / 2;
 constexpr uint32_t kMaxGrid = 0x7FFFFFFFu;
 
 template <bool FP32M, bool RNEM, bool CLIP>
@@ -94,11 +96,11 @@ int sr_cast_f32_bf16(const float* d_src, void* d_dst, uint64_t n, uint64_t seed,
     if (!d_src || !d_dst) return SR_ERR_NULL;
     if (!aligned(d_src, 4) || !aligned(d_dst, 2)) return SR_ERR_ALIGN;
     const uint64_t nblk = (n + 7) >> 3;
-    const uint64_t per_wg = (uint64_t)kThreads * kCastU;
+    const uint64_t per_wg = (uint64_t)kThreads / 2;                 // blocks per workgroup
     const uint64_t grid = (nblk + per_wg - 1) / per_wg;
     if (grid > kMaxGrid) return SR_ERR_ARG;
     const uint32_t vec = (aligned(d_src, 16) && aligned(d_dst, 16)) ? 1u : 0u;
-    hipLaunchKernelGGL((cast_kernel<kCastU, kNT>), dim3((uint32_t)grid), dim3(kThreads), 0,
+    hipLaunchKernelGGL((cast_kernel<kNT>), dim3((uint32_t)grid), dim3(kThreads), 0,
                        static_cast<hipStream_t>(stream), d_src, static_cast<uint16_t*>(d_dst), n,
                        (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), step, tensor_id, vec);
     const hipError_t e = hipGetLastError();
@@ -193,7 +195,7 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
             return SR_ERR_ALIGN;
         if (t.elem_offset + t.numel < t.numel) return SR_ERR_ARG;          // index range wraps
         const uint64_t nblk = ((t.elem_offset + t.numel - 1) >> 3) - (t.elem_offset >> 3) + 1;
-        if ((nblk + kBlocksPerChunk - 1) / kBlocksPerChunk > kMaxGrid) return SR_ERR_ARG;
+        if ((nblk + kBlocksPerChunkFp32 - 1) / kBlocksPerChunkFp32 > kMaxGrid) return SR_ERR_ARG;
     }
 
     AdamwBatch batch;
@@ -228,7 +230,8 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
         const sr_tensor_t& t = tensors[i];
         if (t.numel == 0) continue;
         const uint64_t nblk = ((t.elem_offset + t.numel - 1) >> 3) - (t.elem_offset >> 3) + 1;
-        const uint32_t nch = (uint32_t)((nblk + kBlocksPerChunk - 1) / kBlocksPerChunk);
+        const uint64_t per_chunk = fp32m ? kBlocksPerChunkFp32 : kBlocksPerChunkBf16;
+        const uint32_t nch = (uint32_t)((nblk + per_chunk - 1) / per_chunk);
         if (nb == kMaxBatch || (uint64_t)chunks_in_batch + nch > kMaxGrid) {
             const hipError_t e = flush();
             if (e != hipSuccess) return hip_fail(e);
