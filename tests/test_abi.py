@@ -60,7 +60,7 @@ def test_strerror_covers_all_codes():
 
 def test_workspace_bytes_bounds_the_partials():
     L = B.lib()
-    chunk = 256 * 8 * 16
+    chunk = 512 * 8 * 16
     for n_t, numel in [(0, 0), (1, 1), (3, chunk), (388, 2651591680), (1, 6658465792)]:
         w = L.sr_workspace_bytes(n_t, numel)
         assert w % 256 == 0 and w >= 8 * (numel // chunk + n_t)
@@ -121,7 +121,7 @@ def test_norm_argument_errors():
     assert L.grad_global_norm(arr, 1, None, ws, 4096, None) == B.SR_ERR_NULL
     assert L.grad_global_norm(None, 1, out, ws, 4096, None) == B.SR_ERR_NULL
     assert L.grad_global_norm(arr, 1, out, None, 4096, None) == B.SR_ERR_WORKSPACE
-    assert L.grad_global_norm(arr, 1, out, ws, 8, None) == B.SR_ERR_WORKSPACE       # 4 chunks need 32 bytes
+    assert L.grad_global_norm(arr, 1, out, ws, 8, None) == B.SR_ERR_WORKSPACE       # 2 chunks need 16 bytes
     assert L.grad_global_norm(arr, 1, out, ws + 4, 4096, None) == B.SR_ERR_WORKSPACE
     assert L.grad_global_norm(arr, 1, out + 2, ws, 4096, None) == B.SR_ERR_ALIGN
     arr[0].g = None
