@@ -16,6 +16,9 @@ from . import build as _build
 
 FLAG_FP32_MOMENTS = 1
 FLAG_RNE_MOMENTS = 2
+FLAG_RNE_PARAMS = 4
+FLAG_MASTER_FP32 = 8
+FLAG_KAHAN = 16
 
 STREAM_PARAM, STREAM_M, STREAM_V, STREAM_CAST = 0, 1, 2, 3
 
@@ -58,7 +61,7 @@ def lib():
         L.ref_adamw_unrounded.argtypes = [u16p, u16p, C.c_void_p, C.c_void_p, C.c_uint64,
                                           C.POINTER(Scalars), C.c_uint32, f32p, f32p, f32p]
         L.ref_adamw_unrounded.restype = None
-        L.ref_sr_adamw_tensor.argtypes = [u16p, u16p, C.c_void_p, C.c_void_p, C.c_uint64,
+        L.ref_sr_adamw_tensor.argtypes = [u16p, u16p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
                                           C.c_uint32, C.c_uint64, C.POINTER(Scalars),
                                           C.c_uint32, C.c_uint64, C.c_uint32, C.c_int]
         L.ref_sr_adamw_tensor.restype = None
@@ -182,10 +185,20 @@ def adamw_unrounded(p, g, m, v, scalars: Scalars, flags=0):
 
 
 def sr_adamw_tensor(p, g, m, v, tensor_id, scalars: Scalars, step, seed, flags=0,
-                    elem_offset=0, nthreads=0):
-    """One tensor, in place over p, m, v (numpy arrays)."""
+                    elem_offset=0, nthreads=0, aux=None):
+    """One tensor, in place over p, m, v (numpy arrays) and aux (binary32 master parameters with
+    FLAG_MASTER_FP32, BF16 compensation bits with FLAG_KAHAN)."""
     assert p.size == g.size == m.size == v.size
-    lib().ref_sr_adamw_tensor(_u16(p), _u16(g), _moment_ptr(m, flags), _moment_ptr(v, flags),
+    aptr = None
+    if flags & FLAG_MASTER_FP32:
+        assert flags & FLAG_FP32_MOMENTS
+        assert aux is not None and aux.dtype == np.float32 and aux.flags.c_contiguous and aux.size == p.size
+        aptr = aux.ctypes.data_as(C.c_void_p)
+    elif flags & FLAG_KAHAN:
+        assert not (flags & FLAG_FP32_MOMENTS)
+        assert aux is not None and aux.dtype == np.uint16 and aux.flags.c_contiguous and aux.size == p.size
+        aptr = aux.ctypes.data_as(C.c_void_p)
+    lib().ref_sr_adamw_tensor(_u16(p), _u16(g), _moment_ptr(m, flags), _moment_ptr(v, flags), aptr,
                               p.size, tensor_id, elem_offset, C.byref(scalars), step, seed,
                               flags, nthreads)
 
@@ -198,7 +211,7 @@ def sr_adamw_step(tensors, hyper, step, seed, flags=0, norm=None, max_norm=0.0, 
                       hyper["weight_decay"], step, norm, max_norm)
     for idx, t in enumerate(tensors):
         sr_adamw_tensor(t["p"], t["g"], t["m"], t["v"], t.get("tensor_id", idx), s, step, seed,
-                        flags, t.get("elem_offset", 0), nthreads)
+                        flags, t.get("elem_offset", 0), nthreads, aux=t.get("aux"))
     return s
 
 

@@ -45,6 +45,9 @@
 
 #define REF_FLAG_FP32_MOMENTS 1u
 #define REF_FLAG_RNE_MOMENTS  2u
+#define REF_FLAG_RNE_PARAMS   4u
+#define REF_FLAG_MASTER_FP32  8u
+#define REF_FLAG_KAHAN       16u
 
 /* ---------------------------------------------------------------- RNG --- */
 
@@ -254,7 +257,7 @@ void ref_adamw_scalars(float lr, float beta1, float beta2, float eps, float weig
 /* One element of Algorithm 1 lines 5-10 before the write-back rounding:
  * returns the unrounded new parameter y and the unrounded moments m1, v1. */
 static void adamw_element(const ref_scalars_t* s, float p, float g, float m, float v,
-                          float* y_out, float* m1_out, float* v1_out)
+                          float* y_out, float* m1_out, float* v1_out, float* sum_out)
 {
     float g1 = g * s->clip;
     /* line 5: m <- beta1 m + (1 - beta1) g */
@@ -277,6 +280,7 @@ static void adamw_element(const ref_scalars_t* s, float p, float g, float m, flo
     float sum = a + b;
     float y = p - sum;
     *y_out = y; *m1_out = m1; *v1_out = v1;
+    if (sum_out) *sum_out = sum;
 }
 
 /* Unrounded results (for the FP32-intermediate checks). m, v are BF16 bit
@@ -290,23 +294,38 @@ void ref_adamw_unrounded(const uint16_t* p, const uint16_t* g, const void* m, co
         float mi = fp32m ? ((const float*)m)[i] : bf16_bits_to_float(((const uint16_t*)m)[i]);
         float vi = fp32m ? ((const float*)v)[i] : bf16_bits_to_float(((const uint16_t*)v)[i]);
         adamw_element(s, bf16_bits_to_float(p[i]), bf16_bits_to_float(g[i]), mi, vi,
-                      &y[i], &m1[i], &v1[i]);
+                      &y[i], &m1[i], &v1[i], NULL);
     }
 }
 
-/* One tensor of one step, in place over p, m, v.
+/* One tensor of one step, in place over p, m, v (and aux).
  *   BF16 moments (default): p, m, v all written back with SR, streams 0, 1, 2;
  *   REF_FLAG_FP32_MOMENTS : m, v are binary32 and stored unrounded, SR on p only;
  *   REF_FLAG_RNE_MOMENTS  : BF16 moments written back with round-to-nearest-even
- *                           (the paper's own setting: SR on line 10 only).
+ *                           (the paper's own setting: SR on line 10 only);
+ *   REF_FLAG_RNE_PARAMS   : the parameter write-back is round-to-nearest-even too
+ *                           (with RNE_MOMENTS: the "BF16" nearest-rounding strategy of
+ *                           Section 5.1, no random bits at all);
+ * Comparison strategies of Section 5.1 / Section 1 that carry an auxiliary tensor `aux`:
+ *   REF_FLAG_MASTER_FP32  : O2-style mixed precision: aux = binary32 master parameters,
+ *                           updated in binary32 and stored unrounded; m, v binary32
+ *                           (FP32_MOMENTS must be set); p = RNE(master) is the BF16 model copy;
+ *   REF_FLAG_KAHAN        : BF16 + Kahan summation on the parameter (Zamirai et al., cited in
+ *                           Section 1): aux = BF16 compensation c.  With the step's total
+ *                           update s (so that the plain result would be p - s):
+ *                             yk = (-s) - c;  t = p + yk;  p' = RNE(t);
+ *                             c' = RNE((p' - p) - yk);   m, v written back with RNE.
  * Element i of the tensor uses RNG index elem_offset + i. */
-void ref_sr_adamw_tensor(uint16_t* p, const uint16_t* g, void* m, void* v,
+void ref_sr_adamw_tensor(uint16_t* p, const uint16_t* g, void* m, void* v, void* aux,
                          uint64_t numel, uint32_t tensor_id, uint64_t elem_offset,
                          const ref_scalars_t* s, uint32_t step, uint64_t seed,
                          uint32_t flags, int nthreads)
 {
-    const int fp32m = (flags & REF_FLAG_FP32_MOMENTS) != 0;
-    const int rnem  = (flags & REF_FLAG_RNE_MOMENTS) != 0;
+    const int fp32m  = (flags & REF_FLAG_FP32_MOMENTS) != 0;
+    const int master = (flags & REF_FLAG_MASTER_FP32) != 0;
+    const int kahan  = (flags & REF_FLAG_KAHAN) != 0;
+    const int rnem   = kahan || (flags & REF_FLAG_RNE_MOMENTS) != 0;
+    const int rnep   = (flags & REF_FLAG_RNE_PARAMS) != 0;
 #ifdef _OPENMP
     if (nthreads > 0) omp_set_num_threads(nthreads);
 #endif
@@ -314,13 +333,30 @@ void ref_sr_adamw_tensor(uint16_t* p, const uint16_t* g, void* m, void* v,
     for (int64_t ii = 0; ii < (int64_t)numel; ++ii) {
         uint64_t i = (uint64_t)ii;
         uint64_t gi = elem_offset + i;
-        float pi = bf16_bits_to_float(p[i]);
+        float pi = master ? ((float*)aux)[i] : bf16_bits_to_float(p[i]);
         float gr = bf16_bits_to_float(g[i]);
         float mi = fp32m ? ((float*)m)[i] : bf16_bits_to_float(((uint16_t*)m)[i]);
         float vi = fp32m ? ((float*)v)[i] : bf16_bits_to_float(((uint16_t*)v)[i]);
-        float y, m1, v1;
-        adamw_element(s, pi, gr, mi, vi, &y, &m1, &v1);
-        p[i] = ref_sr_round(y, ref_r16(seed, step, tensor_id, gi, 0u));
+        float y, m1, v1, sum;
+        adamw_element(s, pi, gr, mi, vi, &y, &m1, &v1, &sum);
+        if (master) {
+            ((float*)aux)[i] = y;
+            p[i] = ref_rne_round(y);
+        } else if (kahan) {
+            float c  = bf16_bits_to_float(((uint16_t*)aux)[i]);
+            float ns = -sum;
+            float yk = ns - c;
+            float t  = pi + yk;
+            uint16_t pn = ref_rne_round(t);
+            float d1 = bf16_bits_to_float(pn) - pi;
+            float cn = d1 - yk;
+            p[i] = pn;
+            ((uint16_t*)aux)[i] = ref_rne_round(cn);
+        } else if (rnep) {
+            p[i] = ref_rne_round(y);
+        } else {
+            p[i] = ref_sr_round(y, ref_r16(seed, step, tensor_id, gi, 0u));
+        }
         if (fp32m) {
             ((float*)m)[i] = m1;
             ((float*)v)[i] = v1;
