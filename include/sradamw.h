@@ -35,7 +35,8 @@ extern "C" {
 #define SR_ERR_NULL      (-1)  /* a required pointer is NULL                              */
 #define SR_ERR_ARG       (-2)  /* step == 0, beta outside [0,1), eps < 0, non-finite
                                   hyper-parameter, max_norm <= 0 with clipping, unknown
-                                  flag, non-zero reserved field, index range overflow     */
+                                  or incompatible flags, non-zero reserved field, index
+                                  range overflow                                          */
 #define SR_ERR_WORKSPACE (-3)  /* workspace NULL, misaligned (8 bytes) or too small       */
 #define SR_ERR_ALIGN     (-4)  /* a BF16 pointer not 2-byte / an FP32 pointer not 4-byte
                                   aligned (16-byte misalignment is NOT an error: such
@@ -49,6 +50,22 @@ extern "C" {
 #define SR_FLAG_RNE_MOMENTS  2u /* BF16 m, v written back with round-to-nearest-even,
                                    Eq.(1): the paper's own setting, SR on line 10 only.
                                    Ignored together with SR_FLAG_FP32_MOMENTS.             */
+#define SR_FLAG_RNE_PARAMS   4u /* the parameter write-back is round-to-nearest-even too;
+                                   with SR_FLAG_RNE_MOMENTS this is the "BF16" strategy of
+                                   Section 5.1 (every tensor BF16, default rounding): no
+                                   random bits are drawn                                   */
+/* Comparison strategies that carry an auxiliary tensor in sr_tensor_t.aux (Section 5.1
+   "Baselines" and the related work of Section 1).  Each must be the only flag set, except
+   that SR_FLAG_MASTER_FP32 requires SR_FLAG_FP32_MOMENTS.                                 */
+#define SR_FLAG_MASTER_FP32  8u /* O2-style mixed precision: aux = binary32 master
+                                   parameters [numel], updated in binary32 and stored
+                                   unrounded; m, v binary32; p (BF16, write-only) receives
+                                   RNE(master), the model copy                             */
+#define SR_FLAG_KAHAN       16u /* BF16 + Kahan summation on the parameter: aux = BF16
+                                   compensation c [numel] (in/out, start it at zero).  With
+                                   s the step's total update (plain result p - s):
+                                   yk = (-s) - c; t = p + yk; p <- RNE(t);
+                                   c <- RNE((p_new - p) - yk); m, v written with RNE       */
 
 /* One tensor of the multi-tensor list. */
 typedef struct sr_tensor {
@@ -56,6 +73,9 @@ typedef struct sr_tensor {
     const void* g;           /* BF16 [numel], in    : reduced gradient (Alg.1 line 4)     */
     void*       m;           /* BF16 or binary32 [numel], in/out: first moment            */
     void*       v;           /* same type as m, in/out: second moment                     */
+    void*       aux;         /* NULL unless a flag names it: binary32 master parameters
+                                (SR_FLAG_MASTER_FP32) or BF16 Kahan compensation
+                                (SR_FLAG_KAHAN), in/out                                   */
     uint64_t    numel;       /* may be 0 (tensor skipped); may exceed 2^32                */
     uint64_t    elem_offset; /* index of element 0 in the RNG counter; 0 for a whole
                                 tensor, the shard's start for a slice of a larger one     */

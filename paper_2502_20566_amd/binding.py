@@ -17,6 +17,9 @@ SR_OK = 0
 SR_ERR_NULL, SR_ERR_ARG, SR_ERR_WORKSPACE, SR_ERR_ALIGN, SR_ERR_HIP = -1, -2, -3, -4, -5
 SR_FLAG_FP32_MOMENTS = 1
 SR_FLAG_RNE_MOMENTS = 2
+SR_FLAG_RNE_PARAMS = 4
+SR_FLAG_MASTER_FP32 = 8
+SR_FLAG_KAHAN = 16
 
 EXPORTS = ("sr_cast_f32_bf16", "grad_global_norm", "sr_adamw_step", "sr_workspace_bytes",
            "sr_strerror", "sr_last_hip_error", "sr_version")
@@ -24,7 +27,7 @@ EXPORTS = ("sr_cast_f32_bf16", "grad_global_norm", "sr_adamw_step", "sr_workspac
 
 class SrTensor(C.Structure):
     _fields_ = [("p", C.c_void_p), ("g", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
-                ("numel", C.c_uint64), ("elem_offset", C.c_uint64),
+                ("aux", C.c_void_p), ("numel", C.c_uint64), ("elem_offset", C.c_uint64),
                 ("tensor_id", C.c_uint32), ("reserved", C.c_uint32)]
 
 
@@ -97,7 +100,10 @@ class TensorList:
     def __init__(self, params: Sequence[torch.Tensor], grads: Sequence[torch.Tensor],
                  ms: Sequence[torch.Tensor], vs: Sequence[torch.Tensor], fp32_moments: bool = False,
                  tensor_ids: Optional[Sequence[int]] = None,
-                 elem_offsets: Optional[Sequence[int]] = None):
+                 elem_offsets: Optional[Sequence[int]] = None,
+                 aux: Optional[Sequence[torch.Tensor]] = None):
+        """aux: per-tensor auxiliary arrays for the comparison strategies -- float32 master
+        parameters (SR_FLAG_MASTER_FP32) or bfloat16 Kahan compensation (SR_FLAG_KAHAN)."""
         n = len(params)
         if not (len(grads) == len(ms) == len(vs) == n):
             raise ValueError("params, grads, ms, vs must have the same length")
@@ -105,7 +111,10 @@ class TensorList:
         self.fp32_moments = fp32_moments
         self.n = n
         self.array = (SrTensor * max(n, 1))()
-        self.keep = (list(params), list(grads), list(ms), list(vs))
+        self.keep = (list(params), list(grads), list(ms), list(vs), None if aux is None else list(aux))
+        self.aux_dtype = None if aux is None else aux[0].dtype if len(aux) else None
+        if aux is not None and len(aux) != n:
+            raise ValueError("aux must have one entry per tensor")
         self.total_numel = 0
         for i in range(n):
             p, g, m, v = params[i], grads[i], ms[i], vs[i]
@@ -117,6 +126,15 @@ class TensorList:
                 raise ValueError(f"tensor {i}: p, g, m, v differ in size")
             e = self.array[i]
             e.p, e.g, e.m, e.v = p.data_ptr(), g.data_ptr(), m.data_ptr(), v.data_ptr()
+            e.aux = None
+            if aux is not None:
+                a = aux[i]
+                if a.dtype not in (torch.float32, torch.bfloat16):
+                    raise ValueError(f"aux[{i}] must be float32 or bfloat16")
+                _check_dev(a, a.dtype, f"aux[{i}]")
+                if a.numel() != p.numel() or a.dtype != aux[0].dtype:
+                    raise ValueError(f"aux[{i}] differs in size or dtype")
+                e.aux = a.data_ptr()
             e.numel = p.numel()
             e.elem_offset = 0 if elem_offsets is None else int(elem_offsets[i])
             e.tensor_id = i if tensor_ids is None else int(tensor_ids[i])
@@ -161,6 +179,10 @@ def sr_adamw_step(tl: TensorList, hyper: dict, step: int, seed: int, flags: int 
     grad_global_norm, or None for no clipping."""
     if bool(flags & SR_FLAG_FP32_MOMENTS) != tl.fp32_moments:
         raise ValueError("SR_FLAG_FP32_MOMENTS does not match the moment dtype of the list")
+    if (flags & SR_FLAG_MASTER_FP32) and tl.n and tl.aux_dtype != torch.float32:
+        raise ValueError("SR_FLAG_MASTER_FP32 needs float32 aux tensors in the list")
+    if (flags & SR_FLAG_KAHAN) and tl.n and tl.aux_dtype != torch.bfloat16:
+        raise ValueError("SR_FLAG_KAHAN needs bfloat16 aux tensors in the list")
     h = SrHyper(hyper["lr"], hyper["beta1"], hyper["beta2"], hyper["eps"], hyper["weight_decay"])
     nptr = None
     if grad_norm is not None:

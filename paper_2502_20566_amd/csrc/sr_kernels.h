@@ -19,7 +19,7 @@ namespace sr {
 #define SR_TUNE_THREADS 64
 #endif
 constexpr int kThreads = SR_TUNE_THREADS;   // lanes per workgroup of the update and cast kernels
-constexpr int kMaxBatch = 64;          // tensors per update launch (argument segment <= 4 KiB;
+constexpr int kMaxBatch = 56;          // tensors per update launch (argument segment <= 4 KiB;
                                        // larger segments were measured and are not faster)
 // Norm, first pass: measured on MI355X, 512-lane workgroups with 16 blocks per lane and
 // nontemporal loads read at 7.1 TB/s (the read-only ceiling); plain loads reach 6.1 TB/s.
@@ -38,6 +38,7 @@ struct TensorDesc {
     const uint16_t* g;
     void* m;
     void* v;
+    void* aux;
     uint64_t numel;
     uint64_t elem_offset;
     uint32_t tensor_id;
@@ -209,33 +210,26 @@ __device__ __forceinline__ uint32_t find_tensor(const uint32_t* start, uint32_t 
 
 // ---------------------------------------------------------------------------- fused update
 
-// Registers of one 8-element block on its way through the update.
-template <bool FP32M>
-struct BlockRegs {
-    v4u p, g, mq, vq;          // packed BF16 pairs (mq, vq unused with FP32M)
-    float mf[8], vf[8];        // binary32 moments (FP32M only)
+// Variant of the step, from the ABI's flag bits (same values as SR_FLAG_* in sradamw.h).
+template <uint32_t F>
+struct Mode {
+    static constexpr bool fp32m  = (F & 1u) != 0;                 // binary32 moments, stored unrounded
+    static constexpr bool master = (F & 8u) != 0;                 // aux = binary32 master parameters
+    static constexpr bool kahan  = (F & 16u) != 0;                // aux = BF16 Kahan compensation
+    static constexpr bool rnem   = !fp32m && (kahan || (F & 2u)); // BF16 moments rounded to nearest
+    static constexpr bool rnep   = master || kahan || (F & 4u);   // BF16 parameter rounded to nearest
+    static constexpr bool srm    = !fp32m && !rnem;               // BF16 moments stochastically rounded
+    static constexpr bool aux    = master || kahan;
+    static constexpr bool half   = fp32m;                         // fast path: a lane owns half a block
 };
 
-// The 128 random bits of each output stream of one block (rm, rv only for SR'd BF16 moments).
-struct BlockBits { u32x4 rp, rm, rv; };
-
-template <bool FP32M, bool RNEM>
-__device__ __forceinline__ BlockBits draw_block_bits(const StepScalars& S, uint64_t gblk, uint32_t tensor_id)
-{
-    BlockBits b;
-    b.rp = block_bits(gblk, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
-    if (!FP32M && !RNEM) {
-        b.rm = block_bits(gblk, STREAM_M, tensor_id, S.step, S.seed_lo, S.seed_hi);
-        b.rv = block_bits(gblk, STREAM_V, tensor_id, S.step, S.seed_lo, S.seed_hi);
-    }
-    return b;
-}
-
-// Algorithm 1 lines 5-10 for one element.  In: p, g, m, v.  Out: y = unrounded new parameter,
-// m and v replaced by the unrounded new moments.  One rounding per operation, in this order (no
-// contraction: the library is built with -ffp-contract=off; sqrt and divide are correctly rounded).
+// Algorithm 1 lines 5-10 for one element.  In: p, g, m, v.  Out: sum = lr u + (lr wd) p and
+// y = p - sum (the unrounded new parameter); m and v are replaced by the unrounded new moments.
+// One rounding per operation, in this order (no contraction: the library is built with
+// -ffp-contract=off; sqrt and divide are correctly rounded).
 template <bool CLIP>
-__device__ __forceinline__ void update_elem(const StepScalars& S, float c, float p, float g, float& m, float& v, float& y)
+__device__ __forceinline__ void update_elem(const StepScalars& S, float c, float p, float g,
+                                            float& m, float& v, float& y, float& sum)
 {
     const float g1 = CLIP ? g * c : g;
     const float t1 = S.beta1 * m;
@@ -251,80 +245,149 @@ __device__ __forceinline__ void update_elem(const StepScalars& S, float c, float
     const float q = mh / d;
     const float a = S.lr * q;
     const float w = S.lw * p;
-    const float sum = a + w;
+    sum = a + w;
     y = p - sum;
     m = m1;
     v = v1;
 }
 
-// The update on the eight elements of one block, then the write-back roundings.
-// In: R as loaded.  Out: R.p (and R.mq, R.vq, or R.mf, R.vf) hold what is to be stored.
-template <bool FP32M, bool RNEM, bool CLIP>
-__device__ __forceinline__ void update_block(BlockRegs<FP32M>& R, const StepScalars& S, float c,
-                                             const BlockBits& bits)
+// The N (8 or 4) elements a lane owns, as binary32 values, and what it will store.
+template <int N>
+struct LaneRegs {
+    float p[N], g[N], m[N], v[N], aux[N];      // in; m, v (binary32 moments) and aux (master) also out
+    uint32_t po[N / 2], mo[N / 2], vo[N / 2], ao[N / 2];   // out: packed BF16 pairs (p; BF16 m, v; Kahan c)
+};
+
+// The update of a lane's N elements and the write-back roundings.  pw, mw, vw: the random words of
+// the lane's elements for the three output streams (16 bits per element; only read where the mode
+// rounds stochastically).
+template <uint32_t F, bool CLIP, int N>
+__device__ __forceinline__ void update_lane(LaneRegs<N>& L, const StepScalars& S, float c,
+                                            const uint32_t* pw, const uint32_t* mw, const uint32_t* vw)
 {
-    float p[8], g[8], m[8], v[8], y[8];
-    unpack8(R.p, p);
-    unpack8(R.g, g);
-    if (FP32M) {
+    using M = Mode<F>;
+    float y[N], sum[N];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { m[j] = R.mf[j]; v[j] = R.vf[j]; }
-    } else {
-        unpack8(R.mq, m);
-        unpack8(R.vq, v);
-    }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) update_elem<CLIP>(S, c, p[j], g[j], m[j], v[j], y[j]);
+    for (int j = 0; j < N; ++j)
+        update_elem<CLIP>(S, c, M::master ? L.aux[j] : L.p[j], L.g[j], L.m[j], L.v[j], y[j], sum[j]);
     // A NaN in m' or v' always makes y NaN, so one test covers all three outputs.
-    const bool nan = any_nan8(y);
-    R.p = nan ? sr8<true>(y, bits.rp) : sr8<false>(y, bits.rp);
-    if (FP32M) {
+    bool nan = false;
+    if (!M::rnep || M::srm) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { R.mf[j] = m[j]; R.vf[j] = v[j]; }
-    } else if (RNEM) {
-        R.mq.x = rne_pair(m[0], m[1]); R.mq.y = rne_pair(m[2], m[3]);
-        R.mq.z = rne_pair(m[4], m[5]); R.mq.w = rne_pair(m[6], m[7]);
-        R.vq.x = rne_pair(v[0], v[1]); R.vq.y = rne_pair(v[2], v[3]);
-        R.vq.z = rne_pair(v[4], v[5]); R.vq.w = rne_pair(v[6], v[7]);
+        for (int j = 0; j < N; ++j) nan |= (y[j] != y[j]);
+    }
+    if (M::master) {
+        // O2-style mixed precision: the master stays binary32, the model copy is RNE(master)
+#pragma unroll
+        for (int j = 0; j < N; ++j) L.aux[j] = y[j];
+#pragma unroll
+        for (int j = 0; j < N / 2; ++j) L.po[j] = rne_pair(y[2 * j], y[2 * j + 1]);
+    } else if (M::kahan) {
+        // Kahan summation on the parameter with BF16 sum and BF16 compensation c:
+        // yk = (-s) - c;  t = p + yk;  p' = RNE(t);  c' = RNE((p' - p) - yk)
+        uint32_t pn[N];
+        float cn[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const float ns = -sum[j];
+            const float yk = ns - L.aux[j];
+            const float t = L.p[j] + yk;
+            pn[j] = rne_one(t) & 0xFFFF0000u;
+            const float d1 = __uint_as_float(pn[j]) - L.p[j];
+            cn[j] = d1 - yk;
+        }
+#pragma unroll
+        for (int j = 0; j < N / 2; ++j) {
+            L.po[j] = pack_high_halves(pn[2 * j], pn[2 * j + 1]);
+            L.ao[j] = rne_pair(cn[2 * j], cn[2 * j + 1]);
+        }
+    } else if (M::rnep) {
+#pragma unroll
+        for (int j = 0; j < N / 2; ++j) L.po[j] = rne_pair(y[2 * j], y[2 * j + 1]);
     } else {
-        R.mq = nan ? sr8<true>(m, bits.rm) : sr8<false>(m, bits.rm);
-        R.vq = nan ? sr8<true>(v, bits.rv) : sr8<false>(v, bits.rv);
+#pragma unroll
+        for (int j = 0; j < N / 2; ++j)
+            L.po[j] = nan ? sr_pair_nan_safe(y[2 * j], y[2 * j + 1], pw[j]) : sr_pair(y[2 * j], y[2 * j + 1], pw[j]);
+    }
+    if (M::rnem) {
+#pragma unroll
+        for (int j = 0; j < N / 2; ++j) {
+            L.mo[j] = rne_pair(L.m[2 * j], L.m[2 * j + 1]);
+            L.vo[j] = rne_pair(L.v[2 * j], L.v[2 * j + 1]);
+        }
+    } else if (M::srm) {
+#pragma unroll
+        for (int j = 0; j < N / 2; ++j) {
+            L.mo[j] = nan ? sr_pair_nan_safe(L.m[2 * j], L.m[2 * j + 1], mw[j]) : sr_pair(L.m[2 * j], L.m[2 * j + 1], mw[j]);
+            L.vo[j] = nan ? sr_pair_nan_safe(L.v[2 * j], L.v[2 * j + 1], vw[j]) : sr_pair(L.v[2 * j], L.v[2 * j + 1], vw[j]);
+        }
     }
 }
 
-template <bool FP32M, bool NT>
-__device__ __forceinline__ void load_block(BlockRegs<FP32M>& R, const TensorDesc& T, int64_t l0, bool full)
+__device__ __forceinline__ void unpack4(v2u x, float (&out)[4])
 {
-    R.p = load8_bf16<NT>(T.p, l0, T.numel, full);
-    R.g = load8_bf16<NT>(T.g, l0, T.numel, full);
-    if (FP32M) {
-        load8_f32<NT>(static_cast<const float*>(T.m), l0, T.numel, full, R.mf);
-        load8_f32<NT>(static_cast<const float*>(T.v), l0, T.numel, full, R.vf);
-    } else {
-        R.mq = load8_bf16<NT>(static_cast<const uint16_t*>(T.m), l0, T.numel, full);
-        R.vq = load8_bf16<NT>(static_cast<const uint16_t*>(T.v), l0, T.numel, full);
-    }
+    out[0] = bf16_lo(x.x); out[1] = bf16_hi(x.x); out[2] = bf16_lo(x.y); out[3] = bf16_hi(x.y);
 }
-
-template <bool FP32M, bool NT>
-__device__ __forceinline__ void store_block(const BlockRegs<FP32M>& R, const TensorDesc& T, int64_t l0, bool full)
+__device__ __forceinline__ void floats4(v4u x, float (&out)[4])
 {
-    store8_bf16<NT>(T.p, l0, T.numel, full, R.p);
-    if (FP32M) {
-        store8_f32<NT>(static_cast<float*>(T.m), l0, T.numel, full, R.mf);
-        store8_f32<NT>(static_cast<float*>(T.v), l0, T.numel, full, R.vf);
+    out[0] = __uint_as_float(x.x); out[1] = __uint_as_float(x.y);
+    out[2] = __uint_as_float(x.z); out[3] = __uint_as_float(x.w);
+}
+__device__ __forceinline__ v4u bits4(const float (&x)[4])
+{
+    v4u r;
+    r.x = __float_as_uint(x[0]); r.y = __float_as_uint(x[1]);
+    r.z = __float_as_uint(x[2]); r.w = __float_as_uint(x[3]);
+    return r;
+}
+__device__ __forceinline__ v4u words4(const uint32_t (&w)[4]) { v4u r; r.x = w[0]; r.y = w[1]; r.z = w[2]; r.w = w[3]; return r; }
+__device__ __forceinline__ v2u words2(const uint32_t (&w)[2]) { v2u r; r.x = w[0]; r.y = w[1]; return r; }
+
+// General path for one whole block of a lane: element-wise access with bounds, any alignment,
+// any element offset.  Same arithmetic, same counter blocks as the fast paths.
+template <uint32_t F, bool CLIP>
+__device__ __forceinline__ void general_block(const TensorDesc& T, const StepScalars& S, float c,
+                                              uint64_t gblk, int64_t l0)
+{
+    using M = Mode<F>;
+    const uint64_t numel = T.numel;
+    LaneRegs<8> L;
+    if (!M::master) unpack8(load8_bf16<false>(T.p, l0, numel, false), L.p);
+    unpack8(load8_bf16<false>(T.g, l0, numel, false), L.g);
+    if (M::fp32m) {
+        load8_f32<false>(static_cast<const float*>(T.m), l0, numel, false, L.m);
+        load8_f32<false>(static_cast<const float*>(T.v), l0, numel, false, L.v);
     } else {
-        store8_bf16<NT>(static_cast<uint16_t*>(T.m), l0, T.numel, full, R.mq);
-        store8_bf16<NT>(static_cast<uint16_t*>(T.v), l0, T.numel, full, R.vq);
+        unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.m), l0, numel, false), L.m);
+        unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.v), l0, numel, false), L.v);
     }
+    if (M::master) load8_f32<false>(static_cast<const float*>(T.aux), l0, numel, false, L.aux);
+    if (M::kahan) unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.aux), l0, numel, false), L.aux);
+    u32x4 rp = {}, rm = {}, rv = {};
+    if (!M::rnep) rp = block_bits(gblk, STREAM_P, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+    if (M::srm) {
+        rm = block_bits(gblk, STREAM_M, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+        rv = block_bits(gblk, STREAM_V, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+    }
+    update_lane<F, CLIP, 8>(L, S, c, rp.w, rm.w, rv.w);
+    store8_bf16<false>(T.p, l0, numel, false, words4(L.po));
+    if (M::fp32m) {
+        store8_f32<false>(static_cast<float*>(T.m), l0, numel, false, L.m);
+        store8_f32<false>(static_cast<float*>(T.v), l0, numel, false, L.v);
+    } else {
+        store8_bf16<false>(static_cast<uint16_t*>(T.m), l0, numel, false, words4(L.mo));
+        store8_bf16<false>(static_cast<uint16_t*>(T.v), l0, numel, false, words4(L.vo));
+    }
+    if (M::master) store8_f32<false>(static_cast<float*>(T.aux), l0, numel, false, L.aux);
+    if (M::kahan) store8_bf16<false>(static_cast<uint16_t*>(T.aux), l0, numel, false, words4(L.ao));
 }
 
-// FP32M: binary32 moments stored unrounded (SR on p only).  RNEM: BF16 moments rounded to nearest.
-// CLIP: scale gradients by min(1, max_norm/(norm + 1e-6)).  U: blocks per lane.  NT: nontemporal
-// loads and stores.
-template <bool FP32M, bool RNEM, bool CLIP, int U, bool NT>
+// F: SR_FLAG_* bits of the step.  CLIP: scale gradients by min(1, max_norm/(norm + 1e-6)).
+// NT: nontemporal loads and stores.  One wave per workgroup, one chunk per workgroup.
+template <uint32_t F, bool CLIP, bool NT>
 __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
 {
+    using M = Mode<F>;
     const uint32_t chunk = blockIdx.x;
     const uint32_t ti = find_tensor(B.chunk_start, B.s.n_tensors, chunk);
     const TensorDesc& T = B.t[ti];
@@ -335,6 +398,7 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
     const bool vec = (T.flags & DESC_VEC) != 0;
     const uint32_t tensor_id = T.tensor_id;
     const StepScalars& S = B.s;
+    const uint64_t cl = chunk - B.chunk_start[ti];                  // chunk index inside the tensor
 
     float c = 1.0f;
     if (CLIP) {
@@ -342,86 +406,77 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
         if (c > 1.0f) c = 1.0f;
     }
 
-    if constexpr (FP32M) {
-        // Binary32 moments: a lane owns HALF a block (4 elements), so that every access of the wave
-        // is one contiguous run (p, g: 8 bytes per lane; m, v: 16 bytes per lane) and a wave issues
-        // only four loads and three stores -- measured 16% faster than whole blocks per lane, whose
-        // binary32 accesses would be strided.  The two lanes of a block draw the same Philox block
-        // and each uses its half.  A chunk is kThreads*4 elements = kThreads/2 blocks.
-        // (The same ownership was measured for BF16 moments, with the three Philox blocks of a lane
-        // pair shared through DPP: 5% slower than whole blocks, so BF16 moments keep whole blocks.)
-        const uint64_t cl = chunk - B.chunk_start[ti];
+    if constexpr (M::half) {
+        // Binary32 moments (and master parameters): a lane owns HALF a block (4 elements), so that
+        // every access of the wave is one contiguous run (BF16 arrays: 8 bytes per lane; binary32
+        // arrays: 16 bytes per lane) and a wave issues few, short accesses -- measured 16% faster
+        // than whole blocks per lane, whose binary32 accesses would be strided.  The two lanes of
+        // a block draw the same Philox block and each uses its half.  A chunk is kThreads*4
+        // elements = kThreads/2 blocks.  (For BF16 moments the same ownership, with the three
+        // Philox blocks of a lane pair shared through DPP, was measured 5% slower than whole
+        // blocks: BF16 moments keep whole blocks.)
         const uint64_t efirst = cl * (uint64_t)(kThreads * 4);
         if (vec && efirst + (uint64_t)(kThreads * 4) <= numel) {          // wave-uniform
             const uint64_t e = efirst + (uint64_t)threadIdx.x * 4;
             float* mp = static_cast<float*>(T.m) + e;
             float* vp = static_cast<float*>(T.v) + e;
-            const v2u Pq = load_v2<NT>(T.p + e), Gq = load_v2<NT>(T.g + e);
-            const v4u Mq = load_v4<NT>(mp), Vq = load_v4<NT>(vp);
-            const u32x4 r = block_bits((G0 + e) >> 3, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
-            const bool upper = (threadIdx.x & 1u) != 0;                    // elements 4..7 of the block
-            const uint32_t w0 = upper ? r.w[2] : r.w[0], w1 = upper ? r.w[3] : r.w[1];
-            const float p[4] = {bf16_lo(Pq.x), bf16_hi(Pq.x), bf16_lo(Pq.y), bf16_hi(Pq.y)};
-            const float g[4] = {bf16_lo(Gq.x), bf16_hi(Gq.x), bf16_lo(Gq.y), bf16_hi(Gq.y)};
-            float m[4] = {__uint_as_float(Mq.x), __uint_as_float(Mq.y), __uint_as_float(Mq.z), __uint_as_float(Mq.w)};
-            float v[4] = {__uint_as_float(Vq.x), __uint_as_float(Vq.y), __uint_as_float(Vq.z), __uint_as_float(Vq.w)};
-            float y[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) update_elem<CLIP>(S, c, p[j], g[j], m[j], v[j], y[j]);
-            const bool nan = (y[0] != y[0]) | (y[1] != y[1]) | (y[2] != y[2]) | (y[3] != y[3]);
-            v2u po;
-            if (nan) { po.x = sr_pair_nan_safe(y[0], y[1], w0); po.y = sr_pair_nan_safe(y[2], y[3], w1); }
-            else     { po.x = sr_pair(y[0], y[1], w0);          po.y = sr_pair(y[2], y[3], w1); }
-            v4u mo, vo;
-            mo.x = __float_as_uint(m[0]); mo.y = __float_as_uint(m[1]); mo.z = __float_as_uint(m[2]); mo.w = __float_as_uint(m[3]);
-            vo.x = __float_as_uint(v[0]); vo.y = __float_as_uint(v[1]); vo.z = __float_as_uint(v[2]); vo.w = __float_as_uint(v[3]);
-            store_v2<NT>(T.p + e, po);
-            store_v4<NT>(mp, mo);
-            store_v4<NT>(vp, vo);
+            float* xp = static_cast<float*>(T.aux) + e;                    // master parameters
+            LaneRegs<4> L;
+            if (M::master) floats4(load_v4<NT>(xp), L.aux);
+            else unpack4(load_v2<NT>(T.p + e), L.p);
+            unpack4(load_v2<NT>(T.g + e), L.g);
+            floats4(load_v4<NT>(mp), L.m);
+            floats4(load_v4<NT>(vp), L.v);
+            uint32_t pw[2] = {0, 0};
+            if (!M::rnep) {
+                const u32x4 r = block_bits((G0 + e) >> 3, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
+                const bool upper = (threadIdx.x & 1u) != 0;                // elements 4..7 of the block
+                pw[0] = upper ? r.w[2] : r.w[0];
+                pw[1] = upper ? r.w[3] : r.w[1];
+            }
+            update_lane<F, CLIP, 4>(L, S, c, pw, pw, pw);
+            store_v2<NT>(T.p + e, words2(L.po));
+            store_v4<NT>(mp, bits4(L.m));
+            store_v4<NT>(vp, bits4(L.v));
+            if (M::master) store_v4<NT>(xp, bits4(L.aux));
             return;
         }
-        // General path (tails, misaligned pointers, element offsets that are not multiples of 8):
-        // the chunk's kThreads/2 blocks, one whole block per lane, element-wise access.
+        // General path: the chunk's kThreads/2 blocks, one whole block per lane.
         const uint64_t b = cl * (uint64_t)(kThreads / 2) + threadIdx.x;
         if (threadIdx.x >= kThreads / 2 || b >= nblk) return;
-        const int64_t l0 = (int64_t)((gblk0 + b) << 3) - (int64_t)G0;
-        BlockRegs<FP32M> R;
-        load_block<FP32M, false>(R, T, l0, false);
-        update_block<FP32M, RNEM, CLIP>(R, S, c, draw_block_bits<FP32M, RNEM>(S, gblk0 + b, tensor_id));
-        store_block<FP32M, false>(R, T, l0, false);
-        return;
-    }
-
-    const uint64_t bfirst = (uint64_t)(chunk - B.chunk_start[ti]) * (uint64_t)(kThreads * U) + threadIdx.x;
-    const uint64_t blast = bfirst + (uint64_t)(U - 1) * kThreads;
-
-    // Fast path: every block of this lane is a whole, 16-byte aligned vector inside the tensor
-    // (with DESC_VEC, elem_offset is a multiple of 8, so block b starts at element 8 b).
-    if (vec && ((blast << 3) + 8 <= numel)) {
-        BlockRegs<FP32M> R[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            load_block<FP32M, NT>(R[u], T, (int64_t)((bfirst + (uint64_t)u * kThreads) << 3), true);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint64_t b = bfirst + (uint64_t)u * kThreads;
-            update_block<FP32M, RNEM, CLIP>(R[u], S, c, draw_block_bits<FP32M, RNEM>(S, gblk0 + b, tensor_id));
-            store_block<FP32M, NT>(R[u], T, (int64_t)(b << 3), true);
+        general_block<F, CLIP>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b) << 3) - (int64_t)G0);
+    } else {
+        // BF16 moments: a lane owns one whole block; a chunk is kThreads blocks.
+        const uint64_t b = cl * (uint64_t)kThreads + threadIdx.x;
+        if (vec && ((b << 3) + 8 <= numel)) {
+            // whole 16-byte aligned vectors (with DESC_VEC, elem_offset is a multiple of 8, so
+            // block b starts at element 8 b)
+            const uint64_t e = b << 3;
+            uint16_t* mp = static_cast<uint16_t*>(T.m) + e;
+            uint16_t* vp = static_cast<uint16_t*>(T.v) + e;
+            uint16_t* cp = static_cast<uint16_t*>(T.aux) + e;              // Kahan compensation
+            LaneRegs<8> L;
+            const v4u Pq = load_v4<NT>(T.p + e), Gq = load_v4<NT>(T.g + e);
+            const v4u Mq = load_v4<NT>(mp), Vq = load_v4<NT>(vp);
+            v4u Cq = {};
+            if (M::kahan) Cq = load_v4<NT>(cp);
+            unpack8(Pq, L.p); unpack8(Gq, L.g); unpack8(Mq, L.m); unpack8(Vq, L.v);
+            if (M::kahan) unpack8(Cq, L.aux);
+            u32x4 rp = {}, rm = {}, rv = {};
+            if (!M::rnep) rp = block_bits(gblk0 + b, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
+            if (M::srm) {
+                rm = block_bits(gblk0 + b, STREAM_M, tensor_id, S.step, S.seed_lo, S.seed_hi);
+                rv = block_bits(gblk0 + b, STREAM_V, tensor_id, S.step, S.seed_lo, S.seed_hi);
+            }
+            update_lane<F, CLIP, 8>(L, S, c, rp.w, rm.w, rv.w);
+            store_v4<NT>(T.p + e, words4(L.po));
+            store_v4<NT>(mp, words4(L.mo));
+            store_v4<NT>(vp, words4(L.vo));
+            if (M::kahan) store_v4<NT>(cp, words4(L.ao));
+            return;
         }
-        return;
-    }
-
-    // General path: tensor tails, misaligned pointers, element offsets that are not multiples
-    // of 8.  Same arithmetic and the same counter blocks, element-wise memory access.
-    for (int u = 0; u < U; ++u) {
-        const uint64_t b = bfirst + (uint64_t)u * kThreads;
-        if (b >= nblk) break;
-        const int64_t l0 = (int64_t)((gblk0 + b) << 3) - (int64_t)G0;
-        const bool full = vec && ((uint64_t)l0 + 8 <= numel);
-        BlockRegs<FP32M> R;
-        load_block<FP32M, false>(R, T, l0, full);
-        update_block<FP32M, RNEM, CLIP>(R, S, c, draw_block_bits<FP32M, RNEM>(S, gblk0 + b, tensor_id));
-        store_block<FP32M, false>(R, T, l0, full);
+        if (b >= nblk) return;
+        general_block<F, CLIP>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b) << 3) - (int64_t)G0);
     }
 }
 

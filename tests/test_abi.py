@@ -28,6 +28,7 @@ def buf(nbytes: int, misalign: int = 0) -> int:
 def tensor(numel=64, **kw):
     t = B.SrTensor()
     t.p, t.g, t.m, t.v = buf(2 * numel), buf(2 * numel), buf(4 * numel), buf(4 * numel)
+    t.aux = None
     t.numel, t.elem_offset, t.tensor_id, t.reserved = numel, 0, 0, 0
     for k, v in kw.items():
         setattr(t, k, v)
@@ -49,7 +50,7 @@ def test_library_exports_every_declared_symbol():
     for name in declared:
         assert hasattr(L, name)
     assert L.sr_version() >= 100
-    assert C.sizeof(B.SrTensor) == 56 and C.sizeof(B.SrHyper) == 20
+    assert C.sizeof(B.SrTensor) == 64 and C.sizeof(B.SrHyper) == 20
 
 
 def test_strerror_covers_all_codes():
@@ -75,7 +76,15 @@ def test_adamw_argument_errors():
     assert step([t], hyper=(float("nan"), 0.9, 0.95, 1e-8, 0.1)) == B.SR_ERR_ARG
     assert step([t], hyper=(1e-3, 0.9, 0.95, float("inf"), 0.1)) == B.SR_ERR_ARG
     assert step([t], hyper=(1e-3, 0.9, 0.95, 1e-8, float("nan"))) == B.SR_ERR_ARG
-    assert step([t], flags=4) == B.SR_ERR_ARG
+    assert step([t], flags=32) == B.SR_ERR_ARG
+    # comparison strategies: exact flag combinations and an aux tensor are required
+    assert step([t], flags=B.SR_FLAG_MASTER_FP32) == B.SR_ERR_ARG
+    assert step([t], flags=B.SR_FLAG_KAHAN | B.SR_FLAG_FP32_MOMENTS) == B.SR_ERR_ARG
+    assert step([t], flags=B.SR_FLAG_KAHAN | B.SR_FLAG_MASTER_FP32 | B.SR_FLAG_FP32_MOMENTS) == B.SR_ERR_ARG
+    assert step([t], flags=B.SR_FLAG_KAHAN) == B.SR_ERR_NULL
+    assert step([t], flags=B.SR_FLAG_MASTER_FP32 | B.SR_FLAG_FP32_MOMENTS) == B.SR_ERR_NULL
+    assert step([tensor(aux=t.m + 1)], flags=B.SR_FLAG_KAHAN) == B.SR_ERR_ALIGN
+    assert step([tensor(aux=t.m + 2)], flags=B.SR_FLAG_MASTER_FP32 | B.SR_FLAG_FP32_MOMENTS) == B.SR_ERR_ALIGN
     assert step([tensor(reserved=1)]) == B.SR_ERR_ARG
     assert step([tensor(elem_offset=2 ** 64 - 8)]) == B.SR_ERR_ARG
     nrm = buf(4)

@@ -59,15 +59,18 @@ def assert_f32_parity(got: np.ndarray, want: np.ndarray, what: str):
 class Pair:
     """The same optimizer state on the device (library) and on the host (oracle)."""
 
-    def __init__(self, params, ms, vs, fp32_moments, tensor_ids=None, elem_offsets=None):
+    def __init__(self, params, ms, vs, fp32_moments, tensor_ids=None, elem_offsets=None, aux=None):
         self.fp32 = fp32_moments
-        self.p, self.m, self.v = params, ms, vs
+        self.p, self.m, self.v, self.aux = params, ms, vs, aux
         self.g = [torch.empty_like(p) for p in params]
         self.ids = list(range(len(params))) if tensor_ids is None else list(tensor_ids)
         self.offs = [0] * len(params) if elem_offsets is None else list(elem_offsets)
-        self.tl = B.TensorList(self.p, self.g, self.m, self.v, fp32_moments, self.ids, self.offs)
+        self.tl = B.TensorList(self.p, self.g, self.m, self.v, fp32_moments, self.ids, self.offs, aux)
         self.host = [dict(p=to_np(p), m=to_np(m), v=to_np(v), tensor_id=i, elem_offset=o)
                      for p, m, v, i, o in zip(params, ms, vs, self.ids, self.offs)]
+        if aux is not None:
+            for h, a in zip(self.host, aux):
+                h["aux"] = to_np(a)
         self.norm = torch.zeros(1, dtype=torch.float32, device=DEV)
         self.ws = torch.empty(max(self.tl.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
 
@@ -100,6 +103,12 @@ class Pair:
             else:
                 assert_bf16_parity(to_np(self.m[i]), h["m"], f"{what} m[{i}]")
                 assert_bf16_parity(to_np(self.v[i]), h["v"], f"{what} v[{i}]")
+            if self.aux is not None:
+                got = to_np(self.aux[i])
+                if got.dtype == np.uint16:
+                    assert_bf16_parity(got, h["aux"], f"{what} aux[{i}]")
+                else:
+                    assert_f32_parity(got, h["aux"], f"{what} aux[{i}]")
 
 
 def make_pair(cfg: W.Config, shapes=None):
@@ -262,12 +271,16 @@ def _random_state(n, seed, fp32=False):
     return p, gr, m, v
 
 
-@pytest.mark.parametrize("fp32", [False, True])
-def test_adamw_ragged_misaligned_and_offset_tensors(fp32):
+@pytest.mark.parametrize("mode", ["sr", "fp32", "nearest", "kahan", "master"])
+def test_adamw_ragged_misaligned_and_offset_tensors(mode):
     """Sizes around the 8-element block and the chunk size, views that start 2 bytes off a
-    16-byte boundary, element offsets that are not multiples of 8: same bits as the oracle."""
-    sizes = [1, 7, 8, 9, 15, 17, 511, 512, 513, 1000, 4096, 4097, 2 * 256 * 8 + 3, 40000]
-    params, grads, ms, vs, offs = [], [], [], [], []
+    16-byte boundary, element offsets that are not multiples of 8: same bits as the oracle,
+    for every variant of the step."""
+    fp32 = mode in ("fp32", "master")
+    flags = {"sr": 0, "fp32": 0, "nearest": B.SR_FLAG_RNE_PARAMS | B.SR_FLAG_RNE_MOMENTS,
+             "kahan": B.SR_FLAG_KAHAN, "master": B.SR_FLAG_MASTER_FP32}[mode]
+    sizes = [1, 7, 8, 9, 15, 17, 255, 256, 257, 511, 512, 513, 1000, 4096, 4097, 2 * 256 * 8 + 3, 40000]
+    params, grads, ms, vs, offs, aux = [], [], [], [], [], []
     for i, n in enumerate(sizes):
         shift = i % 3                                     # 0: aligned, 1 or 2 elements off
         p, g, m, v = _random_state(n + 8, 100 + i, fp32)
@@ -275,15 +288,62 @@ def test_adamw_ragged_misaligned_and_offset_tensors(fp32):
         mshift = shift if i % 2 == 0 else (shift + 1) % 3   # moments sometimes aligned differently
         ms.append(m[mshift:mshift + n]); vs.append(v[shift:shift + n])
         offs.append([0, 8, 5, 1 << 33, (1 << 35) + 3][i % 5])
-    guards = [(t, to_np(t)) for t in params]
-    pair = Pair(params, ms, vs, fp32, tensor_ids=[7 * i + 1 for i in range(len(sizes))], elem_offsets=offs)
+        ashift = shift if i % 4 != 1 else (shift + 2) % 3
+        if mode == "kahan":
+            a = (torch.randn(n + 8, device=DEV) * 1e-5).to(torch.bfloat16)
+            aux.append(a[ashift:ashift + n])
+        elif mode == "master":
+            a = params[-1].float() + torch.randn(n, device=DEV) * 1e-5      # master near its BF16 copy
+            buf = torch.zeros(n + 8, device=DEV)
+            buf[ashift:ashift + n] = a
+            aux.append(buf[ashift:ashift + n])
+    pair = Pair(params, ms, vs, fp32, tensor_ids=[7 * i + 1 for i in range(len(sizes))], elem_offsets=offs,
+                aux=aux if aux else None)
     for g_dst, g_src in zip(pair.g, grads):
         g_dst.copy_(g_src)
     hyper = dict(lr=3e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
     for t in (1, 2):
-        pair.step(hyper, t, seed=0xDEADBEEFCAFE, clip=0.01)
-        pair.compare(f"ragged step {t}")
-    del guards
+        pair.step(hyper, t, seed=0xDEADBEEFCAFE, clip=0.01, flags=flags)
+        pair.compare(f"ragged {mode} step {t}")
+
+
+def _mode_run(flags, fp32, make_aux, steps=5, clip=None):
+    cfg = W.config(2)
+    shapes = W.gpt_shapes(72, 2, 200, 1003, 33)
+    params = W.make_params(shapes, DEV, W.data_seed(2, 0), cfg.param_std)
+    ms, vs = W.make_moments(shapes, DEV, fp32)
+    aux = make_aux(params) if make_aux else None
+    pair = Pair(params, ms, vs, fp32, aux=aux)
+    for t in range(1, steps + 1):
+        W.fill_grads(pair.g, W.data_seed(2, t), 1e-3)
+        pair.step(cfg.hyper, t, 11, clip=clip, flags=flags)
+        pair.compare(f"flags {flags} step {t}")
+    return pair
+
+
+def test_adamw_all_nearest_bf16_strategy():
+    # Section 5.1's "BF16" strategy: every write-back rounded to nearest, no random bits
+    a = _mode_run(B.SR_FLAG_RNE_PARAMS | B.SR_FLAG_RNE_MOMENTS, False, None)
+    assert a is not None
+
+
+def test_adamw_nearest_parameter_with_stochastic_or_fp32_moments():
+    _mode_run(B.SR_FLAG_RNE_PARAMS, False, None, steps=3)
+    _mode_run(B.SR_FLAG_RNE_PARAMS, True, None, steps=3, clip=0.5)
+
+
+def test_adamw_fp32_master_weights():
+    # O2-style mixed precision: binary32 master and moments, BF16 model copy = RNE(master)
+    pair = _mode_run(B.SR_FLAG_MASTER_FP32, True, lambda ps: [p.float().clone() for p in ps], clip=0.5)
+    for i, h in enumerate(pair.host):
+        assert bool(np.all(to_np(pair.aux[i]) == h["aux"]))          # master agrees to the bit
+        want = torch.from_numpy(h["aux"]).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        assert bool(np.all(to_np(pair.p[i]) == want))
+
+
+def test_adamw_kahan_compensation():
+    pair = _mode_run(B.SR_FLAG_KAHAN, False, lambda ps: [torch.zeros_like(p) for p in ps], steps=6)
+    assert any(h["aux"].any() for h in pair.host)                     # compensation is in use
 
 
 def test_adamw_does_not_write_outside_its_tensors():
