@@ -22,27 +22,45 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published peak
 
 
-def algorithmic_bytes_per_element(cfg) -> int:
-    # BF16 p,g,m,v read + p,m,v written = 14; FP32 moments: 2+2+4+4 read, 2+4+4 written = 22;
-    # the norm pass reads the gradients once more.
-    b = 22 if cfg.fp32_moments else 14
-    return b + (2 if cfg.clip is not None else 0)
+# step variants: name -> (flags by name, FP32 moments, aux dtype, algorithmic bytes per element)
+#   sr            BF16 p,g,m,v read + p,m,v written                        8 + 6  = 14
+#   rne_moments   same traffic, moments rounded to nearest (the paper's own setting)
+#   nearest       same traffic, every write-back to nearest (the "BF16" strategy of Section 5.1)
+#   fp32_moments  2+2+4+4 read, 2+4+4 written                              12 + 10 = 22
+#   kahan         BF16 p,g,m,v,c read + p,m,v,c written                    10 + 8  = 18
+#   master        x32,g,m32,v32 read + x32,p16,m32,v32 written (O2 style)  14 + 14 = 28
+MODES = {
+    "sr": ((), False, None, 14),
+    "rne_moments": (("SR_FLAG_RNE_MOMENTS",), False, None, 14),
+    "nearest": (("SR_FLAG_RNE_PARAMS", "SR_FLAG_RNE_MOMENTS"), False, None, 14),
+    "fp32_moments": (("SR_FLAG_FP32_MOMENTS",), True, None, 22),
+    "kahan": (("SR_FLAG_KAHAN",), False, "bf16", 18),
+    "master": (("SR_FLAG_MASTER_FP32", "SR_FLAG_FP32_MOMENTS"), True, "f32", 28),
+}
 
 
-def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds):
+def algorithmic_bytes_per_element(mode, clip) -> int:
+    # the norm pass of a clipping config reads the gradients once more
+    return MODES[mode][3] + (2 if clip is not None else 0)
+
+
+def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags):
     """Time the CPU oracle (as it stands) on a bounded window of the same workload and check the
-    GPU against it on that window.  `state` holds flat device tensors p, g, m, v (first tensor)."""
+    GPU against it on that window.  `state` holds flat device tensors p, g, m, v, aux (first
+    tensor; aux may be None).  `flags`: the step's flag bits (same values on both sides)."""
     import numpy as np
     from oracle import ref
-    p, g, m, v = state
-    flags = ref.FLAG_FP32_MOMENTS if cfg.fp32_moments else 0
+    p, g, m, v, aux = state
     threads = min(ref.max_threads(), os.cpu_count() or 1)
 
     def window(lo, n):
         def cp(t):
             s = t[lo:lo + n]
             return W.bf16_to_u16_numpy(s) if s.dtype == torch.bfloat16 else s.cpu().numpy().copy()
-        return dict(p=cp(p), g=cp(g), m=cp(m), v=cp(v), tensor_id=0, elem_offset=lo)
+        d = dict(p=cp(p), g=cp(g), m=cp(m), v=cp(v), tensor_id=0, elem_offset=lo)
+        if aux is not None:
+            d["aux"] = cp(aux)
+        return d
 
     # calibrate on 2^21 elements, then size the sample for about `seconds` of CPU work
     n0 = min(1 << 21, p.numel())
@@ -68,6 +86,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5)
+    ap.add_argument("--mode", choices=sorted(MODES), default=None,
+                    help="step variant (default: the config's own: sr, or fp32_moments for config 4)")
     ap.add_argument("--warm-steps", type=int, default=None, help="seeded steps that warm the moments")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -91,12 +111,21 @@ def main():
     torch.cuda.set_device(0)
     cfg = W.config(args.config)
     warm = cfg.warm_steps if args.warm_steps is None else args.warm_steps
+    mode = args.mode or ("fp32_moments" if cfg.fp32_moments else "sr")
+    flag_names, fp32_moments, aux_kind, _ = MODES[mode]
+    flags = 0
+    for name in flag_names:
+        flags |= getattr(B, name)
 
     params = W.make_params(cfg.shapes, dev, W.data_seed(cfg.index, 0), cfg.param_std)
-    ms, vs = W.make_moments(cfg.shapes, dev, cfg.fp32_moments)
+    ms, vs = W.make_moments(cfg.shapes, dev, fp32_moments)
     grads = [torch.empty_like(p) for p in params]
-    tl = B.TensorList(params, grads, ms, vs, cfg.fp32_moments)
-    flags = B.SR_FLAG_FP32_MOMENTS if cfg.fp32_moments else 0
+    aux = None
+    if aux_kind == "f32":
+        aux = [p.float() for p in params]                 # binary32 master parameters
+    elif aux_kind == "bf16":
+        aux = [torch.zeros_like(p) for p in params]       # Kahan compensation starts at zero
+    tl = B.TensorList(params, grads, ms, vs, fp32_moments, aux=aux)
     norm = torch.zeros(1, dtype=torch.float32, device=dev)
     ws = torch.empty(max(tl.workspace_bytes(), 256), dtype=torch.uint8, device=dev)
     numel = tl.total_numel
@@ -122,8 +151,9 @@ def main():
     cpu = None
     check = None
     if not args.no_cpu_baseline:
-        cpu, check = cpu_baseline(W, B, torch, cfg, (params[0], grads[0], ms[0], vs[0]), t, cfg.seed,
-                                  args.cpu_seconds)
+        cpu, check = cpu_baseline(W, B, torch, cfg, (params[0], grads[0], ms[0], vs[0],
+                                                     None if aux is None else aux[0]), t, cfg.seed,
+                                  args.cpu_seconds, flags)
         if cfg.clip is not None:
             cpu["sample"] += " (oracle timed without the clip scale)"
 
@@ -135,9 +165,16 @@ def main():
         lo, n, w = check
         got_p = W.bf16_to_u16_numpy(params[0][lo:lo + n])
         bad = int((got_p != w["p"]).sum())
-        if not cfg.fp32_moments:
+        if fp32_moments:
+            bad += int((ms[0][lo:lo + n].cpu().numpy() != w["m"]).sum())
+            bad += int((vs[0][lo:lo + n].cpu().numpy() != w["v"]).sum())
+        else:
             bad += int((W.bf16_to_u16_numpy(ms[0][lo:lo + n]) != w["m"]).sum())
             bad += int((W.bf16_to_u16_numpy(vs[0][lo:lo + n]) != w["v"]).sum())
+        if aux_kind == "f32":
+            bad += int((aux[0][lo:lo + n].cpu().numpy() != w["aux"]).sum())
+        elif aux_kind == "bf16":
+            bad += int((W.bf16_to_u16_numpy(aux[0][lo:lo + n]) != w["aux"]).sum())
         parity = "bit-exact" if bad == 0 else f"{bad} mismatches"
         del got_p
         t += 1
@@ -168,13 +205,13 @@ def main():
         dst.copy_(src)                                    # 2^30 bytes read, 2^30 bytes written
         torch.cuda.synchronize()
 
-    bpe = algorithmic_bytes_per_element(cfg)
+    bpe = algorithmic_bytes_per_element(mode, cfg.clip)
     value = numel * args.steps / wall
     achieved = bpe * numel / (dev_avg_ms * 1e-3) / 1e9
     # HBM bytes per launch measured with rocprofv3 PMC counters (see the summary under profiles/)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"adamw_kernel_config{cfg.index}_hbm_traffic.txt")
-    if os.path.exists(tpath):
+    if mode == "sr" and os.path.exists(tpath):
         for line in open(tpath):
             if line.startswith("hbm_bytes_per_launch"):
                 traffic = int(line.split("=")[1])
@@ -193,7 +230,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}", "numel": numel, "tensors": len(params),
-                   "moments": "fp32" if cfg.fp32_moments else "bf16", "clip": cfg.clip,
+                   "mode": mode, "moments": "fp32" if fp32_moments else "bf16", "clip": cfg.clip,
                    "warm_steps": warm, "bytes_per_element": bpe},
         "hbm_GBps": bpe * numel / (ms_per_step * 1e-3) / 1e9,
         "pct_of_hbm_peak": 100.0 * bpe * numel / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
