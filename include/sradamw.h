@@ -67,6 +67,15 @@ extern "C" {
                                    yk = (-s) - c; t = p + yk; p <- RNE(t);
                                    c <- RNE((p_new - p) - yk); m, v written with RNE       */
 
+/* Variants of the arithmetic; combine with any of the above. */
+#define SR_FLAG_EPS_IN_ROOT 32u /* denominator sqrt(v' rbc2 + eps) instead of
+                                   sqrt(v' rbc2) + eps: eps inside the root, the form of the
+                                   update in Appendix B                                    */
+#define SR_FLAG_DIV_BIAS    64u /* bias corrections as the divisions of Algorithm 1 lines
+                                   7-8 as printed, m'/(1-beta1^t) and v'/(1-beta2^t) with
+                                   1-beta^t formed in binary64 and rounded once, instead of
+                                   multiplications by the rounded reciprocals              */
+
 /* One tensor of the multi-tensor list. */
 typedef struct sr_tensor {
     void*       p;           /* BF16 [numel], in/out: parameters x_t                      */

@@ -19,13 +19,16 @@ FLAG_RNE_MOMENTS = 2
 FLAG_RNE_PARAMS = 4
 FLAG_MASTER_FP32 = 8
 FLAG_KAHAN = 16
+FLAG_EPS_IN_ROOT = 32
+FLAG_DIV_BIAS = 64
 
 STREAM_PARAM, STREAM_M, STREAM_V, STREAM_CAST = 0, 1, 2, 3
 
 
 class Scalars(C.Structure):
     _fields_ = [(n, C.c_float) for n in
-                ("beta1", "beta2", "omb1", "omb2", "rbc1", "rbc2", "lr", "eps", "lw", "clip")]
+                ("beta1", "beta2", "omb1", "omb2", "rbc1", "rbc2", "lr", "eps", "lw", "clip",
+                 "bc1", "bc2")]
 
 
 _lib = None

@@ -48,6 +48,8 @@
 #define REF_FLAG_RNE_PARAMS   4u
 #define REF_FLAG_MASTER_FP32  8u
 #define REF_FLAG_KAHAN       16u
+#define REF_FLAG_EPS_IN_ROOT 32u
+#define REF_FLAG_DIV_BIAS    64u
 
 /* ---------------------------------------------------------------- RNG --- */
 
@@ -218,6 +220,7 @@ typedef struct {
     float lr, eps;        /* as given                                            */
     float lw;             /* lr * weight_decay, formed in double, rounded once   */
     float clip;           /* gradient scale c (1 when clipping is off)           */
+    float bc1, bc2;       /* 1 - beta^t, formed in double, rounded once          */
 } ref_scalars_t;
 
 static double pow_uint(double base, uint32_t e)
@@ -243,6 +246,8 @@ void ref_adamw_scalars(float lr, float beta1, float beta2, float eps, float weig
     s->omb2 = (float)(1.0 - (double)beta2);
     s->rbc1 = (float)(1.0 / (1.0 - pow_uint((double)beta1, step)));
     s->rbc2 = (float)(1.0 / (1.0 - pow_uint((double)beta2, step)));
+    s->bc1 = (float)(1.0 - pow_uint((double)beta1, step));
+    s->bc2 = (float)(1.0 - pow_uint((double)beta2, step));
     s->lr = lr; s->eps = eps;
     s->lw = (float)((double)lr * (double)weight_decay);
     s->clip = 1.0f;
@@ -256,7 +261,7 @@ void ref_adamw_scalars(float lr, float beta1, float beta2, float eps, float weig
 
 /* One element of Algorithm 1 lines 5-10 before the write-back rounding:
  * returns the unrounded new parameter y and the unrounded moments m1, v1. */
-static void adamw_element(const ref_scalars_t* s, float p, float g, float m, float v,
+static void adamw_element(const ref_scalars_t* s, uint32_t flags, float p, float g, float m, float v,
                           float* y_out, float* m1_out, float* v1_out, float* sum_out)
 {
     float g1 = g * s->clip;
@@ -269,11 +274,16 @@ static void adamw_element(const ref_scalars_t* s, float p, float g, float m, flo
     float t3 = s->beta2 * v;
     float t4 = s->omb2 * gg;
     float v1 = t3 + t4;
-    /* lines 7-8: bias corrections (as multiplications by host reciprocals) */
-    float mh = m1 * s->rbc1;
-    float vh = v1 * s->rbc2;
-    /* line 10: x - (alpha mhat/(sqrt(vhat) + eps) + alpha lambda x) */
-    float d = sqrtf(vh) + s->eps;
+    /* lines 7-8: bias corrections: multiplications by host reciprocals, or, with
+     * REF_FLAG_DIV_BIAS, the divisions by 1 - beta^t as the lines are printed */
+    float mh, vh;
+    if (flags & REF_FLAG_DIV_BIAS) { mh = m1 / s->bc1; vh = v1 / s->bc2; }
+    else                           { mh = m1 * s->rbc1; vh = v1 * s->rbc2; }
+    /* line 10: x - (alpha mhat/(sqrt(vhat) + eps) + alpha lambda x); with
+     * REF_FLAG_EPS_IN_ROOT the denominator is sqrt(vhat + eps), the form of Appendix B */
+    float d;
+    if (flags & REF_FLAG_EPS_IN_ROOT) { float ve = vh + s->eps; d = sqrtf(ve); }
+    else                              { d = sqrtf(vh) + s->eps; }
     float u = mh / d;
     float a = s->lr * u;
     float b = s->lw * p;
@@ -293,7 +303,7 @@ void ref_adamw_unrounded(const uint16_t* p, const uint16_t* g, const void* m, co
     for (uint64_t i = 0; i < numel; ++i) {
         float mi = fp32m ? ((const float*)m)[i] : bf16_bits_to_float(((const uint16_t*)m)[i]);
         float vi = fp32m ? ((const float*)v)[i] : bf16_bits_to_float(((const uint16_t*)v)[i]);
-        adamw_element(s, bf16_bits_to_float(p[i]), bf16_bits_to_float(g[i]), mi, vi,
+        adamw_element(s, flags, bf16_bits_to_float(p[i]), bf16_bits_to_float(g[i]), mi, vi,
                       &y[i], &m1[i], &v1[i], NULL);
     }
 }
@@ -315,6 +325,8 @@ void ref_adamw_unrounded(const uint16_t* p, const uint16_t* g, const void* m, co
  *                           update s (so that the plain result would be p - s):
  *                             yk = (-s) - c;  t = p + yk;  p' = RNE(t);
  *                             c' = RNE((p' - p) - yk);   m, v written back with RNE.
+ * Variants of the arithmetic (any strategy): REF_FLAG_EPS_IN_ROOT, REF_FLAG_DIV_BIAS, see
+ * adamw_element.
  * Element i of the tensor uses RNG index elem_offset + i. */
 void ref_sr_adamw_tensor(uint16_t* p, const uint16_t* g, void* m, void* v, void* aux,
                          uint64_t numel, uint32_t tensor_id, uint64_t elem_offset,
@@ -338,7 +350,7 @@ void ref_sr_adamw_tensor(uint16_t* p, const uint16_t* g, void* m, void* v, void*
         float mi = fp32m ? ((float*)m)[i] : bf16_bits_to_float(((uint16_t*)m)[i]);
         float vi = fp32m ? ((float*)v)[i] : bf16_bits_to_float(((uint16_t*)v)[i]);
         float y, m1, v1, sum;
-        adamw_element(s, pi, gr, mi, vi, &y, &m1, &v1, &sum);
+        adamw_element(s, flags, pi, gr, mi, vi, &y, &m1, &v1, &sum);
         if (master) {
             ((float*)aux)[i] = y;
             p[i] = ref_rne_round(y);

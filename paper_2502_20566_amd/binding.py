@@ -20,6 +20,8 @@ SR_FLAG_RNE_MOMENTS = 2
 SR_FLAG_RNE_PARAMS = 4
 SR_FLAG_MASTER_FP32 = 8
 SR_FLAG_KAHAN = 16
+SR_FLAG_EPS_IN_ROOT = 32
+SR_FLAG_DIV_BIAS = 64
 
 EXPORTS = ("sr_cast_f32_bf16", "grad_global_norm", "sr_adamw_step", "sr_workspace_bytes",
            "sr_strerror", "sr_last_hip_error", "sr_version")

@@ -47,9 +47,13 @@ struct TensorDesc {
 
 struct StepScalars {
     float beta1, beta2, omb1, omb2, rbc1, rbc2, lr, eps, lw, max_norm;
+    float bc1, bc2;                        // 1 - beta^t (used by the divide-by-bias-correction variant)
     const float* d_norm;
     uint32_t seed_lo, seed_hi, step, n_tensors;
+    uint32_t variant;                      // VARIANT_* bits: wave-uniform choices of the arithmetic
+    uint32_t pad_;
 };
+enum : uint32_t { VARIANT_EPS_IN_ROOT = 1u, VARIANT_DIV_BIAS = 2u };
 
 struct AdamwBatch {
     StepScalars s;
@@ -239,9 +243,14 @@ __device__ __forceinline__ void update_elem(const StepScalars& S, float c, float
     const float t3 = S.beta2 * v;
     const float t4 = S.omb2 * gg;
     const float v1 = t3 + t4;
-    const float mh = m1 * S.rbc1;
-    const float vh = v1 * S.rbc2;
-    const float d = __builtin_sqrtf(vh) + S.eps;
+    // Bias corrections as multiplications by host reciprocals, or (variant) the divisions of
+    // Algorithm 1 lines 7-8 as printed; eps outside the root, or (variant) inside it as in
+    // Appendix B.  The variant bits are kernel arguments: the branches are wave-uniform.
+    float mh, vh, d;
+    if (S.variant & VARIANT_DIV_BIAS) { mh = m1 / S.bc1; vh = v1 / S.bc2; }
+    else                              { mh = m1 * S.rbc1; vh = v1 * S.rbc2; }
+    if (S.variant & VARIANT_EPS_IN_ROOT) { const float ve = vh + S.eps; d = __builtin_sqrtf(ve); }
+    else                                 { d = __builtin_sqrtf(vh) + S.eps; }
     const float q = mh / d;
     const float a = S.lr * q;
     const float w = S.lw * p;

@@ -173,8 +173,14 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     if (!hyper) return SR_ERR_NULL;
     if (n_tensors && !tensors) return SR_ERR_NULL;
     if (step == 0) return SR_ERR_ARG;
-    if (flags & ~(SR_FLAG_FP32_MOMENTS | SR_FLAG_RNE_MOMENTS | SR_FLAG_RNE_PARAMS | SR_FLAG_MASTER_FP32 | SR_FLAG_KAHAN))
+    if (flags & ~(SR_FLAG_FP32_MOMENTS | SR_FLAG_RNE_MOMENTS | SR_FLAG_RNE_PARAMS | SR_FLAG_MASTER_FP32 |
+                  SR_FLAG_KAHAN | SR_FLAG_EPS_IN_ROOT | SR_FLAG_DIV_BIAS))
         return SR_ERR_ARG;
+    // variants of the arithmetic combine with any strategy and do not select a kernel
+    uint32_t variant = 0;
+    if (flags & SR_FLAG_EPS_IN_ROOT) variant |= VARIANT_EPS_IN_ROOT;
+    if (flags & SR_FLAG_DIV_BIAS) variant |= VARIANT_DIV_BIAS;
+    flags &= ~(SR_FLAG_EPS_IN_ROOT | SR_FLAG_DIV_BIAS);
     if ((flags & SR_FLAG_MASTER_FP32) && flags != (SR_FLAG_MASTER_FP32 | SR_FLAG_FP32_MOMENTS)) return SR_ERR_ARG;
     if ((flags & SR_FLAG_KAHAN) && flags != SR_FLAG_KAHAN) return SR_ERR_ARG;
     const sr_hyper_t h = *hyper;
@@ -217,6 +223,9 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     S.omb2 = (float)(1.0 - (double)h.beta2);
     S.rbc1 = (float)(1.0 / (1.0 - pow_uint((double)h.beta1, step)));
     S.rbc2 = (float)(1.0 / (1.0 - pow_uint((double)h.beta2, step)));
+    S.bc1 = (float)(1.0 - pow_uint((double)h.beta1, step));
+    S.bc2 = (float)(1.0 - pow_uint((double)h.beta2, step));
+    S.variant = variant;
     S.lr = h.lr;
     S.eps = h.eps;
     S.lw = (float)((double)h.lr * (double)h.weight_decay);

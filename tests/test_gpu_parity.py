@@ -341,6 +341,16 @@ def test_adamw_fp32_master_weights():
         assert bool(np.all(to_np(pair.p[i]) == want))
 
 
+@pytest.mark.parametrize("variant", [B.SR_FLAG_EPS_IN_ROOT, B.SR_FLAG_DIV_BIAS,
+                                     B.SR_FLAG_EPS_IN_ROOT | B.SR_FLAG_DIV_BIAS])
+def test_adamw_arithmetic_variants(variant):
+    # eps inside the root (Appendix B's form) and divisions by 1 - beta^t (lines 7-8 as printed),
+    # on the default strategy, with FP32 moments + clip, and with Kahan
+    _mode_run(variant, False, None, steps=4)
+    _mode_run(variant, True, None, steps=3, clip=0.5)
+    _mode_run(variant | B.SR_FLAG_KAHAN, False, lambda ps: [torch.zeros_like(p) for p in ps], steps=3)
+
+
 def test_adamw_kahan_compensation():
     pair = _mode_run(B.SR_FLAG_KAHAN, False, lambda ps: [torch.zeros_like(p) for p in ps], steps=6)
     assert any(h["aux"].any() for h in pair.host)                     # compensation is in use

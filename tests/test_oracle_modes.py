@@ -171,3 +171,85 @@ def test_kahan_single_step_algebra():
     ref.sr_adamw_step([dict(p=pp, g=g, m=mm, v=vv, aux=cc)], HYP, 3, 0, ref.FLAG_KAHAN)
     assert bool(np.all(pp == pn)) and bool(np.all(cc == cn))
     assert bool(np.all(mm == torch_rne_bits(m1))) and bool(np.all(vv == torch_rne_bits(v1)))
+
+
+# ------------------------------------------------ variants of the arithmetic
+
+def _alg1_exact_variant(p, g, m, v, hyper, t, eps_in_root):
+    """Lines 5-10 in exact rational arithmetic (60-digit decimal root); eps outside the root
+    (standard AdamW) or inside it (the form used in Appendix B)."""
+    import decimal
+    from fractions import Fraction
+    decimal.getcontext().prec = 60
+    b1, b2, lr, eps, wd = (Fraction(float(f32(hyper[k]))) for k in ("beta1", "beta2", "lr", "eps", "weight_decay"))
+    P, G, M, V = (Fraction(float(x)) for x in (p, g, m, v))
+    m1 = b1 * M + (1 - b1) * G
+    v1 = b2 * V + (1 - b2) * G * G
+    mhat = m1 / (1 - b1 ** t)
+    vhat = v1 / (1 - b2 ** t)
+    arg = vhat + eps if eps_in_root else vhat
+    root = Fraction((decimal.Decimal(arg.numerator) / decimal.Decimal(arg.denominator)).sqrt())
+    den = root if eps_in_root else root + eps
+    return float(P - (lr * mhat / den + lr * wd * P))
+
+
+@pytest.mark.parametrize("flags", [ref.FLAG_EPS_IN_ROOT, ref.FLAG_DIV_BIAS, ref.FLAG_EPS_IN_ROOT | ref.FLAG_DIV_BIAS])
+def test_arithmetic_variants_against_exact_evaluation(flags):
+    n = 16
+    rng = np.random.default_rng(20)
+    p = trunc_bits(rng.standard_normal(n) * 0.02)
+    g = trunc_bits(rng.standard_normal(n) * 1e-5)          # small gradients: eps placement matters
+    m = (rng.standard_normal(n) * 1e-5).astype(np.float32)
+    v = (rng.random(n) * 1e-10).astype(np.float32)
+    hyper = dict(HYP, eps=1e-6)
+    for t in (1, 7):
+        s = ref.adamw_scalars(step=t, **hyper)
+        y, _, _ = ref.adamw_unrounded(p, g, m, v, s, flags=flags | ref.FLAG_FP32_MOMENTS)
+        y_std, _, _ = ref.adamw_unrounded(p, g, m, v, s, flags=ref.FLAG_FP32_MOMENTS)
+        inside = bool(flags & ref.FLAG_EPS_IN_ROOT)
+        for i in range(n):
+            want = _alg1_exact_variant(val(p)[i], val(g)[i], m[i], v[i], hyper, t, inside)
+            upd = abs(float(val(p)[i]) - want)
+            assert abs(float(y[i]) - want) <= 0.5 * float(np.spacing(f32(abs(want)))) + 16 * 2.0 ** -24 * upd
+        if inside:
+            # with gradients this small the two placements of eps give clearly different updates
+            assert float(np.max(np.abs(y - y_std))) > 1e-5
+        else:
+            # dividing by 1 - beta^t instead of multiplying by its reciprocal: a few roundings apart
+            assert bool(np.all(np.abs(y - y_std) <= 4 * np.spacing(np.abs(y_std)) + 1e-9))
+            assert bool(np.any(y != y_std)) or t == 1
+
+
+def test_eps_inside_root_step1_closed_form():
+    # m = v = 0, step 1: the update is lr g / sqrt(g^2 + eps)
+    n = 2048
+    rng = np.random.default_rng(21)
+    p = trunc_bits(rng.standard_normal(n) * 0.02)
+    g = trunc_bits(rng.standard_normal(n) * 1e-4)
+    z = np.zeros(n, np.uint16)
+    hyper = dict(HYP, eps=1e-8, weight_decay=0.0)
+    s = ref.adamw_scalars(step=1, **hyper)
+    y, _, _ = ref.adamw_unrounded(p, g, z, z, s, flags=ref.FLAG_EPS_IN_ROOT)
+    pv, gv = val(p).astype(np.float64), val(g).astype(np.float64)
+    upd = float(f32(hyper["lr"])) * gv / np.sqrt(gv * gv + float(f32(1e-8)))
+    want = pv - upd
+    assert bool(np.all(np.abs(y - want) <= 0.5 * np.spacing(np.abs(want).astype(np.float32)) + 16 * 2.0 ** -24 * np.abs(upd)))
+    assert float(np.median(np.abs(upd))) > 1e-3
+
+
+def test_variants_flow_through_the_full_step():
+    n = 1024
+    rng = np.random.default_rng(22)
+    p0 = trunc_bits(rng.standard_normal(n) * 0.02)
+    g = trunc_bits(rng.standard_normal(n) * 1e-5)
+    z = np.zeros(n, np.uint16)
+    outs = {}
+    for flags in (0, ref.FLAG_EPS_IN_ROOT, ref.FLAG_DIV_BIAS):
+        pp, mm, vv = p0.copy(), z.copy(), z.copy()
+        ref.sr_adamw_step([dict(p=pp, g=g, m=mm, v=vv)], dict(HYP, eps=1e-6), 3, 5, flags)
+        s = ref.adamw_scalars(step=3, **dict(HYP, eps=1e-6))
+        y, _, _ = ref.adamw_unrounded(p0, g, z, z, s, flags=flags)
+        lo = (y.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+        assert bool(np.all((pp == lo) | (pp == lo + 1)))     # the step rounds this variant's y
+        outs[flags] = pp
+    assert bool(np.any(outs[0] != outs[ref.FLAG_EPS_IN_ROOT]))
