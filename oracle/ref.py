@@ -22,7 +22,9 @@ FLAG_KAHAN = 16
 FLAG_EPS_IN_ROOT = 32
 FLAG_DIV_BIAS = 64
 
-STREAM_PARAM, STREAM_M, STREAM_V, STREAM_CAST = 0, 1, 2, 3
+STREAM_PARAM, STREAM_M, STREAM_V, STREAM_CAST, STREAM_ACC = 0, 1, 2, 3, 4
+ACC_RNE = 1
+ACC_FIRST = 2
 
 
 class Scalars(C.Structure):
@@ -68,6 +70,9 @@ def lib():
                                           C.c_uint32, C.c_uint64, C.POINTER(Scalars),
                                           C.c_uint32, C.c_uint64, C.c_uint32, C.c_int]
         L.ref_sr_adamw_tensor.restype = None
+        L.ref_grad_accumulate.argtypes = [u16p, u16p, C.c_uint64, C.c_float, C.c_uint32, C.c_uint64,
+                                          C.c_uint32, C.c_uint64, C.c_uint32, C.c_int]
+        L.ref_grad_accumulate.restype = None
         L.ref_grad_global_norm.argtypes = [C.POINTER(u16p), C.POINTER(C.c_uint64), C.c_uint32]
         L.ref_grad_global_norm.restype = C.c_float
         L.ref_max_threads.argtypes = []
@@ -216,6 +221,13 @@ def sr_adamw_step(tensors, hyper, step, seed, flags=0, norm=None, max_norm=0.0, 
         sr_adamw_tensor(t["p"], t["g"], t["m"], t["v"], t.get("tensor_id", idx), s, step, seed,
                         flags, t.get("elem_offset", 0), nthreads, aux=t.get("aux"))
     return s
+
+
+def grad_accumulate(acc, g, scale, micro_step, seed, tensor_id=0, elem_offset=0, flags=0, nthreads=0):
+    """acc <- Q(acc + scale*g) in place (numpy uint16 BF16 bit patterns)."""
+    assert acc.size == g.size
+    lib().ref_grad_accumulate(_u16(acc), _u16(g), acc.size, scale, micro_step, seed, tensor_id,
+                              elem_offset, flags, nthreads)
 
 
 def grad_global_norm(grads) -> float:

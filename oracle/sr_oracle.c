@@ -382,6 +382,35 @@ void ref_sr_adamw_tensor(uint16_t* p, const uint16_t* g, void* m, void* v, void*
     }
 }
 
+/* ------------------------------------------------ gradient accumulation --- */
+
+#define REF_ACC_RNE   1u   /* round the accumulator to nearest-even instead of stochastically */
+#define REF_ACC_FIRST 2u   /* first micro-batch: the old accumulator is not read (taken as 0)  */
+
+/* BF16 gradient accumulation over micro-batches with a stochastically rounded write-back
+ * (every tensor stays BF16, Section 3; fewer or more accumulation steps are the knob Section 5.2
+ * "Memory" mentions).  Per element, binary32, one rounding per operation:
+ *     t = scale * g;   s = acc + t;   acc <- Q_SR(s)
+ * with the random bits of output stream 4 and `micro_step` in the counter's step word.
+ * Element i uses RNG index elem_offset + i. */
+void ref_grad_accumulate(uint16_t* acc, const uint16_t* g, uint64_t numel, float scale,
+                         uint32_t micro_step, uint64_t seed, uint32_t tensor_id,
+                         uint64_t elem_offset, uint32_t flags, int nthreads)
+{
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+    #pragma omp parallel for schedule(static)
+    for (int64_t ii = 0; ii < (int64_t)numel; ++ii) {
+        uint64_t i = (uint64_t)ii;
+        float a = (flags & REF_ACC_FIRST) ? 0.0f : bf16_bits_to_float(acc[i]);
+        float t = scale * bf16_bits_to_float(g[i]);
+        float s = a + t;
+        acc[i] = (flags & REF_ACC_RNE) ? ref_rne_round(s)
+                                       : ref_sr_round(s, ref_r16(seed, micro_step, tensor_id, elem_offset + i, 4u));
+    }
+}
+
 /* ------------------------------------------------------ gradient norm --- */
 
 /* Global L2 norm over a list of BF16 gradient tensors: sum of squares in

@@ -161,3 +161,20 @@ def test_config5_full_size_windows_through_warm_start():
     # after the warm start the second moment is alive and updates are far below a BF16 spacing
     v_end = ref.bf16_bits_to_f32(win.host[0]["v"])
     assert float((v_end > 0).mean()) > 0.99
+
+
+def test_cast_every_binary32_encoding():
+    """All 2^32 binary32 encodings (every exponent, subnormal, infinity and NaN payload), each with
+    the draw its index gets: the GPU cast equals the by-value oracle bit for bit."""
+    chunk = 1 << 28
+    bad = 0
+    for c in range(16):
+        bits = torch.arange(c * chunk, (c + 1) * chunk, dtype=torch.int64, device=DEV).to(torch.int32)  # wraps
+        x = bits.view(torch.float32)
+        out = torch.empty(chunk, dtype=torch.bfloat16, device=DEV)
+        B.sr_cast_f32_bf16(x, out, 0x5EED, 1 + c, 3)
+        torch.cuda.synchronize()
+        want = ref.sr_cast_f32_bf16(x.cpu().numpy(), 0x5EED, 1 + c, 3)
+        bad += int((to_np(out) != want).sum())
+        del bits, x, out
+    assert bad == 0
