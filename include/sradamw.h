@@ -152,6 +152,47 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
                   uint32_t step, uint64_t seed, uint32_t flags,
                   const float* d_grad_norm, float max_norm, void* stream);
 
+/* One accumulator/gradient pair of a multi-tensor gradient accumulation. */
+typedef struct sr_accum {
+    void*       acc;         /* BF16 [numel], in/out: accumulated gradient                 */
+    const void* grad;        /* BF16 [numel], in    : this micro-batch's gradient          */
+    uint64_t    numel;       /* may be 0                                                   */
+    uint64_t    elem_offset; /* index of element 0 in the RNG counter (as in sr_tensor_t)  */
+    uint32_t    tensor_id;   /* RNG counter word                                           */
+    uint32_t    reserved;    /* must be 0                                                  */
+} sr_accum_t;
+
+#define SR_ACC_RNE   1u      /* round the accumulator to nearest-even instead of SR        */
+#define SR_ACC_FIRST 2u      /* first micro-batch: acc is not read (taken as zero)         */
+
+/*
+ * BF16 gradient accumulation over micro-batches with a stochastically rounded
+ * write-back, and (optionally) the global norm of the result in the same pass.
+ * "Every tensor in BF16" (Section 3) includes the gradient buffer that micro-
+ * batches accumulate into (gradient accumulation steps: Section 5.2 "Memory");
+ * nearest rounding would stop accumulating once acc dwarfs the micro-gradient
+ * (the x + u example of Section 2.1), SR does not in expectation.
+ * Per element, binary32, one rounding per operation:
+ *     t = scale * grad;  s = acc + t;  acc <- Q_SR(s)
+ * with the 16 random bits of element i from Philox4x32-10(counter = (i>>3 low
+ * word, 4<<29 | i>>3 high bits, tensor_id, micro_step), key = seed), i =
+ * elem_offset + index.  Give every accumulation call of a training run its
+ * own micro_step.
+ *   d_norm_out  NULL, or a device scalar that receives (float) sqrt(sum of
+ *               squares of the accumulator values written by this call), in
+ *               binary64, fixed summation tree -- the norm a following
+ *               sr_adamw_step clips with, at no extra pass over the gradients
+ *   d_workspace only used with d_norm_out: at least
+ *               sr_accumulate_workspace_bytes(n_tensors, total numel) bytes,
+ *               8-byte aligned
+ */
+int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scale,
+                       uint32_t micro_step, uint64_t seed, uint32_t flags, float* d_norm_out,
+                       void* d_workspace, uint64_t workspace_bytes, void* stream);
+
+/* Workspace bound for sr_grad_accumulate with a norm (multiple of 256). */
+uint64_t sr_accumulate_workspace_bytes(uint32_t n_tensors, uint64_t total_numel);
+
 /* Bytes of device workspace grad_global_norm needs for a list of n_tensors
  * tensors with total_numel elements in all (an upper bound, multiple of 256). */
 uint64_t sr_workspace_bytes(uint32_t n_tensors, uint64_t total_numel);

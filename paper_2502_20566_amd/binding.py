@@ -23,7 +23,11 @@ SR_FLAG_KAHAN = 16
 SR_FLAG_EPS_IN_ROOT = 32
 SR_FLAG_DIV_BIAS = 64
 
+SR_ACC_RNE = 1
+SR_ACC_FIRST = 2
+
 EXPORTS = ("sr_cast_f32_bf16", "grad_global_norm", "sr_adamw_step", "sr_workspace_bytes",
+           "sr_grad_accumulate", "sr_accumulate_workspace_bytes",
            "sr_strerror", "sr_last_hip_error", "sr_version")
 
 
@@ -31,6 +35,11 @@ class SrTensor(C.Structure):
     _fields_ = [("p", C.c_void_p), ("g", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
                 ("aux", C.c_void_p), ("numel", C.c_uint64), ("elem_offset", C.c_uint64),
                 ("tensor_id", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class SrAccum(C.Structure):
+    _fields_ = [("acc", C.c_void_p), ("grad", C.c_void_p), ("numel", C.c_uint64),
+                ("elem_offset", C.c_uint64), ("tensor_id", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class SrHyper(C.Structure):
@@ -68,6 +77,11 @@ def lib():
         L.sr_adamw_step.argtypes = [C.POINTER(SrTensor), C.c_uint32, C.POINTER(SrHyper), C.c_uint32,
                                     C.c_uint64, C.c_uint32, C.c_void_p, C.c_float, C.c_void_p]
         L.sr_adamw_step.restype = C.c_int
+        L.sr_grad_accumulate.argtypes = [C.POINTER(SrAccum), C.c_uint32, C.c_float, C.c_uint32, C.c_uint64,
+                                         C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+        L.sr_grad_accumulate.restype = C.c_int
+        L.sr_accumulate_workspace_bytes.argtypes = [C.c_uint32, C.c_uint64]
+        L.sr_accumulate_workspace_bytes.restype = C.c_uint64
         L.sr_workspace_bytes.argtypes = [C.c_uint32, C.c_uint64]
         L.sr_workspace_bytes.restype = C.c_uint64
         L.sr_strerror.argtypes = [C.c_int]
@@ -194,3 +208,49 @@ def sr_adamw_step(tl: TensorList, hyper: dict, step: int, seed: int, flags: int 
                              _stream_handle(stream))
     if rc != SR_OK:
         raise SrError(rc, "sr_adamw_step")
+
+
+class AccumList:
+    """A marshalled list of (accumulator, micro-batch gradient) pairs for sr_grad_accumulate."""
+
+    def __init__(self, accs: Sequence[torch.Tensor], grads: Sequence[torch.Tensor],
+                 tensor_ids: Optional[Sequence[int]] = None, elem_offsets: Optional[Sequence[int]] = None):
+        n = len(accs)
+        if len(grads) != n:
+            raise ValueError("accs and grads must have the same length")
+        self.n = n
+        self.array = (SrAccum * max(n, 1))()
+        self.keep = (list(accs), list(grads))
+        self.total_numel = 0
+        for i in range(n):
+            _check_dev(accs[i], torch.bfloat16, f"accs[{i}]")
+            _check_dev(grads[i], torch.bfloat16, f"grads[{i}]")
+            if accs[i].numel() != grads[i].numel():
+                raise ValueError(f"pair {i} differs in size")
+            e = self.array[i]
+            e.acc, e.grad, e.numel = accs[i].data_ptr(), grads[i].data_ptr(), accs[i].numel()
+            e.elem_offset = 0 if elem_offsets is None else int(elem_offsets[i])
+            e.tensor_id = i if tensor_ids is None else int(tensor_ids[i])
+            e.reserved = 0
+            self.total_numel += accs[i].numel()
+
+    def workspace_bytes(self) -> int:
+        return int(lib().sr_accumulate_workspace_bytes(self.n, self.total_numel))
+
+
+def sr_grad_accumulate(al: AccumList, scale: float, micro_step: int, seed: int, flags: int = 0,
+                       norm_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                       stream=None) -> None:
+    """acc <- Q(acc + scale*grad) for every pair; with norm_out (float32 device scalar) and a
+    workspace of al.workspace_bytes() bytes also the global norm of the result."""
+    nptr, wptr, wbytes = None, None, 0
+    if norm_out is not None:
+        _check_dev(norm_out, torch.float32, "norm_out")
+        if workspace is None or not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("a contiguous device workspace is needed with norm_out")
+        nptr, wptr = norm_out.data_ptr(), workspace.data_ptr()
+        wbytes = workspace.numel() * workspace.element_size()
+    rc = lib().sr_grad_accumulate(al.array, al.n, scale, micro_step, seed, flags, nptr, wptr, wbytes,
+                                  _stream_handle(stream))
+    if rc != SR_OK:
+        raise SrError(rc, "sr_grad_accumulate")

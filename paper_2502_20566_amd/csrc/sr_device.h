@@ -8,7 +8,7 @@
 namespace sr {
 
 // RNG output streams (top three bits of counter word 1).
-enum : uint32_t { STREAM_P = 0, STREAM_M = 1, STREAM_V = 2, STREAM_CAST = 3 };
+enum : uint32_t { STREAM_P = 0, STREAM_M = 1, STREAM_V = 2, STREAM_CAST = 3, STREAM_ACC = 4 };
 
 struct u32x4 { uint32_t w[4]; };
 

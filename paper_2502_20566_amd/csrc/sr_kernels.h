@@ -28,6 +28,10 @@ constexpr int kNormMaxBatch = 160;     // tensors per norm launch
 constexpr int kNormIters = 16;         // blocks per lane in the norm's first pass
 constexpr int kNormChunkElems = kNormThreads * 8 * kNormIters;
 constexpr int kFinalThreads = 1024;
+constexpr int kAccThreads = 256;       // lanes per workgroup of the gradient accumulation
+constexpr int kAccIters = 4;           // blocks per lane (one partial sum of squares per chunk)
+constexpr int kAccChunkElems = kAccThreads * 8 * kAccIters;
+constexpr int kAccMaxBatch = 88;       // tensors per accumulation launch
 
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
@@ -72,6 +76,24 @@ struct NormBatch {
     NormDesc t[kNormMaxBatch];
 };
 static_assert(sizeof(NormBatch) <= 4096, "kernel argument segment");
+
+struct AccDesc {
+    uint16_t* acc;
+    const uint16_t* g;
+    uint64_t numel;
+    uint64_t elem_offset;
+    uint32_t tensor_id;
+    uint32_t flags;                        // DESC_VEC
+};
+enum : uint32_t { ACC_RNE = 1u, ACC_FIRST = 2u, ACC_NORM = 4u };
+struct AccBatch {
+    float scale;
+    uint32_t seed_lo, seed_hi, micro_step, n_tensors, partial_base, mode, pad_;
+    uint32_t chunk_start[kAccMaxBatch + 1];
+    uint32_t pad2_;
+    AccDesc t[kAccMaxBatch];
+};
+static_assert(sizeof(AccBatch) <= 4096, "kernel argument segment");
 
 // ------------------------------------------------------------------ memory access helpers
 
@@ -534,6 +556,80 @@ __device__ __forceinline__ double wave_sum(double x)
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
     return x;                                   // lane 0 holds the wave's sum
+}
+
+// ----------------------------------------------------------------- gradient accumulation
+
+// acc <- Q(acc + scale g) over micro-batches, every tensor BF16: t = scale g; s = acc + t (one
+// rounding each); Q = stochastic rounding with output stream 4 and the micro-step in the counter,
+// or round-to-nearest.  With ACC_NORM each chunk also leaves the binary64 sum of squares of the
+// values it wrote, so the global norm of the accumulated gradient costs no second pass over it.
+__global__ __launch_bounds__(kAccThreads) void accumulate_kernel(const AccBatch B, double* __restrict__ partials)
+{
+    __shared__ double wsum[kAccThreads / 64];
+    const uint32_t chunk = blockIdx.x;
+    const uint32_t ti = find_tensor(B.chunk_start, B.n_tensors, chunk);
+    const AccDesc& T = B.t[ti];
+    const uint64_t numel = T.numel;
+    const uint64_t G0 = T.elem_offset;
+    const uint64_t gblk0 = G0 >> 3;
+    const uint64_t nblk = ((G0 + numel - 1) >> 3) - gblk0 + 1;
+    const bool vec = (T.flags & DESC_VEC) != 0;
+    const bool rne = (B.mode & ACC_RNE) != 0, first = (B.mode & ACC_FIRST) != 0;
+    const uint64_t bfirst = (uint64_t)(chunk - B.chunk_start[ti]) * (uint64_t)(kAccThreads * kAccIters) + threadIdx.x;
+
+    double sq = 0.0;
+#pragma unroll 2
+    for (int it = 0; it < kAccIters; ++it) {
+        const uint64_t b = bfirst + (uint64_t)it * kAccThreads;
+        if (b >= nblk) break;
+        const int64_t l0 = (int64_t)((gblk0 + b) << 3) - (int64_t)G0;
+        const bool full = vec && ((uint64_t)l0 + 8 <= numel);
+        float a[8], g[8], s[8];
+        unpack8(load8_bf16<true>(T.g, l0, numel, full), g);
+        if (first) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a[j] = 0.0f;
+        } else {
+            unpack8(load8_bf16<true>(T.acc, l0, numel, full), a);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float t = B.scale * g[j];
+            s[j] = a[j] + t;
+        }
+        v4u o;
+        if (rne) {
+            o.x = rne_pair(s[0], s[1]); o.y = rne_pair(s[2], s[3]);
+            o.z = rne_pair(s[4], s[5]); o.w = rne_pair(s[6], s[7]);
+        } else {
+            const u32x4 r = block_bits(gblk0 + b, STREAM_ACC, T.tensor_id, B.micro_step, B.seed_lo, B.seed_hi);
+            o = any_nan8(s) ? sr8<true>(s, r) : sr8<false>(s, r);
+        }
+        store8_bf16<true>(T.acc, l0, numel, full, o);
+        if (B.mode & ACC_NORM) {
+            float w[8];
+            unpack8(o, w);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                // lanes of a partial block wrote only elements inside the tensor
+                const int64_t l = l0 + j;
+                const double wd = (l >= 0 && (uint64_t)l < numel) ? (double)w[j] : 0.0;
+                sq = __builtin_fma(wd, wd, sq);
+            }
+        }
+    }
+    if (B.mode & ACC_NORM) {
+        sq = wave_sum(sq);
+        if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = sq;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double t = wsum[0];
+#pragma unroll
+            for (int w = 1; w < kAccThreads / 64; ++w) t += wsum[w];
+            partials[B.partial_base + chunk] = t;
+        }
+    }
 }
 
 // Pass 1: one binary64 partial sum of squares per chunk.  g is widened to binary64 before

@@ -166,6 +166,91 @@ int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_no
     return e == hipSuccess ? SR_OK : hip_fail(e);
 }
 
+uint64_t sr_accumulate_workspace_bytes(uint32_t n_tensors, uint64_t total_numel)
+{
+    const uint64_t chunks = total_numel / (uint64_t)kAccChunkElems + (uint64_t)n_tensors + 1;
+    return (chunks * sizeof(double) + 255u) & ~(uint64_t)255u;
+}
+
+int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scale, uint32_t micro_step,
+                       uint64_t seed, uint32_t flags, float* d_norm_out, void* d_workspace,
+                       uint64_t workspace_bytes, void* stream)
+{
+    if (n_tensors && !tensors) return SR_ERR_NULL;
+    if (flags & ~(SR_ACC_RNE | SR_ACC_FIRST)) return SR_ERR_ARG;
+    if (!std::isfinite(scale)) return SR_ERR_ARG;
+    if (d_norm_out && !aligned(d_norm_out, 4)) return SR_ERR_ALIGN;
+    const uint64_t blocks_per_chunk = (uint64_t)kAccThreads * kAccIters;
+    uint64_t total_chunks = 0;
+    for (uint32_t i = 0; i < n_tensors; ++i) {
+        const sr_accum_t& t = tensors[i];
+        if (t.reserved != 0) return SR_ERR_ARG;
+        if (t.numel == 0) continue;
+        if (!t.acc || !t.grad) return SR_ERR_NULL;
+        if (!aligned(t.acc, 2) || !aligned(t.grad, 2)) return SR_ERR_ALIGN;
+        if (t.elem_offset + t.numel < t.numel) return SR_ERR_ARG;
+        const uint64_t nblk = ((t.elem_offset + t.numel - 1) >> 3) - (t.elem_offset >> 3) + 1;
+        const uint64_t nch = (nblk + blocks_per_chunk - 1) / blocks_per_chunk;
+        if (nch > kMaxGrid) return SR_ERR_ARG;
+        total_chunks += nch;
+    }
+    if (total_chunks > 0xFFFFFFFFull) return SR_ERR_ARG;
+    if (d_norm_out && total_chunks) {
+        if (!d_workspace || !aligned(d_workspace, 8)) return SR_ERR_WORKSPACE;
+        if (workspace_bytes < total_chunks * sizeof(double)) return SR_ERR_WORKSPACE;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    double* partials = static_cast<double*>(d_workspace);
+
+    AccBatch batch;
+    std::memset(&batch, 0, sizeof(batch));
+    batch.scale = scale;
+    batch.seed_lo = (uint32_t)(seed & 0xFFFFFFFFu);
+    batch.seed_hi = (uint32_t)(seed >> 32);
+    batch.micro_step = micro_step;
+    batch.mode = (flags & SR_ACC_RNE ? ACC_RNE : 0u) | (flags & SR_ACC_FIRST ? ACC_FIRST : 0u) |
+                 (d_norm_out ? ACC_NORM : 0u);
+    uint32_t nb = 0, chunks_in_batch = 0, base = 0;
+    auto flush = [&]() -> hipError_t {
+        if (nb == 0) return hipSuccess;
+        batch.n_tensors = nb;
+        batch.partial_base = base;
+        batch.chunk_start[nb] = chunks_in_batch;
+        hipLaunchKernelGGL(accumulate_kernel, dim3(chunks_in_batch), dim3(kAccThreads), 0, s, batch, partials);
+        base += chunks_in_batch;
+        nb = 0; chunks_in_batch = 0;
+        return hipGetLastError();
+    };
+    for (uint32_t i = 0; i < n_tensors; ++i) {
+        const sr_accum_t& t = tensors[i];
+        if (t.numel == 0) continue;
+        const uint64_t nblk = ((t.elem_offset + t.numel - 1) >> 3) - (t.elem_offset >> 3) + 1;
+        const uint32_t nch = (uint32_t)((nblk + blocks_per_chunk - 1) / blocks_per_chunk);
+        if (nb == kAccMaxBatch || (uint64_t)chunks_in_batch + nch > kMaxGrid) {
+            const hipError_t e = flush();
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        AccDesc& d = batch.t[nb];
+        d.acc = static_cast<uint16_t*>(t.acc);
+        d.g = static_cast<const uint16_t*>(t.grad);
+        d.numel = t.numel;
+        d.elem_offset = t.elem_offset;
+        d.tensor_id = t.tensor_id;
+        d.flags = ((t.elem_offset & 7u) == 0 && aligned(t.acc, 16) && aligned(t.grad, 16)) ? DESC_VEC : 0u;
+        batch.chunk_start[nb] = chunks_in_batch;
+        chunks_in_batch += nch;
+        ++nb;
+    }
+    hipError_t e = flush();
+    if (e != hipSuccess) return hip_fail(e);
+    if (d_norm_out) {
+        hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(kFinalThreads), 0, s, partials, (uint32_t)total_chunks, d_norm_out);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return SR_OK;
+}
+
 int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper_t* hyper,
                   uint32_t step, uint64_t seed, uint32_t flags, const float* d_grad_norm,
                   float max_norm, void* stream)

@@ -144,3 +144,33 @@ def test_binding_rejects_host_tensors_and_wrong_dtypes():
         B.sr_cast_f32_bf16(x, y, 0, 1)
     with pytest.raises(ValueError):
         B.TensorList([y], [y], [y], [y])
+
+
+def test_accumulate_argument_errors():
+    L = B.lib()
+    a = B.SrAccum()
+    a.acc, a.grad, a.numel, a.elem_offset, a.tensor_id, a.reserved = buf(2 * 100000), buf(2 * 100000), 100000, 0, 0, 0
+    arr = (B.SrAccum * 1)(a)
+    out, ws = buf(4), buf(4096)
+
+    def call(arr=arr, n=1, scale=1.0, flags=0, out=None, ws=None, wsb=0):
+        return L.sr_grad_accumulate(arr, n, scale, 1, 0, flags, out, ws, wsb, None)
+    assert call(arr=None) == B.SR_ERR_NULL
+    assert call(flags=4) == B.SR_ERR_ARG
+    assert call(scale=float("nan")) == B.SR_ERR_ARG
+    assert call(out=out + 2, ws=ws, wsb=4096) == B.SR_ERR_ALIGN
+    assert call(out=out, ws=None, wsb=4096) == B.SR_ERR_WORKSPACE
+    assert call(out=out, ws=ws, wsb=8) == B.SR_ERR_WORKSPACE            # 13 chunks need 104 bytes
+    assert call(out=out, ws=ws + 4, wsb=4096) == B.SR_ERR_WORKSPACE
+    arr[0].reserved = 1
+    assert call() == B.SR_ERR_ARG
+    arr[0].reserved = 0
+    arr[0].grad = None
+    assert call() == B.SR_ERR_NULL
+    arr[0].grad = a.grad + 1
+    assert call() == B.SR_ERR_ALIGN
+    arr[0].grad = a.grad
+    arr[0].elem_offset = 2 ** 64 - 5
+    assert call() == B.SR_ERR_ARG
+    assert call(n=0) == B.SR_OK
+    assert L.sr_accumulate_workspace_bytes(3, 10 ** 9) >= 8 * (10 ** 9 // (256 * 8 * 4) + 3)

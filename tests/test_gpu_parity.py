@@ -495,3 +495,91 @@ def test_norm_matches_oracle_on_gpt_list_and_misaligned_views():
 def test_norm_is_reproducible():
     g = W.make_grads(W.gpt_shapes(64, 2, 256, 5003, 64), DEV, 5, 1e-3)
     assert len({_gpu_norm(g) for _ in range(3)}) == 1
+
+
+# ------------------------------------------------------------------ sr_grad_accumulate
+
+def test_grad_accumulate_micro_batches_bit_exact_with_fused_norm():
+    """Four micro-batches accumulated in BF16 with SR over a ragged, partly misaligned list; every
+    step bit-exact; the norm written by the last call equals the oracle's norm of the result; a
+    clipped update then consumes accumulator and norm."""
+    sizes = [1, 9, 511, 512, 4097, 8192 * 3 + 5, 70001]
+    accs, micro, offs = [], [], []
+    for i, n in enumerate(sizes):
+        shift = i % 3
+        accs.append(torch.zeros(n + 8, dtype=torch.bfloat16, device=DEV)[shift:shift + n])
+        micro.append(torch.empty(n + 8, dtype=torch.bfloat16, device=DEV)[(shift + i) % 2:(shift + i) % 2 + n])
+        offs.append([0, 8, 3, 1 << 34][i % 4])
+    al = B.AccumList(accs, micro, tensor_ids=[3 * i for i in range(len(sizes))], elem_offsets=offs)
+    host = [to_np(a) for a in accs]
+    norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+    ws = torch.empty(max(al.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
+    K = 4
+    for k in range(K):
+        W.fill_grads(micro, 900 + k, 1e-3)
+        flags = B.SR_ACC_FIRST if k == 0 else 0
+        last = k == K - 1
+        B.sr_grad_accumulate(al, 1.0 / K, 100 + k, 77, flags, norm if last else None, ws if last else None)
+        torch.cuda.synchronize()
+        for i, h in enumerate(host):
+            ref.grad_accumulate(h, to_np(micro[i]), 1.0 / K, 100 + k, 77, tensor_id=3 * i, elem_offset=offs[i],
+                                flags=(ref.ACC_FIRST if k == 0 else 0))
+            assert bool(np.all(to_np(accs[i]) == h)), f"micro-batch {k} tensor {i}"
+    want = ref.grad_global_norm(host)
+    got = float(norm.item())
+    assert got == want or abs(got - want) <= 1e-6 * want
+    # nearest-rounding variant
+    W.fill_grads(micro, 999, 1e-3)
+    B.sr_grad_accumulate(al, 0.5, 200, 77, B.SR_ACC_RNE)
+    torch.cuda.synchronize()
+    for i, h in enumerate(host):
+        ref.grad_accumulate(h, to_np(micro[i]), 0.5, 200, 77, tensor_id=3 * i, elem_offset=offs[i], flags=ref.ACC_RNE)
+        assert bool(np.all(to_np(accs[i]) == h))
+
+
+def test_grad_accumulate_norm_feeds_a_clipped_step():
+    cfg = W.config(3)
+    shapes = W.gpt_shapes(64, 2, 256, 5003, 64)
+    pair = make_pair(cfg, shapes)
+    micro = [torch.empty_like(g) for g in pair.g]
+    al = B.AccumList(pair.g, micro)
+    ws = torch.empty(max(al.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
+    for k in range(2):
+        W.fill_grads(micro, 50 + k, cfg.grad_std, cfg.outlier_frac, cfg.outlier_std)
+        B.sr_grad_accumulate(al, 0.5, 1 + k, 3, B.SR_ACC_FIRST if k == 0 else 0, pair.norm if k == 1 else None, ws)
+    torch.cuda.synchronize()
+    fused = float(pair.norm.item())
+    # the separate two-pass norm of the same buffers gives the same value (same squares, same
+    # binary64 arithmetic, different chunking: equal or one rounding apart)
+    B.grad_global_norm(pair.tl, pair.norm, pair.ws)
+    torch.cuda.synchronize()
+    two_pass = float(pair.norm.item())
+    assert fused == two_pass or abs(fused - two_pass) <= 1e-6 * two_pass
+    want = ref.grad_global_norm([to_np(g) for g in pair.g])
+    assert fused == want or abs(fused - want) <= 1e-6 * want
+    pair.norm.fill_(fused)
+    for h, g in zip(pair.host, pair.g):
+        h["g"] = to_np(g)
+    B.sr_adamw_step(pair.tl, cfg.hyper, 1, 0, 0, pair.norm, cfg.clip)
+    torch.cuda.synchronize()
+    ref.sr_adamw_step(pair.host, cfg.hyper, 1, 0, 0, norm=fused, max_norm=cfg.clip)
+    pair.compare("step after fused accumulate+norm")
+
+
+def test_grad_accumulate_special_values_and_empty():
+    vals = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x7F7F, 0xFF7F, 0x7F80, 0xFF80, 0x7FC0, 0xFFC1,
+                     0x3F80, 0xBF80, 0x0080, 0x1234, 0x9234], dtype=np.uint16)
+    rng = np.random.default_rng(1)
+    n = 1 << 14
+    a = bf16_dev(vals[rng.integers(0, vals.size, n)])
+    g = bf16_dev(vals[rng.integers(0, vals.size, n)])
+    ha, hg = to_np(a), to_np(g)
+    al = B.AccumList([a], [g])
+    B.sr_grad_accumulate(al, 2.0, 5, 9)
+    torch.cuda.synchronize()
+    ref.grad_accumulate(ha, hg, 2.0, 5, 9)
+    assert_bf16_parity(to_np(a), ha, "accumulate specials")
+    B.sr_grad_accumulate(B.AccumList([], []), 1.0, 1, 0)
+    e = torch.empty(0, dtype=torch.bfloat16, device=DEV)
+    B.sr_grad_accumulate(B.AccumList([e], [e]), 1.0, 1, 0)
+    torch.cuda.synchronize()
