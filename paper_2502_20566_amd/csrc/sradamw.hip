@@ -168,8 +168,11 @@ int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_no
 
 uint64_t sr_accumulate_workspace_bytes(uint32_t n_tensors, uint64_t total_numel)
 {
-    const uint64_t chunks = total_numel / (uint64_t)kAccChunkElems + (uint64_t)n_tensors + 1;
-    return (chunks * sizeof(double) + 255u) & ~(uint64_t)255u;
+    // first-level partials plus the folded levels (each kReduceFan times smaller)
+    uint64_t chunks = total_numel / (uint64_t)kAccChunkElems + (uint64_t)n_tensors + 1;
+    uint64_t total = chunks;
+    while (chunks > kReduceAbove) { chunks = (chunks + kReduceFan - 1) / kReduceFan; total += chunks; }
+    return (total * sizeof(double) + 255u) & ~(uint64_t)255u;
 }
 
 int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scale, uint32_t micro_step,
@@ -196,8 +199,10 @@ int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scal
     }
     if (total_chunks > 0xFFFFFFFFull) return SR_ERR_ARG;
     if (d_norm_out && total_chunks) {
+        uint64_t need = total_chunks, level = total_chunks;
+        while (level > kReduceAbove) { level = (level + kReduceFan - 1) / kReduceFan; need += level; }
         if (!d_workspace || !aligned(d_workspace, 8)) return SR_ERR_WORKSPACE;
-        if (workspace_bytes < total_chunks * sizeof(double)) return SR_ERR_WORKSPACE;
+        if (workspace_bytes < need * sizeof(double)) return SR_ERR_WORKSPACE;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     double* partials = static_cast<double*>(d_workspace);
@@ -244,7 +249,19 @@ int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scal
     hipError_t e = flush();
     if (e != hipSuccess) return hip_fail(e);
     if (d_norm_out) {
-        hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(kFinalThreads), 0, s, partials, (uint32_t)total_chunks, d_norm_out);
+        // fold the partial sums level by level (each level behind the previous one in the
+        // workspace), then one workgroup finishes
+        uint32_t n_level = (uint32_t)total_chunks;
+        double* level = partials;
+        while (n_level > kReduceAbove) {
+            const uint32_t n_next = (n_level + kReduceFan - 1) / kReduceFan;
+            hipLaunchKernelGGL(sumsq_reduce_kernel, dim3(n_next), dim3(kReduceThreads), 0, s, level, n_level, level + n_level);
+            e = hipGetLastError();
+            if (e != hipSuccess) return hip_fail(e);
+            level += n_level;
+            n_level = n_next;
+        }
+        hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(kFinalThreads), 0, s, level, n_level, d_norm_out);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e);
     }

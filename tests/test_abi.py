@@ -160,7 +160,7 @@ def test_accumulate_argument_errors():
     assert call(scale=float("nan")) == B.SR_ERR_ARG
     assert call(out=out + 2, ws=ws, wsb=4096) == B.SR_ERR_ALIGN
     assert call(out=out, ws=None, wsb=4096) == B.SR_ERR_WORKSPACE
-    assert call(out=out, ws=ws, wsb=8) == B.SR_ERR_WORKSPACE            # 13 chunks need 104 bytes
+    assert call(out=out, ws=ws, wsb=8) == B.SR_ERR_WORKSPACE            # 196 chunks need 1568 bytes
     assert call(out=out, ws=ws + 4, wsb=4096) == B.SR_ERR_WORKSPACE
     arr[0].reserved = 1
     assert call() == B.SR_ERR_ARG
@@ -173,4 +173,4 @@ def test_accumulate_argument_errors():
     arr[0].elem_offset = 2 ** 64 - 5
     assert call() == B.SR_ERR_ARG
     assert call(n=0) == B.SR_OK
-    assert L.sr_accumulate_workspace_bytes(3, 10 ** 9) >= 8 * (10 ** 9 // (256 * 8 * 4) + 3)
+    assert L.sr_accumulate_workspace_bytes(3, 10 ** 9) >= 8 * (10 ** 9 // 512 + 3)

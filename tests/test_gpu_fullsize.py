@@ -178,3 +178,27 @@ def test_cast_every_binary32_encoding():
         bad += int((to_np(out) != want).sum())
         del bits, x, out
     assert bad == 0
+
+
+def test_grad_accumulate_full_size_with_fused_norm():
+    """Config-3 parameter list (355M elements, 292 tensors): two micro-batches accumulated with SR;
+    every element against the oracle; the fused norm (several hundred thousand partial sums, folded
+    in two levels) against the oracle's norm of the result."""
+    cfg = W.config(3)
+    accs = [torch.zeros(W.numel_of(sh), dtype=torch.bfloat16, device=DEV) for _, sh, _ in cfg.shapes]
+    micro = [torch.empty_like(a) for a in accs]
+    al = B.AccumList(accs, micro)
+    norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+    ws = torch.empty(al.workspace_bytes(), dtype=torch.uint8, device=DEV)
+    host = [to_np(a) for a in accs]
+    for k in range(2):
+        W.fill_grads(micro, W.data_seed(3, 70 + k), cfg.grad_std, cfg.outlier_frac, cfg.outlier_std)
+        B.sr_grad_accumulate(al, 0.5, 10 + k, 5, B.SR_ACC_FIRST if k == 0 else 0, norm if k == 1 else None, ws)
+        torch.cuda.synchronize()
+        for i, h in enumerate(host):
+            ref.grad_accumulate(h, to_np(micro[i]), 0.5, 10 + k, 5, tensor_id=i, flags=ref.ACC_FIRST if k == 0 else 0)
+    bad = sum(int((to_np(a) != h).sum()) for a, h in zip(accs, host))
+    assert bad == 0
+    want = ref.grad_global_norm(host)
+    got = float(norm.item())
+    assert got == want or abs(got - want) <= 1e-6 * want, (got, want)
