@@ -14,7 +14,9 @@
  *     are read before the call returns and may be freed right after it.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work on it: no host synchronisation, no device
- *     allocation, no hidden state.  Results are ordered by the stream.
+ *     allocation, no hidden state.  Results are ordered by the stream.  The
+ *     calling thread's current device must be the device of the stream and
+ *     of the tensors.
  *   - Return value: SR_OK (0) or a negative SR_ERR_* code.  Arguments are
  *     validated on the host first; on an argument error nothing is enqueued.
  *   - Outputs depend only on the input bits, the hyper-parameters, `step`,

@@ -583,3 +583,109 @@ def test_grad_accumulate_special_values_and_empty():
     e = torch.empty(0, dtype=torch.bfloat16, device=DEV)
     B.sr_grad_accumulate(B.AccumList([e], [e]), 1.0, 1, 0)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ randomized sweep
+
+def test_adamw_randomized_cases():
+    """Forty seeded random cases: list length, sizes, alignments, element offsets, tensor ids,
+    strategy and variant flags, clipping, and hyper-parameters including the corners (beta = 0,
+    eps = 0, zero weight decay, large learning rate, late steps)."""
+    rng = np.random.default_rng(2024)
+    strategies = [0, B.SR_FLAG_RNE_MOMENTS, B.SR_FLAG_RNE_PARAMS | B.SR_FLAG_RNE_MOMENTS, B.SR_FLAG_RNE_PARAMS,
+                  B.SR_FLAG_FP32_MOMENTS, B.SR_FLAG_FP32_MOMENTS | B.SR_FLAG_RNE_PARAMS,
+                  B.SR_FLAG_KAHAN, B.SR_FLAG_MASTER_FP32 | B.SR_FLAG_FP32_MOMENTS]
+    for case in range(40):
+        flags = strategies[case % len(strategies)]
+        if rng.random() < 0.3:
+            flags |= B.SR_FLAG_EPS_IN_ROOT
+        if rng.random() < 0.3:
+            flags |= B.SR_FLAG_DIV_BIAS
+        fp32 = bool(flags & B.SR_FLAG_FP32_MOMENTS)
+        n_t = int(rng.integers(1, 70))
+        params, ms, vs, aux, grads, offs, ids = [], [], [], [], [], [], []
+        for i in range(n_t):
+            n = int(rng.choice([1, 5, 8, 64, 257, 512, 1000, 4099, 20000]))
+            sh = [int(rng.integers(0, 3)) if rng.random() < 0.3 else 0 for _ in range(5)]
+            p, g, m, v = _random_state(n + 8, 7000 + 100 * case + i, fp32)
+            params.append(p[sh[0]:sh[0] + n]); grads.append(g[sh[1]:sh[1] + n])
+            ms.append(m[sh[2]:sh[2] + n]); vs.append(v[sh[3]:sh[3] + n])
+            offs.append(int(rng.choice([0, 0, 8, 3, 1 << 32, (1 << 40) + 5])))
+            ids.append(int(rng.integers(0, 1 << 32)))
+            if flags & B.SR_FLAG_KAHAN:
+                aux.append((torch.randn(n + 8, device=DEV) * 1e-5).to(torch.bfloat16)[sh[4]:sh[4] + n])
+            elif flags & B.SR_FLAG_MASTER_FP32:
+                buf = torch.zeros(n + 8, device=DEV)
+                buf[sh[4]:sh[4] + n] = params[-1].float() + torch.randn(n, device=DEV) * 1e-5
+                aux.append(buf[sh[4]:sh[4] + n])
+        pair = Pair(params, ms, vs, fp32, tensor_ids=ids, elem_offsets=offs, aux=aux if aux else None)
+        for gd, gs in zip(pair.g, grads):
+            gd.copy_(gs)
+        hyper = dict(lr=float(rng.choice([0.0, 1e-5, 6e-4, 3e-3, 0.5])),
+                     beta1=float(rng.choice([0.0, 0.5, 0.9, 0.99])),
+                     beta2=float(rng.choice([0.0, 0.95, 0.999, 0.99999])),
+                     eps=float(rng.choice([0.0, 1e-12, 1e-8, 1e-3])),
+                     weight_decay=float(rng.choice([0.0, 0.1, 1.0])))
+        t = int(rng.choice([1, 2, 17, 1000, 123456, 2 ** 32 - 1]))
+        clip = None if rng.random() < 0.5 else float(rng.choice([1e-3, 0.05, 1.0, 100.0]))
+        seed = int(rng.integers(0, 2 ** 63))
+        pair.step(hyper, t, seed, clip=clip, flags=flags & ~B.SR_FLAG_FP32_MOMENTS)
+        pair.compare(f"random case {case} flags {flags} t {t} clip {clip} hyper {hyper}")
+
+
+# ------------------------------------------------------- resume and stagnation behaviour
+
+def test_resume_from_copied_state_is_bit_identical():
+    """The optimizer RNG is stateless: ten steps straight equal five steps, a 'restart' from a
+    copy of the tensors in new buffers, and five more -- only (seed, step) carry over."""
+    cfg = W.config(2)
+    shapes = W.gpt_shapes(48, 1, 128, 501, 16)
+    def fresh():
+        p = W.make_params(shapes, DEV, 31, cfg.param_std)
+        m, v = W.make_moments(shapes, DEV, False)
+        g = [torch.empty_like(x) for x in p]
+        return p, g, m, v
+    p, g, m, v = fresh()
+    tl = B.TensorList(p, g, m, v)
+    for t in range(1, 11):
+        W.fill_grads(g, 400 + t, 1e-3)
+        B.sr_adamw_step(tl, cfg.hyper, t, 99)
+    p2, g2, m2, v2 = fresh()
+    tl2 = B.TensorList(p2, g2, m2, v2)
+    for t in range(1, 6):
+        W.fill_grads(g2, 400 + t, 1e-3)
+        B.sr_adamw_step(tl2, cfg.hyper, t, 99)
+    torch.cuda.synchronize()
+    p3 = [x.clone() for x in p2]; m3 = [x.clone() for x in m2]; v3 = [x.clone() for x in v2]
+    g3 = [torch.empty_like(x) for x in p3]
+    del tl2, p2, m2, v2
+    tl3 = B.TensorList(p3, g3, m3, v3)
+    for t in range(6, 11):
+        W.fill_grads(g3, 400 + t, 1e-3)
+        B.sr_adamw_step(tl3, cfg.hyper, t, 99)
+    torch.cuda.synchronize()
+    for a, b in zip(p + m + v, p3 + m3 + v3):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_sub_spacing_updates_stagnate_under_nearest_rounding_only():
+    """Section 2.1: with updates far below half a BF16 spacing, Q(x + u) = x for nearest rounding
+    while E[Q_SR(x + u)] = x + u.  Parameters at 1.0 (spacing 2^-8 below), update about 6e-4."""
+    n = 1 << 20
+    hyper = dict(lr=6e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0)
+    g = torch.full((n,), 1e-4, dtype=torch.bfloat16, device=DEV)
+
+    def run(flags):
+        p = torch.ones(n, dtype=torch.bfloat16, device=DEV)
+        m = torch.zeros_like(p); v = torch.zeros_like(p)
+        B.sr_adamw_step(B.TensorList([p], [g], [m], [v]), hyper, 1, 4, flags)
+        torch.cuda.synchronize()
+        return p.float()
+    nearest = run(B.SR_FLAG_RNE_PARAMS | B.SR_FLAG_RNE_MOMENTS)
+    assert bool((nearest == 1.0).all())
+    sr = run(0)
+    update = 6e-4                                            # lr * g/(|g| + eps) at step 1
+    moved = float((1.0 - sr.double()).mean())
+    q = update / 2.0 ** -8
+    assert abs(moved - update) <= 5 * 2.0 ** -8 * np.sqrt(q * (1 - q) / n) + 1e-6
+    assert set(torch.unique(sr).tolist()) == {1.0, 1.0 - 2.0 ** -8}
