@@ -89,7 +89,7 @@ def main():
     ap.add_argument("--mode", choices=sorted(MODES), default=None,
                     help="step variant (default: the config's own: sr, or fp32_moments for config 4)")
     ap.add_argument("--warm-steps", type=int, default=None, help="seeded steps that warm the moments")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, do one device copy of 2^30 bytes (a dispatch of "
