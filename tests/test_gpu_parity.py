@@ -689,3 +689,45 @@ def test_sub_spacing_updates_stagnate_under_nearest_rounding_only():
     q = update / 2.0 ** -8
     assert abs(moved - update) <= 5 * 2.0 ** -8 * np.sqrt(q * (1 - q) / n) + 1e-6
     assert set(torch.unique(sr).tolist()) == {1.0, 1.0 - 2.0 ** -8}
+
+
+def test_norm_and_step_are_capturable_in_a_hip_graph():
+    """The library only launches kernels whose tables travel in their arguments (no allocation,
+    no memset, no host synchronisation), so norm + clipped step can be captured once and replayed.
+    Three replays, with eager work and synchronisations between them, equal three eager calls."""
+    cfg = W.config(3)
+    shapes = W.gpt_shapes(48, 2, 192, 1001, 32)
+
+    def fresh():
+        p = W.make_params(shapes, DEV, 61, cfg.param_std)
+        m, v = W.make_moments(shapes, DEV, False)
+        g = W.make_grads(shapes, DEV, 62, cfg.grad_std, cfg.outlier_frac, cfg.outlier_std)
+        tl = B.TensorList(p, g, m, v)
+        return p, g, m, v, tl, torch.zeros(1, dtype=torch.float32, device=DEV), \
+            torch.empty(max(tl.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
+
+    p, g, m, v, tl, norm, ws = fresh()
+    for _ in range(3):
+        B.grad_global_norm(tl, norm, ws)
+        B.sr_adamw_step(tl, cfg.hyper, 5, 8, 0, norm, cfg.clip)
+    torch.cuda.synchronize()
+    eager = [to_np(x) for x in p + m + v]
+
+    p2, g2, m2, v2, tl2, norm2, ws2 = fresh()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.grad_global_norm(tl2, norm2, ws2)
+            B.sr_adamw_step(tl2, cfg.hyper, 5, 8, 0, norm2, cfg.clip)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    # capture does not execute: state is still the initial one
+    scratch = torch.zeros(1024, device=DEV)
+    for _ in range(3):
+        graph.replay()
+        scratch += 1.0                                    # unrelated eager work between replays
+        torch.cuda.synchronize()
+    for a, b in zip(eager, [to_np(x) for x in p2 + m2 + v2]):
+        assert bool(np.all(a == b))
