@@ -41,8 +41,9 @@ extern "C" {
                                   range overflow                                          */
 #define SR_ERR_WORKSPACE (-3)  /* workspace NULL, misaligned (8 bytes) or too small       */
 #define SR_ERR_ALIGN     (-4)  /* a BF16 pointer not 2-byte / an FP32 pointer not 4-byte
-                                  aligned (16-byte misalignment is NOT an error: such
-                                  tensors take the element-wise path, same results)       */
+                                  aligned.  Nothing more is required: tensors may be views
+                                  starting at any element of a larger buffer and keep the
+                                  vector path                                             */
 #define SR_ERR_HIP       (-5)  /* a launch failed; see sr_last_hip_error()                */
 
 /* flags of sr_adamw_step */

@@ -40,8 +40,13 @@ constexpr int kAccChunkElems = kAccThreads * 8 * kAccIters;
 constexpr int kAccMaxBatch = 88;       // tensors per accumulation launch
 
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+// Vector accesses are declared with the alignment of the ELEMENT type (2 bytes for BF16 arrays, 4 for
+// binary32 arrays): global memory on this target takes dwordx4/x2 accesses at any such address, so
+// tensors that are views starting anywhere in a larger buffer keep the vector path.
+typedef v4u v4u_a2 __attribute__((aligned(2)));
+typedef v4u v4u_a4 __attribute__((aligned(4)));
 
-enum : uint32_t { DESC_VEC = 1u };     // all pointers 16-byte aligned and elem_offset % 8 == 0
+enum : uint32_t { DESC_VEC = 1u };     // elem_offset % 8 == 0: blocks of the RNG counter start at element 0
 
 struct TensorDesc {
     uint16_t* p;
@@ -89,7 +94,7 @@ struct AccDesc {
     uint64_t numel;
     uint64_t elem_offset;
     uint32_t tensor_id;
-    uint32_t flags;                        // DESC_VEC
+    uint32_t pad_;
 };
 enum : uint32_t { ACC_RNE = 1u, ACC_FIRST = 2u, ACC_NORM = 4u };
 struct AccBatch {
@@ -103,39 +108,56 @@ static_assert(sizeof(AccBatch) <= 4096, "kernel argument segment");
 
 // ------------------------------------------------------------------ memory access helpers
 
-template <bool NT>
+// A = alignment of the array's element type in bytes (2 or 4).
+template <bool NT, int A>
 __device__ __forceinline__ v4u load_v4(const void* ptr)
 {
-    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const v4u*>(ptr));
-    return *reinterpret_cast<const v4u*>(ptr);
+    if (A == 2) {
+        if (NT) return __builtin_nontemporal_load(reinterpret_cast<const v4u_a2*>(ptr));
+        return *reinterpret_cast<const v4u_a2*>(ptr);
+    }
+    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const v4u_a4*>(ptr));
+    return *reinterpret_cast<const v4u_a4*>(ptr);
 }
-template <bool NT>
+template <bool NT, int A>
 __device__ __forceinline__ void store_v4(void* ptr, v4u x)
 {
-    if (NT) __builtin_nontemporal_store(x, reinterpret_cast<v4u*>(ptr));
-    else *reinterpret_cast<v4u*>(ptr) = x;
+    if (A == 2) {
+        if (NT) __builtin_nontemporal_store(x, reinterpret_cast<v4u_a2*>(ptr));
+        else *reinterpret_cast<v4u_a2*>(ptr) = x;
+    } else {
+        if (NT) __builtin_nontemporal_store(x, reinterpret_cast<v4u_a4*>(ptr));
+        else *reinterpret_cast<v4u_a4*>(ptr) = x;
+    }
 }
 
 typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+typedef v2u v2u_a2 __attribute__((aligned(2)));
 template <bool NT>
 __device__ __forceinline__ v2u load_v2(const void* ptr)
 {
-    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const v2u*>(ptr));
-    return *reinterpret_cast<const v2u*>(ptr);
+    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const v2u_a2*>(ptr));
+    return *reinterpret_cast<const v2u_a2*>(ptr);
 }
 template <bool NT>
 __device__ __forceinline__ void store_v2(void* ptr, v2u x)
 {
-    if (NT) __builtin_nontemporal_store(x, reinterpret_cast<v2u*>(ptr));
-    else *reinterpret_cast<v2u*>(ptr) = x;
+    if (NT) __builtin_nontemporal_store(x, reinterpret_cast<v2u_a2*>(ptr));
+    else *reinterpret_cast<v2u_a2*>(ptr) = x;
+}
+
+// True when the 8-element block starting at element l0 lies inside [0, numel).
+__device__ __forceinline__ bool block_inside(int64_t l0, uint64_t numel)
+{
+    return l0 >= 0 && (uint64_t)l0 + 8 <= numel;
 }
 
 // Eight BF16 values starting at element l0 of `base` as four packed pairs.  `full`: the block lies
-// inside the tensor and is 16-byte aligned.  Otherwise element-wise, with zeros outside [0, numel).
+// inside the tensor (one vector access).  Otherwise element-wise, with zeros outside [0, numel).
 template <bool NT>
 __device__ __forceinline__ v4u load8_bf16(const uint16_t* base, int64_t l0, uint64_t numel, bool full)
 {
-    if (full) return load_v4<NT>(base + l0);
+    if (full) return load_v4<NT, 2>(base + l0);
     uint32_t h[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -151,7 +173,7 @@ __device__ __forceinline__ v4u load8_bf16(const uint16_t* base, int64_t l0, uint
 template <bool NT>
 __device__ __forceinline__ void store8_bf16(uint16_t* base, int64_t l0, uint64_t numel, bool full, v4u x)
 {
-    if (full) { store_v4<NT>(base + l0, x); return; }
+    if (full) { store_v4<NT, 2>(base + l0, x); return; }
     const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -164,7 +186,7 @@ template <bool NT>
 __device__ __forceinline__ void load8_f32(const float* base, int64_t l0, uint64_t numel, bool full, float (&out)[8])
 {
     if (full) {
-        const v4u a = load_v4<NT>(base + l0), b = load_v4<NT>(base + l0 + 4);
+        const v4u a = load_v4<NT, 4>(base + l0), b = load_v4<NT, 4>(base + l0 + 4);
         out[0] = __uint_as_float(a.x); out[1] = __uint_as_float(a.y);
         out[2] = __uint_as_float(a.z); out[3] = __uint_as_float(a.w);
         out[4] = __uint_as_float(b.x); out[5] = __uint_as_float(b.y);
@@ -187,8 +209,8 @@ __device__ __forceinline__ void store8_f32(float* base, int64_t l0, uint64_t num
         a.z = __float_as_uint(x[2]); a.w = __float_as_uint(x[3]);
         b.x = __float_as_uint(x[4]); b.y = __float_as_uint(x[5]);
         b.z = __float_as_uint(x[6]); b.w = __float_as_uint(x[7]);
-        store_v4<NT>(base + l0, a);
-        store_v4<NT>(base + l0 + 4, b);
+        store_v4<NT, 4>(base + l0, a);
+        store_v4<NT, 4>(base + l0 + 4, b);
         return;
     }
 #pragma unroll
@@ -380,26 +402,49 @@ __device__ __forceinline__ v4u bits4(const float (&x)[4])
 __device__ __forceinline__ v4u words4(const uint32_t (&w)[4]) { v4u r; r.x = w[0]; r.y = w[1]; r.z = w[2]; r.w = w[3]; return r; }
 __device__ __forceinline__ v2u words2(const uint32_t (&w)[2]) { v2u r; r.x = w[0]; r.y = w[1]; return r; }
 
-// General path for one whole block of a lane: element-wise access with bounds, any alignment,
-// any element offset.  Same arithmetic, same counter blocks as the fast paths.
-template <uint32_t F, bool CLIP>
+// One whole block of a lane, at any element offset: vector accesses when the block lies inside the
+// tensor, element-wise accesses with bounds for the first and last block of a tensor whose counter
+// blocks do not start at element 0.
+template <uint32_t F, bool CLIP, bool NT>
 __device__ __forceinline__ void general_block(const TensorDesc& T, const StepScalars& S, float c,
                                               uint64_t gblk, int64_t l0)
 {
     using M = Mode<F>;
     const uint64_t numel = T.numel;
+    const bool full = block_inside(l0, numel);
     LaneRegs<8> L;
-    if (!M::master) unpack8(load8_bf16<false>(T.p, l0, numel, false), L.p);
-    unpack8(load8_bf16<false>(T.g, l0, numel, false), L.g);
-    if (M::fp32m) {
-        load8_f32<false>(static_cast<const float*>(T.m), l0, numel, false, L.m);
-        load8_f32<false>(static_cast<const float*>(T.v), l0, numel, false, L.v);
+    if (full) {
+        // all loads of the block back to back, one vector each (two for binary32 arrays)
+        v4u pq = {}, aq = {};
+        if (!M::master) pq = load_v4<NT, 2>(T.p + l0);
+        const v4u gq = load_v4<NT, 2>(T.g + l0);
+        if (M::fp32m) {
+            load8_f32<NT>(static_cast<const float*>(T.m), l0, numel, true, L.m);
+            load8_f32<NT>(static_cast<const float*>(T.v), l0, numel, true, L.v);
+        } else {
+            const v4u mq = load_v4<NT, 2>(static_cast<const uint16_t*>(T.m) + l0);
+            const v4u vq = load_v4<NT, 2>(static_cast<const uint16_t*>(T.v) + l0);
+            unpack8(mq, L.m);
+            unpack8(vq, L.v);
+        }
+        if (M::master) load8_f32<NT>(static_cast<const float*>(T.aux), l0, numel, true, L.aux);
+        if (M::kahan) aq = load_v4<NT, 2>(static_cast<const uint16_t*>(T.aux) + l0);
+        if (!M::master) unpack8(pq, L.p);
+        unpack8(gq, L.g);
+        if (M::kahan) unpack8(aq, L.aux);
     } else {
-        unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.m), l0, numel, false), L.m);
-        unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.v), l0, numel, false), L.v);
+        if (!M::master) unpack8(load8_bf16<false>(T.p, l0, numel, false), L.p);
+        unpack8(load8_bf16<false>(T.g, l0, numel, false), L.g);
+        if (M::fp32m) {
+            load8_f32<false>(static_cast<const float*>(T.m), l0, numel, false, L.m);
+            load8_f32<false>(static_cast<const float*>(T.v), l0, numel, false, L.v);
+        } else {
+            unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.m), l0, numel, false), L.m);
+            unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.v), l0, numel, false), L.v);
+        }
+        if (M::master) load8_f32<false>(static_cast<const float*>(T.aux), l0, numel, false, L.aux);
+        if (M::kahan) unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.aux), l0, numel, false), L.aux);
     }
-    if (M::master) load8_f32<false>(static_cast<const float*>(T.aux), l0, numel, false, L.aux);
-    if (M::kahan) unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.aux), l0, numel, false), L.aux);
     u32x4 rp = {}, rm = {}, rv = {};
     if (!M::rnep) rp = block_bits(gblk, STREAM_P, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
     if (M::srm) {
@@ -407,6 +452,19 @@ __device__ __forceinline__ void general_block(const TensorDesc& T, const StepSca
         rv = block_bits(gblk, STREAM_V, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
     }
     update_lane<F, CLIP, 8>(L, S, c, rp.w, rm.w, rv.w);
+    if (full) {
+        store_v4<NT, 2>(T.p + l0, words4(L.po));
+        if (M::fp32m) {
+            store8_f32<NT>(static_cast<float*>(T.m), l0, numel, true, L.m);
+            store8_f32<NT>(static_cast<float*>(T.v), l0, numel, true, L.v);
+        } else {
+            store_v4<NT, 2>(static_cast<uint16_t*>(T.m) + l0, words4(L.mo));
+            store_v4<NT, 2>(static_cast<uint16_t*>(T.v) + l0, words4(L.vo));
+        }
+        if (M::master) store8_f32<NT>(static_cast<float*>(T.aux), l0, numel, true, L.aux);
+        if (M::kahan) store_v4<NT, 2>(static_cast<uint16_t*>(T.aux) + l0, words4(L.ao));
+        return;
+    }
     store8_bf16<false>(T.p, l0, numel, false, words4(L.po));
     if (M::fp32m) {
         store8_f32<false>(static_cast<float*>(T.m), l0, numel, false, L.m);
@@ -459,11 +517,11 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
             float* vp = static_cast<float*>(T.v) + e;
             float* xp = static_cast<float*>(T.aux) + e;                    // master parameters
             LaneRegs<4> L;
-            if (M::master) floats4(load_v4<NT>(xp), L.aux);
+            if (M::master) floats4(load_v4<NT, 4>(xp), L.aux);
             else unpack4(load_v2<NT>(T.p + e), L.p);
             unpack4(load_v2<NT>(T.g + e), L.g);
-            floats4(load_v4<NT>(mp), L.m);
-            floats4(load_v4<NT>(vp), L.v);
+            floats4(load_v4<NT, 4>(mp), L.m);
+            floats4(load_v4<NT, 4>(vp), L.v);
             uint32_t pw[2] = {0, 0};
             if (!M::rnep) {
                 const u32x4 r = block_bits((G0 + e) >> 3, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
@@ -473,47 +531,21 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
             }
             update_lane<F, CLIP, 4>(L, S, c, pw, pw, pw);
             store_v2<NT>(T.p + e, words2(L.po));
-            store_v4<NT>(mp, bits4(L.m));
-            store_v4<NT>(vp, bits4(L.v));
-            if (M::master) store_v4<NT>(xp, bits4(L.aux));
+            store_v4<NT, 4>(mp, bits4(L.m));
+            store_v4<NT, 4>(vp, bits4(L.v));
+            if (M::master) store_v4<NT, 4>(xp, bits4(L.aux));
             return;
         }
-        // General path: the chunk's kThreads/2 blocks, one whole block per lane.
+        // Tail chunk, or counter blocks that do not start at element 0: the chunk's kThreads/2
+        // blocks, one whole block per lane.
         const uint64_t b = cl * (uint64_t)(kThreads / 2) + threadIdx.x;
         if (threadIdx.x >= kThreads / 2 || b >= nblk) return;
-        general_block<F, CLIP>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b) << 3) - (int64_t)G0);
+        general_block<F, CLIP, NT>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b) << 3) - (int64_t)G0);
     } else {
         // BF16 moments: a lane owns one whole block; a chunk is kThreads blocks.
         const uint64_t b = cl * (uint64_t)kThreads + threadIdx.x;
-        if (vec && ((b << 3) + 8 <= numel)) {
-            // whole 16-byte aligned vectors (with DESC_VEC, elem_offset is a multiple of 8, so
-            // block b starts at element 8 b)
-            const uint64_t e = b << 3;
-            uint16_t* mp = static_cast<uint16_t*>(T.m) + e;
-            uint16_t* vp = static_cast<uint16_t*>(T.v) + e;
-            uint16_t* cp = static_cast<uint16_t*>(T.aux) + e;              // Kahan compensation
-            LaneRegs<8> L;
-            const v4u Pq = load_v4<NT>(T.p + e), Gq = load_v4<NT>(T.g + e);
-            const v4u Mq = load_v4<NT>(mp), Vq = load_v4<NT>(vp);
-            v4u Cq = {};
-            if (M::kahan) Cq = load_v4<NT>(cp);
-            unpack8(Pq, L.p); unpack8(Gq, L.g); unpack8(Mq, L.m); unpack8(Vq, L.v);
-            if (M::kahan) unpack8(Cq, L.aux);
-            u32x4 rp = {}, rm = {}, rv = {};
-            if (!M::rnep) rp = block_bits(gblk0 + b, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
-            if (M::srm) {
-                rm = block_bits(gblk0 + b, STREAM_M, tensor_id, S.step, S.seed_lo, S.seed_hi);
-                rv = block_bits(gblk0 + b, STREAM_V, tensor_id, S.step, S.seed_lo, S.seed_hi);
-            }
-            update_lane<F, CLIP, 8>(L, S, c, rp.w, rm.w, rv.w);
-            store_v4<NT>(T.p + e, words4(L.po));
-            store_v4<NT>(mp, words4(L.mo));
-            store_v4<NT>(vp, words4(L.vo));
-            if (M::kahan) store_v4<NT>(cp, words4(L.ao));
-            return;
-        }
         if (b >= nblk) return;
-        general_block<F, CLIP>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b) << 3) - (int64_t)G0);
+        general_block<F, CLIP, NT>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b) << 3) - (int64_t)G0);
     }
 }
 
@@ -525,12 +557,12 @@ template <bool NT>
 __global__ __launch_bounds__(kThreads) void cast_kernel(const float* __restrict__ src,
                                                         uint16_t* __restrict__ dst, uint64_t n,
                                                         uint32_t seed_lo, uint32_t seed_hi,
-                                                        uint32_t step, uint32_t tensor_id, uint32_t vec)
+                                                        uint32_t step, uint32_t tensor_id)
 {
     const uint64_t efirst = (uint64_t)blockIdx.x * (uint64_t)(kThreads * 4);
-    if (vec && efirst + (uint64_t)(kThreads * 4) <= n) {                  // wave-uniform
+    if (efirst + (uint64_t)(kThreads * 4) <= n) {                  // wave-uniform
         const uint64_t e = efirst + (uint64_t)threadIdx.x * 4;
-        const v4u x = load_v4<NT>(src + e);
+        const v4u x = load_v4<NT, 4>(src + e);
         const u32x4 r = block_bits(e >> 3, STREAM_CAST, tensor_id, step, seed_lo, seed_hi);
         const bool upper = ((e >> 2) & 1u) != 0;
         const uint32_t w0 = upper ? r.w[2] : r.w[0], w1 = upper ? r.w[3] : r.w[1];
@@ -543,16 +575,17 @@ __global__ __launch_bounds__(kThreads) void cast_kernel(const float* __restrict_
         store_v2<NT>(dst + e, o);
         return;
     }
-    // General path (tail chunk, misaligned pointers): the chunk's kThreads/2 blocks, one per lane.
+    // Tail chunk: its kThreads/2 blocks, one per lane, the last one element-wise.
     const uint64_t nblk = (n + 7) >> 3;
     const uint64_t b = (uint64_t)blockIdx.x * (uint64_t)(kThreads / 2) + threadIdx.x;
     if (threadIdx.x >= kThreads / 2 || b >= nblk) return;
     const int64_t l0 = (int64_t)(b << 3);
+    const bool full = block_inside(l0, n);
     float y[8];
-    load8_f32<false>(src, l0, n, false, y);
+    load8_f32<NT>(src, l0, n, full, y);
     const u32x4 r = block_bits(b, STREAM_CAST, tensor_id, step, seed_lo, seed_hi);
     const v4u o = any_nan8(y) ? sr8<true>(y, r) : sr8<false>(y, r);
-    store8_bf16<false>(dst, l0, n, false, o);
+    store8_bf16<NT>(dst, l0, n, full, o);
 }
 
 // ------------------------------------------------------------------------- gradient norm
@@ -580,7 +613,6 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(const AccBatch 
     const uint64_t G0 = T.elem_offset;
     const uint64_t gblk0 = G0 >> 3;
     const uint64_t nblk = ((G0 + numel - 1) >> 3) - gblk0 + 1;
-    const bool vec = (T.flags & DESC_VEC) != 0;
     const bool rne = (B.mode & ACC_RNE) != 0, first = (B.mode & ACC_FIRST) != 0;
     const uint64_t bfirst = (uint64_t)(chunk - B.chunk_start[ti]) * (uint64_t)(kAccThreads * kAccIters) + threadIdx.x;
 
@@ -590,7 +622,7 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(const AccBatch 
         const uint64_t b = bfirst + (uint64_t)it * kAccThreads;
         if (b >= nblk) break;
         const int64_t l0 = (int64_t)((gblk0 + b) << 3) - (int64_t)G0;
-        const bool full = vec && ((uint64_t)l0 + 8 <= numel);
+        const bool full = block_inside(l0, numel);
         float a[8], g[8], s[8];
         unpack8(load8_bf16<true>(T.g, l0, numel, full), g);
         if (first) {
@@ -647,7 +679,6 @@ __global__ __launch_bounds__(kNormThreads) void sumsq_partial_kernel(const NormB
     const uint32_t ti = find_tensor(B.chunk_start, B.n_tensors, chunk);
     const uint16_t* g = B.t[ti].g;
     const uint64_t numel = B.t[ti].numel;
-    const bool vec = (reinterpret_cast<uintptr_t>(g) & 15u) == 0;
     const uint64_t nblk = (numel + 7) >> 3;
     const uint64_t bfirst = (uint64_t)(chunk - B.chunk_start[ti]) * (uint64_t)(kNormThreads * kNormIters) + threadIdx.x;
 
@@ -657,7 +688,7 @@ __global__ __launch_bounds__(kNormThreads) void sumsq_partial_kernel(const NormB
         const uint64_t b = bfirst + (uint64_t)it * kNormThreads;
         if (b >= nblk) break;
         const int64_t l0 = (int64_t)(b << 3);
-        const bool full = vec && ((uint64_t)l0 + 8 <= numel);
+        const bool full = block_inside(l0, numel);
         float x[8];
         unpack8(load8_bf16<true>(g, l0, numel, full), x);
 #pragma unroll

@@ -102,10 +102,9 @@ int sr_cast_f32_bf16(const float* d_src, void* d_dst, uint64_t n, uint64_t seed,
     const uint64_t per_wg = (uint64_t)kThreads / 2;                 // blocks per workgroup
     const uint64_t grid = (nblk + per_wg - 1) / per_wg;
     if (grid > kMaxGrid) return SR_ERR_ARG;
-    const uint32_t vec = (aligned(d_src, 16) && aligned(d_dst, 16)) ? 1u : 0u;
     hipLaunchKernelGGL((cast_kernel<kNT>), dim3((uint32_t)grid), dim3(kThreads), 0,
                        static_cast<hipStream_t>(stream), d_src, static_cast<uint16_t*>(d_dst), n,
-                       (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), step, tensor_id, vec);
+                       (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), step, tensor_id);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? SR_OK : hip_fail(e);
 }
@@ -241,7 +240,7 @@ int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scal
         d.numel = t.numel;
         d.elem_offset = t.elem_offset;
         d.tensor_id = t.tensor_id;
-        d.flags = ((t.elem_offset & 7u) == 0 && aligned(t.acc, 16) && aligned(t.grad, 16)) ? DESC_VEC : 0u;
+        d.pad_ = 0;
         batch.chunk_start[nb] = chunks_in_batch;
         chunks_in_batch += nch;
         ++nb;
@@ -366,9 +365,7 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
         d.numel = t.numel;
         d.elem_offset = t.elem_offset;
         d.tensor_id = t.tensor_id;
-        const bool vec = (t.elem_offset & 7u) == 0 && aligned(t.p, 16) && aligned(t.g, 16) &&
-                         aligned(t.m, 16) && aligned(t.v, 16) && aligned(d.aux, 16);
-        d.flags = vec ? DESC_VEC : 0u;
+        d.flags = (t.elem_offset & 7u) == 0 ? DESC_VEC : 0u;
         batch.chunk_start[nb] = chunks_in_batch;
         chunks_in_batch += nch;
         ++nb;
