@@ -198,6 +198,27 @@ def main():
     dev_ms = [a.elapsed_time(b) for a, b in zip(ev0, ev1)]
     dev_avg_ms = float(np.mean(dev_ms))
 
+    # ceiling of the access pattern on these very buffers: the step's 4-read/3-write traffic with
+    # no arithmetic (BF16 strategies without an auxiliary tensor, flat or list alike)
+    ceiling = None
+    if MODES[mode][3] == 14:
+        def probe():
+            for p_, g_, m_, v_ in zip(params, grads, ms, vs):
+                B.sr_stream_probe(p_, g_, m_, v_)
+        probe()
+        torch.cuda.synchronize()
+        reps = max(3, min(args.steps, 10))
+        pe0 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+        pe1 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+        for i in range(reps):
+            pe0[i].record()
+            probe()
+            pe1[i].record()
+        torch.cuda.synchronize()
+        probe_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(pe0, pe1)]))
+        ceiling = {"kind": "4-read/3-write copy of the same buffers, no arithmetic (sr_stream_probe)",
+                   "ms": probe_ms, "GBps": 14 * numel / (probe_ms * 1e-3) / 1e9}
+
     if args.calibrate_copy:
         src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -237,7 +258,10 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "kernel": "adamw_kernel", "avg_launch_ms": dev_avg_ms,
-                     "min_launch_ms": float(np.min(dev_ms))},
+                     "min_launch_ms": float(np.min(dev_ms)),
+                     "copy_ceiling": ceiling,
+                     "frac_of_copy_ceiling": None if ceiling is None else
+                     (MODES[mode][3] * numel / (dev_avg_ms * 1e-3) / 1e9) / ceiling["GBps"]},
         "cpu_baseline": cpu,
         "parity_sample": parity,
     }

@@ -200,6 +200,17 @@ uint64_t sr_accumulate_workspace_bytes(uint32_t n_tensors, uint64_t total_numel)
  * tensors with total_numel elements in all (an upper bound, multiple of 256). */
 uint64_t sr_workspace_bytes(uint32_t n_tensors, uint64_t total_numel);
 
+/*
+ * Measurement aid, not part of the method: the memory traffic of the BF16 step
+ * (8 bytes read, 6 written per element: the 14 bytes per element of "every
+ * tensor in BF16", Section 3) with no arithmetic -- reads p, g, m, v and writes
+ * p, m, v back UNCHANGED, in the launch geometry of sr_adamw_step.  Its time on
+ * the caller's own buffers is the rate this access pattern can reach on them,
+ * the ceiling the step is compared with.  BF16 arrays [numel], 2-byte aligned;
+ * only whole 8-element blocks are touched.
+ */
+int sr_stream_probe(void* d_p, const void* d_g, void* d_m, void* d_v, uint64_t numel, void* stream);
+
 /* Static description of an SR_ERR_* code. */
 const char* sr_strerror(int code);
 

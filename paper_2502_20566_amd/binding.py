@@ -27,7 +27,7 @@ SR_ACC_RNE = 1
 SR_ACC_FIRST = 2
 
 EXPORTS = ("sr_cast_f32_bf16", "grad_global_norm", "sr_adamw_step", "sr_workspace_bytes",
-           "sr_grad_accumulate", "sr_accumulate_workspace_bytes",
+           "sr_grad_accumulate", "sr_accumulate_workspace_bytes", "sr_stream_probe",
            "sr_strerror", "sr_last_hip_error", "sr_version")
 
 
@@ -82,6 +82,8 @@ def lib():
         L.sr_grad_accumulate.restype = C.c_int
         L.sr_accumulate_workspace_bytes.argtypes = [C.c_uint32, C.c_uint64]
         L.sr_accumulate_workspace_bytes.restype = C.c_uint64
+        L.sr_stream_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+        L.sr_stream_probe.restype = C.c_int
         L.sr_workspace_bytes.argtypes = [C.c_uint32, C.c_uint64]
         L.sr_workspace_bytes.restype = C.c_uint64
         L.sr_strerror.argtypes = [C.c_int]
@@ -208,6 +210,18 @@ def sr_adamw_step(tl: TensorList, hyper: dict, step: int, seed: int, flags: int 
                              _stream_handle(stream))
     if rc != SR_OK:
         raise SrError(rc, "sr_adamw_step")
+
+
+def sr_stream_probe(p: torch.Tensor, g: torch.Tensor, m: torch.Tensor, v: torch.Tensor, stream=None) -> None:
+    """4-read/3-write pass over BF16 p, g, m, v that leaves the data unchanged (measurement aid)."""
+    for name, t in (("p", p), ("g", g), ("m", m), ("v", v)):
+        _check_dev(t, torch.bfloat16, name)
+        if t.numel() != p.numel():
+            raise ValueError("p, g, m, v differ in size")
+    rc = lib().sr_stream_probe(p.data_ptr(), g.data_ptr(), m.data_ptr(), v.data_ptr(), p.numel(),
+                               _stream_handle(stream))
+    if rc != SR_OK:
+        raise SrError(rc, "sr_stream_probe")
 
 
 class AccumList:

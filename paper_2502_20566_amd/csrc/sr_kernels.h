@@ -549,6 +549,27 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
     }
 }
 
+// --------------------------------------------------------------------- stream probe
+
+// The memory traffic of the BF16 update with no arithmetic: reads the blocks of p, g, m, v and
+// writes p, m, v back.  `mask` is 0 at run time (the data are unchanged) but unknown to the
+// compiler, so neither the loads nor the stores can be dropped.  Same geometry as the update:
+// one wave per workgroup, one block per lane, nontemporal vector accesses.
+__global__ __launch_bounds__(kThreads) void stream_probe_kernel(uint16_t* __restrict__ p, const uint16_t* __restrict__ g,
+                                                               uint16_t* __restrict__ m, uint16_t* __restrict__ v,
+                                                               uint64_t nblk, uint32_t mask)
+{
+    const uint64_t b = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (b >= nblk) return;
+    const uint64_t e = b << 3;
+    const v4u P = load_v4<true, 2>(p + e), G = load_v4<true, 2>(g + e);
+    const v4u M = load_v4<true, 2>(m + e), V = load_v4<true, 2>(v + e);
+    const v4u k = G & mask;
+    store_v4<true, 2>(p + e, P ^ k);
+    store_v4<true, 2>(m + e, M ^ k);
+    store_v4<true, 2>(v + e, V ^ k);
+}
+
 // ----------------------------------------------------------------------- standalone SR cast
 
 // A lane owns half a block (4 elements): one 16-byte load and one 8-byte store per lane, every

@@ -73,6 +73,21 @@ int sr_version(void) { return 100; }
 
 int sr_last_hip_error(void) { return g_last_hip_error; }
 
+int sr_stream_probe(void* d_p, const void* d_g, void* d_m, void* d_v, uint64_t numel, void* stream)
+{
+    const uint64_t nblk = numel >> 3;                 // whole blocks only; a tail is left untouched
+    if (nblk == 0) return SR_OK;
+    if (!d_p || !d_g || !d_m || !d_v) return SR_ERR_NULL;
+    if (!aligned(d_p, 2) || !aligned(d_g, 2) || !aligned(d_m, 2) || !aligned(d_v, 2)) return SR_ERR_ALIGN;
+    const uint64_t grid = (nblk + kThreads - 1) / kThreads;
+    if (grid > kMaxGrid) return SR_ERR_ARG;
+    hipLaunchKernelGGL(stream_probe_kernel, dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                       static_cast<uint16_t*>(d_p), static_cast<const uint16_t*>(d_g), static_cast<uint16_t*>(d_m),
+                       static_cast<uint16_t*>(d_v), nblk, 0u);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SR_OK : hip_fail(e);
+}
+
 const char* sr_strerror(int code)
 {
     switch (code) {

@@ -731,3 +731,18 @@ def test_norm_and_step_are_capturable_in_a_hip_graph():
         torch.cuda.synchronize()
     for a, b in zip(eager, [to_np(x) for x in p2 + m2 + v2]):
         assert bool(np.all(a == b))
+
+
+def test_stream_probe_leaves_data_unchanged():
+    n = 100003
+    ts = [(torch.randn(n + 8, device=DEV) * 0.01).to(torch.bfloat16)[1:1 + n] for _ in range(4)]
+    before = [to_np(t) for t in ts]
+    B.sr_stream_probe(*ts)
+    aligned = [(torch.randn(4096, device=DEV) * 0.01).to(torch.bfloat16) for _ in range(4)]
+    b2 = [to_np(t) for t in aligned]
+    B.sr_stream_probe(*aligned)
+    torch.cuda.synchronize()
+    for t, b in zip(ts + aligned, before + b2):
+        assert bool(np.all(to_np(t) == b))
+    e = torch.empty(0, dtype=torch.bfloat16, device=DEV)
+    B.sr_stream_probe(e, e, e, e)
