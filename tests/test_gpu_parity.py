@@ -746,3 +746,37 @@ def test_stream_probe_leaves_data_unchanged():
         assert bool(np.all(to_np(t) == b))
     e = torch.empty(0, dtype=torch.bfloat16, device=DEV)
     B.sr_stream_probe(e, e, e, e)
+
+
+def test_optimizer_object_drives_the_same_steps():
+    """SRAdamW (bookkeeping only) on a small torch module equals direct calls through the binding,
+    including clipping, an lr schedule, and a resume through state_dict."""
+    from paper_2502_20566_amd.optimizer import SRAdamW
+    torch.manual_seed(0)
+    model = torch.nn.Sequential(torch.nn.Linear(64, 96), torch.nn.LayerNorm(96), torch.nn.Linear(96, 10)).to(DEV).to(torch.bfloat16)
+    params = list(model.parameters())
+    ref_p = [p.detach().clone().view(-1) for p in params]
+    ref_m = [torch.zeros_like(p) for p in ref_p]
+    ref_v = [torch.zeros_like(p) for p in ref_p]
+    hyper = dict(lr=3e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    opt = SRAdamW(params, lr=3e-3, max_norm=0.5, seed=21)
+    norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+    x = torch.randn(32, 64, device=DEV, dtype=torch.bfloat16)
+    for t in range(1, 6):
+        lr = 3e-3 * (1.0 - 0.1 * t)
+        loss = model(x).float().pow(2).mean()
+        loss.backward()
+        grads = [p.grad.detach().clone().view(-1) for p in params]
+        opt.step(lr=lr)
+        opt.zero_grad()
+        tl = B.TensorList(ref_p, grads, ref_m, ref_v)
+        ws = torch.empty(max(tl.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
+        B.grad_global_norm(tl, norm, ws)
+        B.sr_adamw_step(tl, dict(hyper, lr=lr), t, 21, 0, norm, 0.5)
+        torch.cuda.synchronize()
+        for a, b in zip(params, ref_p):
+            assert torch.equal(a.detach().view(-1).view(torch.int16), b.view(torch.int16))
+        if t == 3:                                            # resume into a fresh object
+            sd = {k: ([x_.clone() for x_ in v_] if isinstance(v_, list) else v_) for k, v_ in opt.state_dict().items()}
+            opt = SRAdamW(params, lr=1.0, max_norm=0.5, seed=0)
+            opt.load_state_dict(sd)
