@@ -65,6 +65,18 @@ def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags):
     # calibrate on 2^21 elements, then size the sample for about `seconds` of CPU work
     n0 = min(1 << 21, p.numel())
     w0 = window(0, n0)
+    # the workload's share of updates below one BF16 spacing of the parameter (what nearest rounding
+    # would mostly lose; Section 2.2), from the oracle's unrounded result on this window
+    sub_ulp = None
+    if aux is None:
+        sc = ref.adamw_scalars(step=step_no, **cfg.hyper)
+        y, _, _ = ref.adamw_unrounded(w0["p"], w0["g"], w0["m"], w0["v"], sc, flags)
+        p32 = ref.bf16_bits_to_f32(w0["p"])
+        sub_ulp = float(np.mean(np.abs(y.astype(np.float64) - p32) < np.spacing(np.abs(p32)).astype(np.float64) * 65536.0))
+    t0 = time.perf_counter()
+    ref.sr_adamw_step([w0], cfg.hyper, step_no, seed, flags, nthreads=1)
+    rate1 = n0 / (time.perf_counter() - t0)
+    w0 = window(0, n0)
     t0 = time.perf_counter()
     ref.sr_adamw_step([w0], cfg.hyper, step_no, seed, flags, nthreads=threads)
     rate0 = n0 / (time.perf_counter() - t0)
@@ -75,7 +87,8 @@ def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags):
     t0 = time.perf_counter()
     ref.sr_adamw_step([w], cfg.hyper, step_no, seed, flags, nthreads=threads)
     dt = time.perf_counter() - t0
-    return dict(value=n / dt, unit="params/s", cores=threads, kind="oracle",
+    return dict(value=n / dt, unit="params/s", cores=threads, kind="oracle", one_thread_value=rate1,
+                sub_ulp_update_fraction=sub_ulp,
                 sample=f"{n} contiguous elements from the middle of the buffer, one step "
                        f"(step {step_no}), {dt:.1f} s"), (lo, n, w)
 
@@ -257,8 +270,9 @@ def main():
         "pct_of_hbm_peak": 100.0 * bpe * numel / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "adamw_kernel", "avg_launch_ms": dev_avg_ms,
-                     "min_launch_ms": float(np.min(dev_ms)),
+                     "kernel": "adamw_kernel" if cfg.clip is None and len(params) <= 56 else
+                     "all launches of a step (norm passes + adamw_kernel per 56 tensors)", "avg_launch_ms": dev_avg_ms,
+                     "median_launch_ms": float(np.median(dev_ms)), "min_launch_ms": float(np.min(dev_ms)),
                      "copy_ceiling": ceiling,
                      "frac_of_copy_ceiling": None if ceiling is None else
                      (MODES[mode][3] * numel / (dev_avg_ms * 1e-3) / 1e9) / ceiling["GBps"]},
