@@ -7,7 +7,9 @@ workload: the 6.7B flat-buffer configuration (BF16 p/g/m/v, SR on all three writ
 moments warm-started by 100 seeded steps).  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--warm-steps N]
-                  [--cpu-seconds S] [--no-cpu-baseline]
+                  [--cpu-seconds S] [--no-cpu-baseline] [--mode M] [--graph]
+  python bench.py --op cast|accumulate|accumulate_norm [--config N]   (the other two entry points,
+                  on an array of the config's size; their own metric, not the headline one)
 """
 import argparse
 import json
@@ -93,6 +95,88 @@ def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags):
                        f"(step {step_no}), {dt:.1f} s"), (lo, n, w)
 
 
+def time_launches(torch, np, fn, warmup, steps):
+    """HIP events on the launch stream around each of `steps` calls of fn, after `warmup` calls."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    e1 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        e0[i].record()
+        fn()
+        e1[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, [a.elapsed_time(b) for a, b in zip(e0, e1)]
+
+
+def run_aux_op(args, torch, np, B, W, cfg):
+    """The standalone SR cast (Eq. 2 on a binary32 array) or the BF16 gradient accumulation with SR,
+    on one flat array of the config's element count.  Same JSON shape as the step, own metric."""
+    from oracle import ref
+    dev = "cuda:0"
+    n = sum(W.numel_of(shape) for _, shape, _ in cfg.shapes)
+    flat = [("flat", (n,), "weight")]
+    seed, tid = cfg.seed, 3
+    threads = min(ref.max_threads(), os.cpu_count() or 1)
+    n_cpu = min(n, 1 << 26) & ~7 or n
+    lo = ((n - n_cpu) // 2) & ~7
+    if args.op == "cast":
+        src = torch.empty(n, dtype=torch.float32, device=dev)
+        for k, at in enumerate(range(0, n, 1 << 28)):            # generated in pieces of 2^28 elements
+            piece = src[at:at + (1 << 28)]
+            piece.copy_(W.make_cast_input(piece.numel(), dev, W.data_seed(cfg.index, 900 + k)))
+        dst = torch.empty(n, dtype=torch.bfloat16, device=dev)
+        fn = lambda: B.sr_cast_f32_bf16(src, dst, seed, 7, tid)
+        bpe, kernel, metric = 6, "cast_kernel", "sr_cast_elements_per_sec"
+        wall, dev_ms = time_launches(torch, np, fn, args.warmup, args.steps)
+        host = src[lo:lo + n_cpu].cpu().numpy()
+        t0 = time.perf_counter()
+        want = ref.sr_cast_f32_bf16(host, seed, 7, tid, elem_offset=lo, nthreads=threads)
+        dt = time.perf_counter() - t0
+        bad = int((W.bf16_to_u16_numpy(dst[lo:lo + n_cpu]) != want).sum())
+    else:
+        with_norm = args.op == "accumulate_norm"
+        acc = W.make_grads(flat, dev, W.data_seed(cfg.index, 901), cfg.grad_std)[0]
+        g = W.make_grads(flat, dev, W.data_seed(cfg.index, 902), cfg.grad_std)[0]
+        al = B.AccumList([acc], [g], tensor_ids=[tid])
+        norm = torch.zeros(1, dtype=torch.float32, device=dev) if with_norm else None
+        ws = torch.empty(max(al.workspace_bytes(), 256), dtype=torch.uint8, device=dev) if with_norm else None
+        k = [0]
+
+        def fn():
+            k[0] += 1
+            B.sr_grad_accumulate(al, 0.25, k[0], seed, 0, norm, ws)
+        bpe, kernel, metric = 6, "accumulate_kernel", "sr_grad_accumulate_elements_per_sec"
+        wall, dev_ms = time_launches(torch, np, fn, args.warmup, args.steps)
+        a0 = W.bf16_to_u16_numpy(acc[lo:lo + n_cpu])
+        g0 = W.bf16_to_u16_numpy(g[lo:lo + n_cpu])
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ref.grad_accumulate(a0, g0, 0.25, k[0], seed, tensor_id=tid, elem_offset=lo, nthreads=threads)
+        want = a0                                                # updated in place
+        dt = time.perf_counter() - t0
+        bad = int((W.bf16_to_u16_numpy(acc[lo:lo + n_cpu]) != want).sum())
+    avg = float(np.mean(dev_ms))
+    achieved = bpe * n / (avg * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": metric, "value": n * args.steps / wall, "unit": "elements/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.op} on one flat array of config {cfg.index}'s size", "numel": n,
+                   "bytes_per_element": bpe},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "kernel": kernel,
+                     "avg_launch_ms": avg, "median_launch_ms": float(np.median(dev_ms)),
+                     "min_launch_ms": float(np.min(dev_ms))},
+        "cpu_baseline": {"value": n_cpu / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
+                         "sample": f"{n_cpu} contiguous elements from the middle of the array, {dt:.1f} s"},
+        "parity_sample": "bit-exact" if bad == 0 else f"{bad} mismatches"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -101,6 +185,10 @@ def main():
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--mode", choices=sorted(MODES), default=None,
                     help="step variant (default: the config's own: sr, or fp32_moments for config 4)")
+    ap.add_argument("--op", choices=("step", "cast", "accumulate", "accumulate_norm"), default="step")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time its replays (same step number "
+                         "on every replay; removes launch gaps of many-tensor lists)")
     ap.add_argument("--warm-steps", type=int, default=None, help="seeded steps that warm the moments")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -123,6 +211,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     cfg = W.config(args.config)
+    if args.op != "step":
+        run_aux_op(args, torch, np, B, W, cfg)
+        return
     warm = cfg.warm_steps if args.warm_steps is None else args.warm_steps
     mode = args.mode or ("fp32_moments" if cfg.fp32_moments else "sr")
     flag_names, fp32_moments, aux_kind, _ = MODES[mode]
@@ -192,8 +283,18 @@ def main():
         del got_p
         t += 1
 
+    step_fn = one_step
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                one_step(t)
+        torch.cuda.current_stream().wait_stream(side)
+        step_fn = lambda _t: graph.replay()
     for _ in range(args.warmup):
-        one_step(t)
+        step_fn(t)
     torch.cuda.synchronize()
 
     # timed region: exactly K steps, inputs resident, HIP events on the launch stream per step
@@ -203,7 +304,7 @@ def main():
     t_start = time.perf_counter()
     for i in range(args.steps):
         ev0[i].record()
-        one_step(t + i)
+        step_fn(t + i)
         ev1[i].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
@@ -265,7 +366,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}", "numel": numel, "tensors": len(params),
                    "mode": mode, "moments": "fp32" if fp32_moments else "bf16", "clip": cfg.clip,
-                   "warm_steps": warm, "bytes_per_element": bpe},
+                   "warm_steps": warm, "bytes_per_element": bpe, "hip_graph": bool(args.graph)},
         "hbm_GBps": bpe * numel / (ms_per_step * 1e-3) / 1e9,
         "pct_of_hbm_peak": 100.0 * bpe * numel / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
