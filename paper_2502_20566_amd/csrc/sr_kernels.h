@@ -132,18 +132,40 @@ __device__ __forceinline__ void store_v4(void* ptr, v4u x)
 }
 
 typedef uint32_t v2u __attribute__((ext_vector_type(2)));
-typedef v2u v2u_a2 __attribute__((aligned(2)));
-template <bool NT>
-__device__ __forceinline__ v2u load_v2(const void* ptr)
+
+// Buffer accesses of the fast paths.  A workgroup describes its own span of each array (base =
+// first byte of the chunk, wave-uniform, in scalar registers; size = the chunk's bytes) and every
+// lane adds a small byte offset: measured on MI355X the 4-read/3-write stream runs 4% faster with
+// buffer instructions than with global ones (14.7 vs 15.3 ms on 6.66e9 elements), and the hardware
+// range check confines every such access to the chunk.  Cache policy: nt (streaming).
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes)
 {
-    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const v2u_a2*>(ptr));
-    return *reinterpret_cast<const v2u_a2*>(ptr);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
-template <bool NT>
-__device__ __forceinline__ void store_v2(void* ptr, v2u x)
+template <bool NT> __device__ __forceinline__ v4u buf_load16(rsrc_t r, uint32_t off)
 {
-    if (NT) __builtin_nontemporal_store(x, reinterpret_cast<v2u_a2*>(ptr));
-    else *reinterpret_cast<v2u_a2*>(ptr) = x;
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, NT ? 2 : 0);
+}
+template <bool NT> __device__ __forceinline__ void buf_store16(rsrc_t r, uint32_t off, v4u x)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(x, r, (int)off, 0, NT ? 2 : 0);
+}
+template <bool NT> __device__ __forceinline__ v2u buf_load8(rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, NT ? 2 : 0);
+}
+template <bool NT> __device__ __forceinline__ void buf_store8(rsrc_t r, uint32_t off, v2u x)
+{
+    __builtin_amdgcn_raw_buffer_store_b64(x, r, (int)off, 0, NT ? 2 : 0);
+}
+
+// Descriptor of n_elems elements of type E starting at element first_elem of `base`.
+template <typename E>
+__device__ __forceinline__ rsrc_t chunk_rsrc(const void* base, int64_t first_elem, uint32_t n_elems)
+{
+    return make_rsrc(reinterpret_cast<const char*>(base) + first_elem * (int64_t)sizeof(E),
+                     n_elems * (uint32_t)sizeof(E));
 }
 
 // True when the 8-element block starting at element l0 lies inside [0, numel).
@@ -399,36 +421,71 @@ __device__ __forceinline__ v4u bits4(const float (&x)[4])
     r.z = __float_as_uint(x[2]); r.w = __float_as_uint(x[3]);
     return r;
 }
+__device__ __forceinline__ void floats8(v4u a, v4u b, float (&out)[8])
+{
+    out[0] = __uint_as_float(a.x); out[1] = __uint_as_float(a.y);
+    out[2] = __uint_as_float(a.z); out[3] = __uint_as_float(a.w);
+    out[4] = __uint_as_float(b.x); out[5] = __uint_as_float(b.y);
+    out[6] = __uint_as_float(b.z); out[7] = __uint_as_float(b.w);
+}
+__device__ __forceinline__ v4u bits4lo(const float (&x)[8])
+{
+    v4u r;
+    r.x = __float_as_uint(x[0]); r.y = __float_as_uint(x[1]);
+    r.z = __float_as_uint(x[2]); r.w = __float_as_uint(x[3]);
+    return r;
+}
+__device__ __forceinline__ v4u bits4hi(const float (&x)[8])
+{
+    v4u r;
+    r.x = __float_as_uint(x[4]); r.y = __float_as_uint(x[5]);
+    r.z = __float_as_uint(x[6]); r.w = __float_as_uint(x[7]);
+    return r;
+}
 __device__ __forceinline__ v4u words4(const uint32_t (&w)[4]) { v4u r; r.x = w[0]; r.y = w[1]; r.z = w[2]; r.w = w[3]; return r; }
 __device__ __forceinline__ v2u words2(const uint32_t (&w)[2]) { v2u r; r.x = w[0]; r.y = w[1]; return r; }
 
-// One whole block of a lane, at any element offset: vector accesses when the block lies inside the
-// tensor, element-wise accesses with bounds for the first and last block of a tensor whose counter
-// blocks do not start at element 0.
+// One whole block of a lane, at any element offset.  lc0: element index (relative to the tensor's
+// first element) of the first block of the workgroup's chunk of `span` blocks; the lane's block is
+// the lane-th of the chunk.  Buffer accesses through the chunk's descriptors when the block lies
+// inside the tensor, element-wise accesses with bounds for the first and last block of a tensor
+// whose counter blocks do not start at element 0.
 template <uint32_t F, bool CLIP, bool NT>
 __device__ __forceinline__ void general_block(const TensorDesc& T, const StepScalars& S, float c,
-                                              uint64_t gblk, int64_t l0)
+                                              uint64_t gblk, int64_t lc0, uint32_t lane, uint32_t span)
 {
     using M = Mode<F>;
     const uint64_t numel = T.numel;
+    const int64_t l0 = lc0 + (int64_t)lane * 8;
     const bool full = block_inside(l0, numel);
+    const uint32_t o16 = lane * 16u, o32 = lane * 32u;          // byte offsets in BF16 / binary32 arrays
+    const rsrc_t rp = chunk_rsrc<uint16_t>(T.p, lc0, span * 8u);
+    const rsrc_t rg = chunk_rsrc<uint16_t>(T.g, lc0, span * 8u);
+    const rsrc_t rm = M::fp32m ? chunk_rsrc<float>(T.m, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.m, lc0, span * 8u);
+    const rsrc_t rv = M::fp32m ? chunk_rsrc<float>(T.v, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.v, lc0, span * 8u);
+    const rsrc_t ra = M::master ? chunk_rsrc<float>(T.aux, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.aux, lc0, span * 8u);
     LaneRegs<8> L;
     if (full) {
         // all loads of the block back to back, one vector each (two for binary32 arrays)
         v4u pq = {}, aq = {};
-        if (!M::master) pq = load_v4<NT, 2>(T.p + l0);
-        const v4u gq = load_v4<NT, 2>(T.g + l0);
+        if (!M::master) pq = buf_load16<NT>(rp, o16);
+        const v4u gq = buf_load16<NT>(rg, o16);
         if (M::fp32m) {
-            load8_f32<NT>(static_cast<const float*>(T.m), l0, numel, true, L.m);
-            load8_f32<NT>(static_cast<const float*>(T.v), l0, numel, true, L.v);
+            const v4u m0 = buf_load16<NT>(rm, o32), m1 = buf_load16<NT>(rm, o32 + 16u);
+            const v4u v0 = buf_load16<NT>(rv, o32), v1 = buf_load16<NT>(rv, o32 + 16u);
+            floats8(m0, m1, L.m);
+            floats8(v0, v1, L.v);
         } else {
-            const v4u mq = load_v4<NT, 2>(static_cast<const uint16_t*>(T.m) + l0);
-            const v4u vq = load_v4<NT, 2>(static_cast<const uint16_t*>(T.v) + l0);
+            const v4u mq = buf_load16<NT>(rm, o16);
+            const v4u vq = buf_load16<NT>(rv, o16);
             unpack8(mq, L.m);
             unpack8(vq, L.v);
         }
-        if (M::master) load8_f32<NT>(static_cast<const float*>(T.aux), l0, numel, true, L.aux);
-        if (M::kahan) aq = load_v4<NT, 2>(static_cast<const uint16_t*>(T.aux) + l0);
+        if (M::master) {
+            const v4u a0 = buf_load16<NT>(ra, o32), a1 = buf_load16<NT>(ra, o32 + 16u);
+            floats8(a0, a1, L.aux);
+        }
+        if (M::kahan) aq = buf_load16<NT>(ra, o16);
         if (!M::master) unpack8(pq, L.p);
         unpack8(gq, L.g);
         if (M::kahan) unpack8(aq, L.aux);
@@ -445,24 +502,24 @@ __device__ __forceinline__ void general_block(const TensorDesc& T, const StepSca
         if (M::master) load8_f32<false>(static_cast<const float*>(T.aux), l0, numel, false, L.aux);
         if (M::kahan) unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.aux), l0, numel, false), L.aux);
     }
-    u32x4 rp = {}, rm = {}, rv = {};
-    if (!M::rnep) rp = block_bits(gblk, STREAM_P, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+    u32x4 rp_ = {}, rm_ = {}, rv_ = {};
+    if (!M::rnep) rp_ = block_bits(gblk, STREAM_P, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
     if (M::srm) {
-        rm = block_bits(gblk, STREAM_M, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
-        rv = block_bits(gblk, STREAM_V, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+        rm_ = block_bits(gblk, STREAM_M, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+        rv_ = block_bits(gblk, STREAM_V, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
     }
-    update_lane<F, CLIP, 8>(L, S, c, rp.w, rm.w, rv.w);
+    update_lane<F, CLIP, 8>(L, S, c, rp_.w, rm_.w, rv_.w);
     if (full) {
-        store_v4<NT, 2>(T.p + l0, words4(L.po));
+        buf_store16<NT>(rp, o16, words4(L.po));
         if (M::fp32m) {
-            store8_f32<NT>(static_cast<float*>(T.m), l0, numel, true, L.m);
-            store8_f32<NT>(static_cast<float*>(T.v), l0, numel, true, L.v);
+            buf_store16<NT>(rm, o32, bits4lo(L.m)); buf_store16<NT>(rm, o32 + 16u, bits4hi(L.m));
+            buf_store16<NT>(rv, o32, bits4lo(L.v)); buf_store16<NT>(rv, o32 + 16u, bits4hi(L.v));
         } else {
-            store_v4<NT, 2>(static_cast<uint16_t*>(T.m) + l0, words4(L.mo));
-            store_v4<NT, 2>(static_cast<uint16_t*>(T.v) + l0, words4(L.vo));
+            buf_store16<NT>(rm, o16, words4(L.mo));
+            buf_store16<NT>(rv, o16, words4(L.vo));
         }
-        if (M::master) store8_f32<NT>(static_cast<float*>(T.aux), l0, numel, true, L.aux);
-        if (M::kahan) store_v4<NT, 2>(static_cast<uint16_t*>(T.aux) + l0, words4(L.ao));
+        if (M::master) { buf_store16<NT>(ra, o32, bits4lo(L.aux)); buf_store16<NT>(ra, o32 + 16u, bits4hi(L.aux)); }
+        if (M::kahan) buf_store16<NT>(ra, o16, words4(L.ao));
         return;
     }
     store8_bf16<false>(T.p, l0, numel, false, words4(L.po));
@@ -513,15 +570,18 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
         const uint64_t efirst = cl * (uint64_t)(kThreads * 4);
         if (vec && efirst + (uint64_t)(kThreads * 4) <= numel) {          // wave-uniform
             const uint64_t e = efirst + (uint64_t)threadIdx.x * 4;
-            float* mp = static_cast<float*>(T.m) + e;
-            float* vp = static_cast<float*>(T.v) + e;
-            float* xp = static_cast<float*>(T.aux) + e;                    // master parameters
+            const uint32_t o8 = threadIdx.x * 8u, o16 = threadIdx.x * 16u;
+            const rsrc_t rp = chunk_rsrc<uint16_t>(T.p, (int64_t)efirst, kThreads * 4u);
+            const rsrc_t rg = chunk_rsrc<uint16_t>(T.g, (int64_t)efirst, kThreads * 4u);
+            const rsrc_t rm = chunk_rsrc<float>(T.m, (int64_t)efirst, kThreads * 4u);
+            const rsrc_t rv = chunk_rsrc<float>(T.v, (int64_t)efirst, kThreads * 4u);
+            const rsrc_t rx = chunk_rsrc<float>(T.aux, (int64_t)efirst, kThreads * 4u);   // master parameters
             LaneRegs<4> L;
-            if (M::master) floats4(load_v4<NT, 4>(xp), L.aux);
-            else unpack4(load_v2<NT>(T.p + e), L.p);
-            unpack4(load_v2<NT>(T.g + e), L.g);
-            floats4(load_v4<NT, 4>(mp), L.m);
-            floats4(load_v4<NT, 4>(vp), L.v);
+            if (M::master) floats4(buf_load16<NT>(rx, o16), L.aux);
+            else unpack4(buf_load8<NT>(rp, o8), L.p);
+            unpack4(buf_load8<NT>(rg, o8), L.g);
+            floats4(buf_load16<NT>(rm, o16), L.m);
+            floats4(buf_load16<NT>(rv, o16), L.v);
             uint32_t pw[2] = {0, 0};
             if (!M::rnep) {
                 const u32x4 r = block_bits((G0 + e) >> 3, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
@@ -530,22 +590,22 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
                 pw[1] = upper ? r.w[3] : r.w[1];
             }
             update_lane<F, CLIP, 4>(L, S, c, pw, pw, pw);
-            store_v2<NT>(T.p + e, words2(L.po));
-            store_v4<NT, 4>(mp, bits4(L.m));
-            store_v4<NT, 4>(vp, bits4(L.v));
-            if (M::master) store_v4<NT, 4>(xp, bits4(L.aux));
+            buf_store8<NT>(rp, o8, words2(L.po));
+            buf_store16<NT>(rm, o16, bits4(L.m));
+            buf_store16<NT>(rv, o16, bits4(L.v));
+            if (M::master) buf_store16<NT>(rx, o16, bits4(L.aux));
             return;
         }
         // Tail chunk, or counter blocks that do not start at element 0: the chunk's kThreads/2
         // blocks, one whole block per lane.
-        const uint64_t b = cl * (uint64_t)(kThreads / 2) + threadIdx.x;
+        const uint64_t b0 = cl * (uint64_t)(kThreads / 2), b = b0 + threadIdx.x;
         if (threadIdx.x >= kThreads / 2 || b >= nblk) return;
-        general_block<F, CLIP, NT>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b) << 3) - (int64_t)G0);
+        general_block<F, CLIP, NT>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b0) << 3) - (int64_t)G0, threadIdx.x, kThreads / 2);
     } else {
         // BF16 moments: a lane owns one whole block; a chunk is kThreads blocks.
-        const uint64_t b = cl * (uint64_t)kThreads + threadIdx.x;
+        const uint64_t b0 = cl * (uint64_t)kThreads, b = b0 + threadIdx.x;
         if (b >= nblk) return;
-        general_block<F, CLIP, NT>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b) << 3) - (int64_t)G0);
+        general_block<F, CLIP, NT>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b0) << 3) - (int64_t)G0, threadIdx.x, kThreads);
     }
 }
 
@@ -554,20 +614,23 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
 // The memory traffic of the BF16 update with no arithmetic: reads the blocks of p, g, m, v and
 // writes p, m, v back.  `mask` is 0 at run time (the data are unchanged) but unknown to the
 // compiler, so neither the loads nor the stores can be dropped.  Same geometry as the update:
-// one wave per workgroup, one block per lane, nontemporal vector accesses.
+// one wave per workgroup, one block per lane, streaming buffer accesses.
 __global__ __launch_bounds__(kThreads) void stream_probe_kernel(uint16_t* __restrict__ p, const uint16_t* __restrict__ g,
                                                                uint16_t* __restrict__ m, uint16_t* __restrict__ v,
                                                                uint64_t nblk, uint32_t mask)
 {
-    const uint64_t b = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    const uint64_t b0 = (uint64_t)blockIdx.x * kThreads, b = b0 + threadIdx.x;
     if (b >= nblk) return;
-    const uint64_t e = b << 3;
-    const v4u P = load_v4<true, 2>(p + e), G = load_v4<true, 2>(g + e);
-    const v4u M = load_v4<true, 2>(m + e), V = load_v4<true, 2>(v + e);
+    const int64_t e0 = (int64_t)(b0 << 3);
+    const rsrc_t rp = chunk_rsrc<uint16_t>(p, e0, kThreads * 8u), rg = chunk_rsrc<uint16_t>(g, e0, kThreads * 8u);
+    const rsrc_t rm = chunk_rsrc<uint16_t>(m, e0, kThreads * 8u), rv = chunk_rsrc<uint16_t>(v, e0, kThreads * 8u);
+    const uint32_t off = threadIdx.x * 16u;
+    const v4u P = buf_load16<true>(rp, off), G = buf_load16<true>(rg, off);
+    const v4u M = buf_load16<true>(rm, off), V = buf_load16<true>(rv, off);
     const v4u k = G & mask;
-    store_v4<true, 2>(p + e, P ^ k);
-    store_v4<true, 2>(m + e, M ^ k);
-    store_v4<true, 2>(v + e, V ^ k);
+    buf_store16<true>(rp, off, P ^ k);
+    buf_store16<true>(rm, off, M ^ k);
+    buf_store16<true>(rv, off, V ^ k);
 }
 
 // ----------------------------------------------------------------------- standalone SR cast
@@ -583,7 +646,9 @@ __global__ __launch_bounds__(kThreads) void cast_kernel(const float* __restrict_
     const uint64_t efirst = (uint64_t)blockIdx.x * (uint64_t)(kThreads * 4);
     if (efirst + (uint64_t)(kThreads * 4) <= n) {                  // wave-uniform
         const uint64_t e = efirst + (uint64_t)threadIdx.x * 4;
-        const v4u x = load_v4<NT, 4>(src + e);
+        const rsrc_t rs = chunk_rsrc<float>(src, (int64_t)efirst, kThreads * 4u);
+        const rsrc_t rd = chunk_rsrc<uint16_t>(dst, (int64_t)efirst, kThreads * 4u);
+        const v4u x = buf_load16<NT>(rs, threadIdx.x * 16u);
         const u32x4 r = block_bits(e >> 3, STREAM_CAST, tensor_id, step, seed_lo, seed_hi);
         const bool upper = ((e >> 2) & 1u) != 0;
         const uint32_t w0 = upper ? r.w[2] : r.w[0], w1 = upper ? r.w[3] : r.w[1];
@@ -593,7 +658,7 @@ __global__ __launch_bounds__(kThreads) void cast_kernel(const float* __restrict_
         v2u o;
         if (nan) { o.x = sr_pair_nan_safe(y0, y1, w0); o.y = sr_pair_nan_safe(y2, y3, w1); }
         else     { o.x = sr_pair(y0, y1, w0);          o.y = sr_pair(y2, y3, w1); }
-        store_v2<NT>(dst + e, o);
+        buf_store8<NT>(rd, threadIdx.x * 8u, o);
         return;
     }
     // Tail chunk: its kThreads/2 blocks, one per lane, the last one element-wise.
@@ -635,7 +700,10 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(const AccBatch 
     const uint64_t gblk0 = G0 >> 3;
     const uint64_t nblk = ((G0 + numel - 1) >> 3) - gblk0 + 1;
     const bool rne = (B.mode & ACC_RNE) != 0, first = (B.mode & ACC_FIRST) != 0;
-    const uint64_t bfirst = (uint64_t)(chunk - B.chunk_start[ti]) * (uint64_t)(kAccThreads * kAccIters) + threadIdx.x;
+    const uint64_t bchunk = (uint64_t)(chunk - B.chunk_start[ti]) * (uint64_t)(kAccThreads * kAccIters);
+    const uint64_t bfirst = bchunk + threadIdx.x;
+    const int64_t lc0 = (int64_t)((gblk0 + bchunk) << 3) - (int64_t)G0;       // first element of the chunk
+    const rsrc_t ra = chunk_rsrc<uint16_t>(T.acc, lc0, kAccChunkElems), rg = chunk_rsrc<uint16_t>(T.g, lc0, kAccChunkElems);
 
     double sq = 0.0;
 #pragma unroll 2
@@ -644,13 +712,14 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(const AccBatch 
         if (b >= nblk) break;
         const int64_t l0 = (int64_t)((gblk0 + b) << 3) - (int64_t)G0;
         const bool full = block_inside(l0, numel);
+        const uint32_t off = (uint32_t)(it * kAccThreads + threadIdx.x) * 16u;
         float a[8], g[8], s[8];
-        unpack8(load8_bf16<true>(T.g, l0, numel, full), g);
+        unpack8(full ? buf_load16<true>(rg, off) : load8_bf16<false>(T.g, l0, numel, false), g);
         if (first) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) a[j] = 0.0f;
         } else {
-            unpack8(load8_bf16<true>(T.acc, l0, numel, full), a);
+            unpack8(full ? buf_load16<true>(ra, off) : load8_bf16<false>(T.acc, l0, numel, false), a);
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -665,7 +734,8 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(const AccBatch 
             const u32x4 r = block_bits(gblk0 + b, STREAM_ACC, T.tensor_id, B.micro_step, B.seed_lo, B.seed_hi);
             o = any_nan8(s) ? sr8<true>(s, r) : sr8<false>(s, r);
         }
-        store8_bf16<true>(T.acc, l0, numel, full, o);
+        if (full) buf_store16<true>(ra, off, o);
+        else store8_bf16<false>(T.acc, l0, numel, false, o);
         if (B.mode & ACC_NORM) {
             float w[8];
             unpack8(o, w);
@@ -701,7 +771,9 @@ __global__ __launch_bounds__(kNormThreads) void sumsq_partial_kernel(const NormB
     const uint16_t* g = B.t[ti].g;
     const uint64_t numel = B.t[ti].numel;
     const uint64_t nblk = (numel + 7) >> 3;
-    const uint64_t bfirst = (uint64_t)(chunk - B.chunk_start[ti]) * (uint64_t)(kNormThreads * kNormIters) + threadIdx.x;
+    const uint64_t bchunk = (uint64_t)(chunk - B.chunk_start[ti]) * (uint64_t)(kNormThreads * kNormIters);
+    const uint64_t bfirst = bchunk + threadIdx.x;
+    const rsrc_t rg = chunk_rsrc<uint16_t>(g, (int64_t)(bchunk << 3), kNormChunkElems);
 
     double acc = 0.0;
 #pragma unroll 4
@@ -711,7 +783,8 @@ __global__ __launch_bounds__(kNormThreads) void sumsq_partial_kernel(const NormB
         const int64_t l0 = (int64_t)(b << 3);
         const bool full = block_inside(l0, numel);
         float x[8];
-        unpack8(load8_bf16<true>(g, l0, numel, full), x);
+        unpack8(full ? buf_load16<true>(rg, (uint32_t)(it * kNormThreads + threadIdx.x) * 16u)
+                     : load8_bf16<false>(g, l0, numel, false), x);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const double xd = (double)x[j];
