@@ -265,12 +265,14 @@ __device__ __forceinline__ v4u sr8(const float (&y)[8], const u32x4& r)
     return o;
 }
 
+// True in every active lane when any active lane holds a NaN among its eight values (wave-uniform, so
+// that the guarded rounding is a branch and not a per-lane select).
 __device__ __forceinline__ bool any_nan8(const float (&y)[8])
 {
     bool n = false;
 #pragma unroll
     for (int j = 0; j < 8; ++j) n |= (y[j] != y[j]);
-    return n;
+    return __builtin_amdgcn_ballot_w64(n) != 0;
 }
 
 // Largest i in [0, n) with start[i] <= chunk (start[] ascending, start[0] = 0).  Wave-uniform.
@@ -304,7 +306,7 @@ struct Mode {
 // One rounding per operation, in this order (no contraction: the library is built with
 // -ffp-contract=off; sqrt and divide are correctly rounded).
 template <bool CLIP>
-__device__ __forceinline__ void update_elem(const StepScalars& S, float c, float p, float g,
+__device__ __forceinline__ void update_elem(const StepScalars& S, uint32_t variant, float c, float p, float g,
                                             float& m, float& v, float& y, float& sum)
 {
     const float g1 = CLIP ? g * c : g;
@@ -317,12 +319,13 @@ __device__ __forceinline__ void update_elem(const StepScalars& S, float c, float
     const float v1 = t3 + t4;
     // Bias corrections as multiplications by host reciprocals, or (variant) the divisions of
     // Algorithm 1 lines 7-8 as printed; eps outside the root, or (variant) inside it as in
-    // Appendix B.  The variant bits are kernel arguments: the branches are wave-uniform.
+    // Appendix B.  `variant` is 0 at compile time in the kernels of the default arithmetic
+    // (straight-line code) and a kernel argument in the others (wave-uniform branches).
     float mh, vh, d;
-    if (S.variant & VARIANT_DIV_BIAS) { mh = m1 / S.bc1; vh = v1 / S.bc2; }
-    else                              { mh = m1 * S.rbc1; vh = v1 * S.rbc2; }
-    if (S.variant & VARIANT_EPS_IN_ROOT) { const float ve = vh + S.eps; d = __builtin_sqrtf(ve); }
-    else                                 { d = __builtin_sqrtf(vh) + S.eps; }
+    if (variant & VARIANT_DIV_BIAS) { mh = m1 / S.bc1; vh = v1 / S.bc2; }
+    else                            { mh = m1 * S.rbc1; vh = v1 * S.rbc2; }
+    if (variant & VARIANT_EPS_IN_ROOT) { const float ve = vh + S.eps; d = __builtin_sqrtf(ve); }
+    else                               { d = __builtin_sqrtf(vh) + S.eps; }
     const float q = mh / d;
     const float a = S.lr * q;
     const float w = S.lw * p;
@@ -342,20 +345,25 @@ struct LaneRegs {
 // The update of a lane's N elements and the write-back roundings.  pw, mw, vw: the random words of
 // the lane's elements for the three output streams (16 bits per element; only read where the mode
 // rounds stochastically).
-template <uint32_t F, bool CLIP, int N>
+template <uint32_t F, bool CLIP, bool VAR, int N>
 __device__ __forceinline__ void update_lane(LaneRegs<N>& L, const StepScalars& S, float c,
                                             const uint32_t* pw, const uint32_t* mw, const uint32_t* vw)
 {
     using M = Mode<F>;
+    const uint32_t variant = VAR ? S.variant : 0u;
     float y[N], sum[N];
 #pragma unroll
     for (int j = 0; j < N; ++j)
-        update_elem<CLIP>(S, c, M::master ? L.aux[j] : L.p[j], L.g[j], L.m[j], L.v[j], y[j], sum[j]);
-    // A NaN in m' or v' always makes y NaN, so one test covers all three outputs.
+        update_elem<CLIP>(S, variant, c, M::master ? L.aux[j] : L.p[j], L.g[j], L.m[j], L.v[j], y[j], sum[j]);
+    // A NaN in m' or v' always makes y NaN, so one test covers all three outputs; the test is
+    // folded over the wave so that the guarded roundings are a branch no wave takes in practice
+    // (as per-lane selects they were 100 of the 680 vector instructions of a wave).
     bool nan = false;
     if (!M::rnep || M::srm) {
+        bool lane_nan = false;
 #pragma unroll
-        for (int j = 0; j < N; ++j) nan |= (y[j] != y[j]);
+        for (int j = 0; j < N; ++j) lane_nan |= (y[j] != y[j]);
+        nan = __builtin_amdgcn_ballot_w64(lane_nan) != 0;          // wave-uniform
     }
     if (M::master) {
         // O2-style mixed precision: the master stays binary32, the model copy is RNE(master)
@@ -385,10 +393,12 @@ __device__ __forceinline__ void update_lane(LaneRegs<N>& L, const StepScalars& S
     } else if (M::rnep) {
 #pragma unroll
         for (int j = 0; j < N / 2; ++j) L.po[j] = rne_pair(y[2 * j], y[2 * j + 1]);
+    } else if (nan) {
+#pragma unroll
+        for (int j = 0; j < N / 2; ++j) L.po[j] = sr_pair_nan_safe(y[2 * j], y[2 * j + 1], pw[j]);
     } else {
 #pragma unroll
-        for (int j = 0; j < N / 2; ++j)
-            L.po[j] = nan ? sr_pair_nan_safe(y[2 * j], y[2 * j + 1], pw[j]) : sr_pair(y[2 * j], y[2 * j + 1], pw[j]);
+        for (int j = 0; j < N / 2; ++j) L.po[j] = sr_pair(y[2 * j], y[2 * j + 1], pw[j]);
     }
     if (M::rnem) {
 #pragma unroll
@@ -397,10 +407,18 @@ __device__ __forceinline__ void update_lane(LaneRegs<N>& L, const StepScalars& S
             L.vo[j] = rne_pair(L.v[2 * j], L.v[2 * j + 1]);
         }
     } else if (M::srm) {
+        if (nan) {
 #pragma unroll
-        for (int j = 0; j < N / 2; ++j) {
-            L.mo[j] = nan ? sr_pair_nan_safe(L.m[2 * j], L.m[2 * j + 1], mw[j]) : sr_pair(L.m[2 * j], L.m[2 * j + 1], mw[j]);
-            L.vo[j] = nan ? sr_pair_nan_safe(L.v[2 * j], L.v[2 * j + 1], vw[j]) : sr_pair(L.v[2 * j], L.v[2 * j + 1], vw[j]);
+            for (int j = 0; j < N / 2; ++j) {
+                L.mo[j] = sr_pair_nan_safe(L.m[2 * j], L.m[2 * j + 1], mw[j]);
+                L.vo[j] = sr_pair_nan_safe(L.v[2 * j], L.v[2 * j + 1], vw[j]);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < N / 2; ++j) {
+                L.mo[j] = sr_pair(L.m[2 * j], L.m[2 * j + 1], mw[j]);
+                L.vo[j] = sr_pair(L.v[2 * j], L.v[2 * j + 1], vw[j]);
+            }
         }
     }
 }
@@ -445,83 +463,95 @@ __device__ __forceinline__ v4u bits4hi(const float (&x)[8])
 __device__ __forceinline__ v4u words4(const uint32_t (&w)[4]) { v4u r; r.x = w[0]; r.y = w[1]; r.z = w[2]; r.w = w[3]; return r; }
 __device__ __forceinline__ v2u words2(const uint32_t (&w)[2]) { v2u r; r.x = w[0]; r.y = w[1]; return r; }
 
-// One whole block of a lane, at any element offset.  lc0: element index (relative to the tensor's
-// first element) of the first block of the workgroup's chunk of `span` blocks; the lane's block is
-// the lane-th of the chunk.  Buffer accesses through the chunk's descriptors when the block lies
-// inside the tensor, element-wise accesses with bounds for the first and last block of a tensor
-// whose counter blocks do not start at element 0.
-template <uint32_t F, bool CLIP, bool NT>
-__device__ __forceinline__ void general_block(const TensorDesc& T, const StepScalars& S, float c,
-                                              uint64_t gblk, int64_t lc0, uint32_t lane, uint32_t span)
+// The random words of a lane's block for the three output streams (only those the mode uses).
+template <uint32_t F>
+__device__ __forceinline__ void block_draws(const TensorDesc& T, const StepScalars& S, uint64_t gblk,
+                                            u32x4& rp, u32x4& rm, u32x4& rv)
 {
     using M = Mode<F>;
-    const uint64_t numel = T.numel;
-    const int64_t l0 = lc0 + (int64_t)lane * 8;
-    const bool full = block_inside(l0, numel);
+    rp = {}; rm = {}; rv = {};
+    if (!M::rnep) rp = block_bits(gblk, STREAM_P, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+    if (M::srm) {
+        rm = block_bits(gblk, STREAM_M, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+        rv = block_bits(gblk, STREAM_V, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+    }
+}
+
+// One whole block of a lane that lies inside its tensor, as straight-line code: the block's loads
+// are issued first (buffer accesses through the descriptors of the workgroup's chunk: `span`
+// blocks starting at element lc0 of the tensor, the lane's block is the lane-th), the Philox
+// draws, which need no data, run while the loads are in flight, then the update and the stores.
+template <uint32_t F, bool CLIP, bool NT, bool VAR>
+__device__ __forceinline__ void inner_block(const TensorDesc& T, const StepScalars& S, float c,
+                                            uint64_t gblk, int64_t lc0, uint32_t lane, uint32_t span)
+{
+    using M = Mode<F>;
     const uint32_t o16 = lane * 16u, o32 = lane * 32u;          // byte offsets in BF16 / binary32 arrays
     const rsrc_t rp = chunk_rsrc<uint16_t>(T.p, lc0, span * 8u);
     const rsrc_t rg = chunk_rsrc<uint16_t>(T.g, lc0, span * 8u);
     const rsrc_t rm = M::fp32m ? chunk_rsrc<float>(T.m, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.m, lc0, span * 8u);
     const rsrc_t rv = M::fp32m ? chunk_rsrc<float>(T.v, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.v, lc0, span * 8u);
     const rsrc_t ra = M::master ? chunk_rsrc<float>(T.aux, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.aux, lc0, span * 8u);
-    LaneRegs<8> L;
-    if (full) {
-        // all loads of the block back to back, one vector each (two for binary32 arrays)
-        v4u pq = {}, aq = {};
-        if (!M::master) pq = buf_load16<NT>(rp, o16);
-        const v4u gq = buf_load16<NT>(rg, o16);
-        if (M::fp32m) {
-            const v4u m0 = buf_load16<NT>(rm, o32), m1 = buf_load16<NT>(rm, o32 + 16u);
-            const v4u v0 = buf_load16<NT>(rv, o32), v1 = buf_load16<NT>(rv, o32 + 16u);
-            floats8(m0, m1, L.m);
-            floats8(v0, v1, L.v);
-        } else {
-            const v4u mq = buf_load16<NT>(rm, o16);
-            const v4u vq = buf_load16<NT>(rv, o16);
-            unpack8(mq, L.m);
-            unpack8(vq, L.v);
-        }
-        if (M::master) {
-            const v4u a0 = buf_load16<NT>(ra, o32), a1 = buf_load16<NT>(ra, o32 + 16u);
-            floats8(a0, a1, L.aux);
-        }
-        if (M::kahan) aq = buf_load16<NT>(ra, o16);
-        if (!M::master) unpack8(pq, L.p);
-        unpack8(gq, L.g);
-        if (M::kahan) unpack8(aq, L.aux);
+    v4u pq = {}, aq = {}, mq0 = {}, mq1 = {}, vq0 = {}, vq1 = {}, xq0 = {}, xq1 = {};
+    if (!M::master) pq = buf_load16<NT>(rp, o16);
+    const v4u gq = buf_load16<NT>(rg, o16);
+    if (M::fp32m) {
+        mq0 = buf_load16<NT>(rm, o32); mq1 = buf_load16<NT>(rm, o32 + 16u);
+        vq0 = buf_load16<NT>(rv, o32); vq1 = buf_load16<NT>(rv, o32 + 16u);
     } else {
-        if (!M::master) unpack8(load8_bf16<false>(T.p, l0, numel, false), L.p);
-        unpack8(load8_bf16<false>(T.g, l0, numel, false), L.g);
-        if (M::fp32m) {
-            load8_f32<false>(static_cast<const float*>(T.m), l0, numel, false, L.m);
-            load8_f32<false>(static_cast<const float*>(T.v), l0, numel, false, L.v);
-        } else {
-            unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.m), l0, numel, false), L.m);
-            unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.v), l0, numel, false), L.v);
-        }
-        if (M::master) load8_f32<false>(static_cast<const float*>(T.aux), l0, numel, false, L.aux);
-        if (M::kahan) unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.aux), l0, numel, false), L.aux);
+        mq0 = buf_load16<NT>(rm, o16);
+        vq0 = buf_load16<NT>(rv, o16);
     }
-    u32x4 rp_ = {}, rm_ = {}, rv_ = {};
-    if (!M::rnep) rp_ = block_bits(gblk, STREAM_P, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
-    if (M::srm) {
-        rm_ = block_bits(gblk, STREAM_M, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
-        rv_ = block_bits(gblk, STREAM_V, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+    if (M::master) { xq0 = buf_load16<NT>(ra, o32); xq1 = buf_load16<NT>(ra, o32 + 16u); }
+    if (M::kahan) aq = buf_load16<NT>(ra, o16);
+
+    u32x4 dp, dm, dv;
+    block_draws<F>(T, S, gblk, dp, dm, dv);
+
+    LaneRegs<8> L;
+    if (!M::master) unpack8(pq, L.p);
+    unpack8(gq, L.g);
+    if (M::fp32m) { floats8(mq0, mq1, L.m); floats8(vq0, vq1, L.v); }
+    else          { unpack8(mq0, L.m); unpack8(vq0, L.v); }
+    if (M::master) floats8(xq0, xq1, L.aux);
+    if (M::kahan) unpack8(aq, L.aux);
+    update_lane<F, CLIP, VAR, 8>(L, S, c, dp.w, dm.w, dv.w);
+    buf_store16<NT>(rp, o16, words4(L.po));
+    if (M::fp32m) {
+        buf_store16<NT>(rm, o32, bits4lo(L.m)); buf_store16<NT>(rm, o32 + 16u, bits4hi(L.m));
+        buf_store16<NT>(rv, o32, bits4lo(L.v)); buf_store16<NT>(rv, o32 + 16u, bits4hi(L.v));
+    } else {
+        buf_store16<NT>(rm, o16, words4(L.mo));
+        buf_store16<NT>(rv, o16, words4(L.vo));
     }
-    update_lane<F, CLIP, 8>(L, S, c, rp_.w, rm_.w, rv_.w);
-    if (full) {
-        buf_store16<NT>(rp, o16, words4(L.po));
-        if (M::fp32m) {
-            buf_store16<NT>(rm, o32, bits4lo(L.m)); buf_store16<NT>(rm, o32 + 16u, bits4hi(L.m));
-            buf_store16<NT>(rv, o32, bits4lo(L.v)); buf_store16<NT>(rv, o32 + 16u, bits4hi(L.v));
-        } else {
-            buf_store16<NT>(rm, o16, words4(L.mo));
-            buf_store16<NT>(rv, o16, words4(L.vo));
-        }
-        if (M::master) { buf_store16<NT>(ra, o32, bits4lo(L.aux)); buf_store16<NT>(ra, o32 + 16u, bits4hi(L.aux)); }
-        if (M::kahan) buf_store16<NT>(ra, o16, words4(L.ao));
-        return;
+    if (M::master) { buf_store16<NT>(ra, o32, bits4lo(L.aux)); buf_store16<NT>(ra, o32 + 16u, bits4hi(L.aux)); }
+    if (M::kahan) buf_store16<NT>(ra, o16, words4(L.ao));
+}
+
+// A block that straddles the first or last element of its tensor (counter blocks that do not
+// start at element 0, or a size that is not a multiple of 8): element-wise accesses with bounds,
+// zeros outside [0, numel).
+template <uint32_t F, bool CLIP, bool VAR>
+__device__ __forceinline__ void edge_block(const TensorDesc& T, const StepScalars& S, float c,
+                                           uint64_t gblk, int64_t l0)
+{
+    using M = Mode<F>;
+    const uint64_t numel = T.numel;
+    LaneRegs<8> L;
+    if (!M::master) unpack8(load8_bf16<false>(T.p, l0, numel, false), L.p);
+    unpack8(load8_bf16<false>(T.g, l0, numel, false), L.g);
+    if (M::fp32m) {
+        load8_f32<false>(static_cast<const float*>(T.m), l0, numel, false, L.m);
+        load8_f32<false>(static_cast<const float*>(T.v), l0, numel, false, L.v);
+    } else {
+        unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.m), l0, numel, false), L.m);
+        unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.v), l0, numel, false), L.v);
     }
+    if (M::master) load8_f32<false>(static_cast<const float*>(T.aux), l0, numel, false, L.aux);
+    if (M::kahan) unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.aux), l0, numel, false), L.aux);
+    u32x4 dp, dm, dv;
+    block_draws<F>(T, S, gblk, dp, dm, dv);
+    update_lane<F, CLIP, VAR, 8>(L, S, c, dp.w, dm.w, dv.w);
     store8_bf16<false>(T.p, l0, numel, false, words4(L.po));
     if (M::fp32m) {
         store8_f32<false>(static_cast<float*>(T.m), l0, numel, false, L.m);
@@ -534,9 +564,20 @@ __device__ __forceinline__ void general_block(const TensorDesc& T, const StepSca
     if (M::kahan) store8_bf16<false>(static_cast<uint16_t*>(T.aux), l0, numel, false, words4(L.ao));
 }
 
+// One whole block of a lane, at any element offset (see inner_block and edge_block).
+template <uint32_t F, bool CLIP, bool NT, bool VAR>
+__device__ __forceinline__ void general_block(const TensorDesc& T, const StepScalars& S, float c,
+                                              uint64_t gblk, int64_t lc0, uint32_t lane, uint32_t span)
+{
+    const int64_t l0 = lc0 + (int64_t)lane * 8;
+    if (block_inside(l0, T.numel)) inner_block<F, CLIP, NT, VAR>(T, S, c, gblk, lc0, lane, span);
+    else edge_block<F, CLIP, VAR>(T, S, c, gblk, l0);
+}
+
 // F: SR_FLAG_* bits of the step.  CLIP: scale gradients by min(1, max_norm/(norm + 1e-6)).
-// NT: nontemporal loads and stores.  One wave per workgroup, one chunk per workgroup.
-template <uint32_t F, bool CLIP, bool NT>
+// NT: streaming cache policy.  VAR: the arithmetic variants of StepScalars::variant are honoured
+// (false: default arithmetic only).  One wave per workgroup, one chunk per workgroup.
+template <uint32_t F, bool CLIP, bool NT, bool VAR>
 __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
 {
     using M = Mode<F>;
@@ -589,7 +630,7 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
                 pw[0] = upper ? r.w[2] : r.w[0];
                 pw[1] = upper ? r.w[3] : r.w[1];
             }
-            update_lane<F, CLIP, 4>(L, S, c, pw, pw, pw);
+            update_lane<F, CLIP, VAR, 4>(L, S, c, pw, pw, pw);
             buf_store8<NT>(rp, o8, words2(L.po));
             buf_store16<NT>(rm, o16, bits4(L.m));
             buf_store16<NT>(rv, o16, bits4(L.v));
@@ -600,12 +641,12 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
         // blocks, one whole block per lane.
         const uint64_t b0 = cl * (uint64_t)(kThreads / 2), b = b0 + threadIdx.x;
         if (threadIdx.x >= kThreads / 2 || b >= nblk) return;
-        general_block<F, CLIP, NT>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b0) << 3) - (int64_t)G0, threadIdx.x, kThreads / 2);
+        general_block<F, CLIP, NT, VAR>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b0) << 3) - (int64_t)G0, threadIdx.x, kThreads / 2);
     } else {
         // BF16 moments: a lane owns one whole block; a chunk is kThreads blocks.
         const uint64_t b0 = cl * (uint64_t)kThreads, b = b0 + threadIdx.x;
         if (b >= nblk) return;
-        general_block<F, CLIP, NT>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b0) << 3) - (int64_t)G0, threadIdx.x, kThreads);
+        general_block<F, CLIP, NT, VAR>(T, S, c, gblk0 + b, (int64_t)((gblk0 + b0) << 3) - (int64_t)G0, threadIdx.x, kThreads);
     }
 }
 
@@ -654,7 +695,7 @@ __global__ __launch_bounds__(kThreads) void cast_kernel(const float* __restrict_
         const uint32_t w0 = upper ? r.w[2] : r.w[0], w1 = upper ? r.w[3] : r.w[1];
         const float y0 = __uint_as_float(x.x), y1 = __uint_as_float(x.y);
         const float y2 = __uint_as_float(x.z), y3 = __uint_as_float(x.w);
-        const bool nan = (y0 != y0) | (y1 != y1) | (y2 != y2) | (y3 != y3);
+        const bool nan = __builtin_amdgcn_ballot_w64((y0 != y0) | (y1 != y1) | (y2 != y2) | (y3 != y3)) != 0;
         v2u o;
         if (nan) { o.x = sr_pair_nan_safe(y0, y1, w0); o.y = sr_pair_nan_safe(y2, y3, w1); }
         else     { o.x = sr_pair(y0, y1, w0);          o.y = sr_pair(y2, y3, w1); }

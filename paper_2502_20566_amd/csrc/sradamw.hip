@@ -41,12 +41,20 @@ constexpr uint64_t kBlocksPerChunkBf16 = (uint64_t)kThreads;
 constexpr uint64_t kBlocksPerChunkFp32 = (uint64_t)kThreads / 2;
 constexpr uint32_t kMaxGrid = 0x7FFFFFFFu;
 
+template <uint32_t F, bool VAR>
+hipError_t launch_adamw_v(bool clip, const AdamwBatch& batch, uint32_t n_chunks, hipStream_t stream)
+{
+    if (clip) hipLaunchKernelGGL((adamw_kernel<F, true, kNT, VAR>), dim3(n_chunks), dim3(kThreads), 0, stream, batch);
+    else      hipLaunchKernelGGL((adamw_kernel<F, false, kNT, VAR>), dim3(n_chunks), dim3(kThreads), 0, stream, batch);
+    return hipGetLastError();
+}
+
+// The default arithmetic runs in kernels compiled without the variant branches.
 template <uint32_t F>
 hipError_t launch_adamw(bool clip, const AdamwBatch& batch, uint32_t n_chunks, hipStream_t stream)
 {
-    if (clip) hipLaunchKernelGGL((adamw_kernel<F, true, kNT>), dim3(n_chunks), dim3(kThreads), 0, stream, batch);
-    else      hipLaunchKernelGGL((adamw_kernel<F, false, kNT>), dim3(n_chunks), dim3(kThreads), 0, stream, batch);
-    return hipGetLastError();
+    return batch.s.variant ? launch_adamw_v<F, true>(clip, batch, n_chunks, stream)
+                           : launch_adamw_v<F, false>(clip, batch, n_chunks, stream);
 }
 
 // The flag combinations that exist as kernels (normalised: RNE_MOMENTS dropped with FP32 moments).
