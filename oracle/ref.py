@@ -60,6 +60,15 @@ def lib():
         L.ref_sr_cast_f32_bf16.argtypes = [f32p, u16p, C.c_uint64, C.c_uint64, C.c_uint32,
                                            C.c_uint32, C.c_uint64, C.c_int]
         L.ref_sr_cast_f32_bf16.restype = None
+        L.ref_fp8_decode.argtypes = [C.c_uint32, C.c_int]
+        L.ref_fp8_decode.restype = C.c_double
+        L.ref_r32.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint32]
+        L.ref_r32.restype = C.c_uint32
+        L.ref_sr_round_fp8.argtypes = [C.c_float, C.c_uint32, C.c_int]
+        L.ref_sr_round_fp8.restype = C.c_uint8
+        L.ref_sr_cast_f32_fp8.argtypes = [f32p, C.POINTER(C.c_uint8), C.c_uint64, C.c_int, C.c_uint64,
+                                          C.c_uint32, C.c_uint32, C.c_uint64, C.c_int]
+        L.ref_sr_cast_f32_fp8.restype = None
         L.ref_adamw_scalars.argtypes = [C.c_float] * 5 + [C.c_uint32, f32p, C.c_float,
                                                           C.POINTER(Scalars)]
         L.ref_adamw_scalars.restype = None
@@ -158,6 +167,32 @@ def sr_cast_f32_bf16(src: np.ndarray, seed, step, tensor_id, elem_offset=0, nthr
     dst = np.empty(src.shape, dtype=np.uint16)
     lib().ref_sr_cast_f32_bf16(_f32(src), _u16(dst), src.size, seed, step, tensor_id,
                                elem_offset, nthreads)
+    return dst
+
+
+# ------------------------------------------------------ 8-bit formats (extension)
+
+E4M3, E5M2 = 0, 1
+
+
+def fp8_decode(code: int, fmt: int) -> float:
+    return float(lib().ref_fp8_decode(code, fmt))
+
+
+def r32(seed, step, tensor_id, i, stream) -> int:
+    return int(lib().ref_r32(seed, step, tensor_id, i, stream))
+
+
+def sr_round_fp8(y, r, fmt: int) -> int:
+    """One value; y is converted to binary32 first (a NaN keeps its sign, not its payload)."""
+    return int(lib().ref_sr_round_fp8(np.float32(y), r, fmt))
+
+
+def sr_cast_f32_fp8(src: np.ndarray, fmt: int, seed, step, tensor_id, elem_offset=0, nthreads=0):
+    src = np.ascontiguousarray(src, dtype=np.float32)
+    dst = np.empty(src.shape, dtype=np.uint8)
+    lib().ref_sr_cast_f32_fp8(_f32(src), dst.ctypes.data_as(C.POINTER(C.c_uint8)), src.size, fmt,
+                              seed, step, tensor_id, elem_offset, nthreads)
     return dst
 
 

@@ -32,7 +32,10 @@
  * exact unbiasedness and second moment, Philox known-answer vectors of the
  * Random123 distribution, 10^4-seed mean test, the random-walk example of
  * Section 2.2, Adam step-1 closed form, exact-rational evaluation of
- * Algorithm 1 on tiny inputs, torch.optim.AdamW on FP32 state, exact norms.
+ * Algorithm 1 on tiny inputs, torch.optim.AdamW on FP32 state, exact norms;
+ * for the 8-bit extension (the conclusion's FP8 remark; the formats are the
+ * OCP ones, not the paper's): torch's float8 decoders for the grids, exact
+ * rational thresholds on brute-force neighbours, torch's nearest conversion.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -208,6 +211,102 @@ void ref_sr_cast_f32_bf16(const float* src, uint16_t* dst, uint64_t n,
     for (int64_t i = 0; i < (int64_t)n; ++i) {
         uint32_t r = ref_r16(seed, step, tensor_id, elem_offset + (uint64_t)i, 3u);
         dst[i] = ref_sr_round(src[i], r);
+    }
+}
+
+/* ------------------------------------------ 8-bit formats (extension) --- */
+
+/* The paper's conclusion names 8-bit floating point as the next target of
+ * stochastic rounding and specifies nothing; Eq.(2) applies to any grid.  The
+ * two grids here are the OCP 8-bit floating-point formats (OFP8):
+ *   format 0, E4M3: 1 sign, 4 exponent bits (bias 7), 3 mantissa bits; no
+ *     infinities; S.1111.111 is the only NaN; largest finite value 448.
+ *   format 1, E5M2: 1 sign, 5 exponent bits (bias 15), 2 mantissa bits;
+ *     S.11111.00 is infinity, S.11111.{01,10,11} are NaNs; largest finite 57344.
+ * Exponent field 0 holds zero and the subnormals (no implicit leading one). */
+
+/* Value of code `code` (0..255): NaN for a NaN code, +-inf for an infinity. */
+double ref_fp8_decode(uint32_t code, int format)
+{
+    int mb = format == 0 ? 3 : 2, bias = format == 0 ? 7 : 15;
+    int sign = (code >> 7) & 1;
+    int e = (int)((code & 0x7Fu) >> mb);
+    int m = (int)(code & ((1u << mb) - 1u));
+    double v;
+    if (format == 0 && (code & 0x7Fu) == 0x7Fu) return NAN;
+    if (format == 1 && e == 31) v = (m == 0) ? INFINITY : NAN;
+    else if (e == 0) v = ldexp((double)m, 1 - bias - mb);
+    else v = ldexp((double)((1 << mb) + m), e - bias - mb);
+    return sign ? -v : v;
+}
+
+/* The 32 random bits of element i: word i mod 4 of the Philox block i div 4. */
+uint32_t ref_r32(uint64_t seed, uint32_t step, uint32_t tensor_id, uint64_t i, uint32_t stream)
+{
+    uint64_t blk = i >> 2;
+    uint32_t ctr[4], key[2], w[4];
+    ctr[0] = (uint32_t)(blk & 0xFFFFFFFFu);
+    ctr[1] = (stream << 29) | (uint32_t)(blk >> 32);
+    ctr[2] = tensor_id;
+    ctr[3] = step;
+    key[0] = (uint32_t)(seed & 0xFFFFFFFFu);
+    key[1] = (uint32_t)(seed >> 32);
+    ref_philox4x32_10(ctr, key, w);
+    return w[i & 3u];
+}
+
+/* Eq.(2) on an 8-bit grid, by the interval definition on VALUES: lo = largest
+ * grid magnitude <= |y|, hi = next one, k = floor(2^32 (|y|-lo)/(hi-lo)), and
+ * the magnitude becomes hi exactly when r32 + k >= 2^32 (probability k/2^32,
+ * which is (|y|-lo)/(hi-lo) itself whenever that has at most 32 fractional
+ * bits: always for |y| at or above the smallest subnormal times 2^-9).  Sign
+ * kept.  Out of range: E5M2 follows the binary16-like rule (a magnitude above
+ * 57344 has hi = 65536, emitted as infinity; infinities pass); E4M3 has no
+ * infinity and saturates (magnitudes >= 448, infinities included, become 448).
+ * NaN becomes S.1111111 in either format. */
+uint8_t ref_sr_round_fp8(float y, uint32_t r32, int format)
+{
+    const int mb = format == 0 ? 3 : 2, emin = format == 0 ? -6 : -14;
+    const double maxfin = format == 0 ? 448.0 : 57344.0;
+    uint32_t bits; memcpy(&bits, &y, 4);
+    const uint8_t sign = (uint8_t)((bits >> 31) << 7);
+    if (y != y) return (uint8_t)(sign | 0x7Fu);
+    double a = fabs((double)y);
+    double mag;
+    if (format == 0 && a >= maxfin) mag = maxfin;
+    else if (isinf(a)) mag = INFINITY;
+    else if (a == 0.0) mag = 0.0;
+    else {
+        int e2; (void)frexp(a, &e2);                 /* a = f 2^e2, f in [0.5, 1)  */
+        int E = e2 - 1; if (E < emin) E = emin;      /* exponent of the grid cell  */
+        double spacing = ldexp(1.0, E - mb);
+        double t = a / spacing;                      /* exact: power-of-two scale  */
+        double n = floor(t);
+        double k = floor((t - n) * 4294967296.0);    /* t - n exact; scaled exactly */
+        if ((double)r32 + k >= 4294967296.0) n += 1.0;
+        mag = n * spacing;
+        if (mag > maxfin) mag = INFINITY;            /* E5M2 only: hi = 65536      */
+    }
+    /* encode: the code whose decoded magnitude is mag (it exists by construction) */
+    for (uint32_t c = 0; c < 128u; ++c) {
+        double v = ref_fp8_decode(c, format);
+        if (v == mag) return (uint8_t)(sign | c);
+    }
+    abort();
+}
+
+/* dst[i] = Q_SR(src[i]; r32(seed, step, tensor_id, elem_offset + i, stream 5)). */
+void ref_sr_cast_f32_fp8(const float* src, uint8_t* dst, uint64_t n, int format,
+                         uint64_t seed, uint32_t step, uint32_t tensor_id,
+                         uint64_t elem_offset, int nthreads)
+{
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+    #pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < (int64_t)n; ++i) {
+        uint32_t r = ref_r32(seed, step, tensor_id, elem_offset + (uint64_t)i, 5u);
+        dst[i] = ref_sr_round_fp8(src[i], r, format);
     }
 }
 
