@@ -8,7 +8,7 @@ moments warm-started by 100 seeded steps).  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--warm-steps N]
                   [--cpu-seconds S] [--no-cpu-baseline] [--mode M] [--graph]
-  python bench.py --op cast|accumulate|accumulate_norm [--config N]   (the other two entry points,
+  python bench.py --op cast|cast_e4m3|cast_e5m2|accumulate|accumulate_norm [--config N]   (the other two entry points,
                   on an array of the config's size; their own metric, not the headline one)
 """
 import argparse
@@ -123,20 +123,34 @@ def run_aux_op(args, torch, np, B, W, cfg):
     threads = min(ref.max_threads(), os.cpu_count() or 1)
     n_cpu = min(n, 1 << 26) & ~7 or n
     lo = ((n - n_cpu) // 2) & ~7
-    if args.op == "cast":
+    if args.op.startswith("cast"):
         src = torch.empty(n, dtype=torch.float32, device=dev)
         for k, at in enumerate(range(0, n, 1 << 28)):            # generated in pieces of 2^28 elements
             piece = src[at:at + (1 << 28)]
             piece.copy_(W.make_cast_input(piece.numel(), dev, W.data_seed(cfg.index, 900 + k)))
-        dst = torch.empty(n, dtype=torch.bfloat16, device=dev)
-        fn = lambda: B.sr_cast_f32_bf16(src, dst, seed, 7, tid)
-        bpe, kernel, metric = 6, "cast_kernel", "sr_cast_elements_per_sec"
-        wall, dev_ms = time_launches(torch, np, fn, args.warmup, args.steps)
         host = src[lo:lo + n_cpu].cpu().numpy()
-        t0 = time.perf_counter()
-        want = ref.sr_cast_f32_bf16(host, seed, 7, tid, elem_offset=lo, nthreads=threads)
-        dt = time.perf_counter() - t0
-        bad = int((W.bf16_to_u16_numpy(dst[lo:lo + n_cpu]) != want).sum())
+        if args.op == "cast":
+            dst = torch.empty(n, dtype=torch.bfloat16, device=dev)
+            fn = lambda: B.sr_cast_f32_bf16(src, dst, seed, 7, tid)
+            bpe, kernel, metric = 6, "cast_kernel", "sr_cast_elements_per_sec"
+            wall, dev_ms = time_launches(torch, np, fn, args.warmup, args.steps)
+            t0 = time.perf_counter()
+            want = ref.sr_cast_f32_bf16(host, seed, 7, tid, elem_offset=lo, nthreads=threads)
+            dt = time.perf_counter() - t0
+            bad = int((W.bf16_to_u16_numpy(dst[lo:lo + n_cpu]) != want).sum())
+        else:                                                    # 8-bit formats: 4 B read + 1 B written
+            fmt = B.SR_FP8_E4M3 if args.op == "cast_e4m3" else B.SR_FP8_E5M2
+            ofmt = ref.E4M3 if args.op == "cast_e4m3" else ref.E5M2
+            dst = torch.empty(n, dtype=torch.uint8, device=dev)
+            fn = lambda: B.sr_cast_f32_fp8(src, dst, fmt, seed, 7, tid)
+            bpe, kernel, metric = 5, "cast_fp8_kernel", "sr_cast_fp8_elements_per_sec"
+            wall, dev_ms = time_launches(torch, np, fn, args.warmup, args.steps)
+            n_cpu = min(n_cpu, 1 << 24)                          # the value-based 8-bit oracle is slow
+            host = host[:n_cpu]
+            t0 = time.perf_counter()
+            want = ref.sr_cast_f32_fp8(host, ofmt, seed, 7, tid, elem_offset=lo, nthreads=threads)
+            dt = time.perf_counter() - t0
+            bad = int((dst[lo:lo + n_cpu].cpu().numpy() != want).sum())
     else:
         with_norm = args.op == "accumulate_norm"
         acc = W.make_grads(flat, dev, W.data_seed(cfg.index, 901), cfg.grad_std)[0]
@@ -185,7 +199,8 @@ def main():
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--mode", choices=sorted(MODES), default=None,
                     help="step variant (default: the config's own: sr, or fp32_moments for config 4)")
-    ap.add_argument("--op", choices=("step", "cast", "accumulate", "accumulate_norm"), default="step")
+    ap.add_argument("--op", choices=("step", "cast", "cast_e4m3", "cast_e5m2", "accumulate", "accumulate_norm"),
+                    default="step")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time its replays (same step number "
                          "on every replay; removes launch gaps of many-tensor lists)")

@@ -116,6 +116,28 @@ int sr_cast_f32_bf16(const float* d_src, void* d_dst, uint64_t n,
                      uint64_t seed, uint32_t step, uint32_t tensor_id, void* stream);
 
 /*
+ * Extension: stochastic rounding of binary32 to an 8-bit floating-point format
+ * (the paper's conclusion names FP8 as the next target of SR and specifies
+ * nothing; Eq.(2) of Section 2.1 is applied to the grid of the chosen OCP 8-bit
+ * format).  format = SR_FP8_E4M3: 4 exponent bits (bias 7), 3 mantissa bits, no
+ * infinities, largest finite value 448; magnitudes >= 448 and infinities
+ * saturate to 448.  format = SR_FP8_E5M2: 5 exponent bits (bias 15), 2 mantissa
+ * bits, binary16-like: a magnitude above 57344 rounds to infinity with the
+ * probability Eq.(2) gives for an upper neighbour 65536, infinities pass.
+ * Subnormals of both formats are produced; NaN becomes S.1111111.  Element i
+ * draws 32 random bits: word i&3 of Philox4x32-10(counter = (i>>2 low word,
+ * 5<<29 | i>>2 high bits, tensor_id, step), key = seed); with lo <= |v| < hi
+ * adjacent grid magnitudes and k = floor(2^32 (|v|-lo)/(hi-lo)) the result is
+ * hi exactly when r32 + k >= 2^32.  d_src: binary32 [n] (4-byte aligned),
+ * d_dst: one byte per element [n], both device, must not overlap; n <= 2^61;
+ * n == 0 is a no-op.  SR_ERR_ARG for an unknown format.
+ */
+#define SR_FP8_E4M3 0u
+#define SR_FP8_E5M2 1u
+int sr_cast_f32_fp8(const float* d_src, void* d_dst, uint64_t n, uint32_t format, uint64_t seed,
+                    uint32_t step, uint32_t tensor_id, void* stream);
+
+/*
  * Global L2 norm of the gradients of a tensor list (the quantity a gradient
  * clip needs; the paper's training frameworks clip, Algorithm 1 does not
  * mention it): *d_norm_out = (float) sqrt( sum over all tensors and elements

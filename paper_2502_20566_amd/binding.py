@@ -26,7 +26,9 @@ SR_FLAG_DIV_BIAS = 64
 SR_ACC_RNE = 1
 SR_ACC_FIRST = 2
 
-EXPORTS = ("sr_cast_f32_bf16", "grad_global_norm", "sr_adamw_step", "sr_workspace_bytes",
+SR_FP8_E4M3, SR_FP8_E5M2 = 0, 1
+
+EXPORTS = ("sr_cast_f32_bf16", "sr_cast_f32_fp8", "grad_global_norm", "sr_adamw_step", "sr_workspace_bytes",
            "sr_grad_accumulate", "sr_accumulate_workspace_bytes", "sr_stream_probe",
            "sr_strerror", "sr_last_hip_error", "sr_version")
 
@@ -71,6 +73,9 @@ def lib():
         L.sr_cast_f32_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint32,
                                        C.c_uint32, C.c_void_p]
         L.sr_cast_f32_bf16.restype = C.c_int
+        L.sr_cast_f32_fp8.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32,
+                                      C.c_uint32, C.c_void_p]
+        L.sr_cast_f32_fp8.restype = C.c_int
         L.grad_global_norm.argtypes = [C.POINTER(SrTensor), C.c_uint32, C.c_void_p, C.c_void_p,
                                        C.c_uint64, C.c_void_p]
         L.grad_global_norm.restype = C.c_int
@@ -177,6 +182,21 @@ def sr_cast_f32_bf16(src: torch.Tensor, dst: torch.Tensor, seed: int, step: int,
                                 _stream_handle(stream))
     if rc != SR_OK:
         raise SrError(rc, "sr_cast_f32_bf16")
+
+
+def sr_cast_f32_fp8(src: torch.Tensor, dst: torch.Tensor, fmt: int, seed: int, step: int, tensor_id: int = 0,
+                    stream=None) -> None:
+    """dst (uint8 or a torch float8 dtype, one byte per element) <- Q_SR(src) on the grid of
+    SR_FP8_E4M3 or SR_FP8_E5M2."""
+    _check_dev(src, torch.float32, "src")
+    if not dst.is_cuda or not dst.is_contiguous() or dst.element_size() != 1:
+        raise ValueError("dst must be a contiguous one-byte device tensor")
+    if src.numel() != dst.numel():
+        raise ValueError("src and dst differ in size")
+    rc = lib().sr_cast_f32_fp8(src.data_ptr(), dst.data_ptr(), src.numel(), fmt, seed, step, tensor_id,
+                               _stream_handle(stream))
+    if rc != SR_OK:
+        raise SrError(rc, "sr_cast_f32_fp8")
 
 
 def grad_global_norm(tl: TensorList, norm_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:

@@ -8,7 +8,7 @@
 namespace sr {
 
 // RNG output streams (top three bits of counter word 1).
-enum : uint32_t { STREAM_P = 0, STREAM_M = 1, STREAM_V = 2, STREAM_CAST = 3, STREAM_ACC = 4 };
+enum : uint32_t { STREAM_P = 0, STREAM_M = 1, STREAM_V = 2, STREAM_CAST = 3, STREAM_ACC = 4, STREAM_FP8 = 5 };
 
 struct u32x4 { uint32_t w[4]; };
 
@@ -96,5 +96,44 @@ __device__ __forceinline__ uint32_t rne_pair(float y0, float y1)
 {
     return pack_high_halves(rne_one(y0), rne_one(y1));
 }
+
+// Stochastic rounding of a binary32 encoding to an 8-bit floating-point code (Eq.(2) on the grid
+// of an OCP 8-bit format), on the encoding's bits.  MB: mantissa bits of the target (3 for E4M3,
+// 2 for E5M2).  EF: binary32 exponent field of the target's smallest normal (127 - 6 = 121 for
+// E4M3, 127 - 14 = 113 for E5M2).
+// The 24-bit significand is split by one 64-bit shift into the kept integer part i (in units of
+// the grid spacing of the cell: 23 - MB dropped bits, more below the smallest normal) and the
+// dropped fraction k scaled to 32 bits; the magnitude code is (exponent steps above EF) * 2^MB + i,
+// which for normals absorbs the implicit one into the exponent field, plus the carry of k + r32.
+// The carry walks from the top of one binade into the next exactly as in the BF16 form.  binary32
+// zeros and subnormals shift out completely and give code 0.  The result is NOT yet limited to the
+// format's range: see fp8_finish.
+template <int MB, int EF>
+__device__ __forceinline__ uint32_t sr_fp8_magnitude(uint32_t bits, uint32_t r32)
+{
+    const int e = (int)__builtin_amdgcn_ubfe(bits, 23, 8);
+    const uint32_t sig = (bits & 0x007FFFFFu) | 0x00800000u;
+    int sh = (23 - MB) + EF - e;                                // 23 - MB for normals, more below
+    sh = sh < 23 - MB ? 23 - MB : (sh > 63 ? 63 : sh);
+    const uint64_t x = ((uint64_t)sig << 32) >> sh;
+    const uint32_t i = (uint32_t)(x >> 32), k = (uint32_t)x;
+    const uint32_t steps = (uint32_t)(e > EF ? e : EF);         // exponent field, at least EF
+    uint32_t low;
+    const uint32_t carry = __builtin_add_overflow(k, r32, &low) ? 1u : 0u;
+    return (steps << MB) + i + carry - ((uint32_t)EF << MB);
+}
+
+// Range and NaN rules for a magnitude code from sr_fp8_magnitude, and the sign.  TOP: the code
+// every larger result collapses to (E4M3: 0x7E, the largest finite value -- the format has no
+// infinity and saturates; E5M2: 0x7C, infinity).  NaN becomes S.1111111.
+template <uint32_t TOP>
+__device__ __forceinline__ uint32_t fp8_finish(uint32_t bits, uint32_t code)
+{
+    if (code > TOP) code = TOP;
+    if ((bits & 0x7FFFFFFFu) > 0x7F800000u) code = 0x7Fu;
+    return code;
+}
+
+__device__ __forceinline__ uint32_t fp8_sign(uint32_t bits) { return (bits >> 24) & 0x80u; }
 
 }  // namespace sr

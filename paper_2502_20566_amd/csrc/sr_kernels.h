@@ -15,6 +15,14 @@ namespace sr {
 // Update and cast kernels run as single-wave workgroups with one block per lane: measured on
 // MI355X, 64-lane workgroups stream the 4-read/3-write pattern about 10% faster than 256-lane
 // ones (finer interleaving of the seven streams in time), and more blocks per lane are slower.
+// Rows of 4 elements per lane in the cast kernels.  Measured on 6.66e9 elements: BF16 cast 6.06 /
+// 6.10 / 7.04 ms with 1 / 2 / 4 rows; 8-bit cast 6.07 / 5.64 / 5.64 ms.
+#ifndef SR_TUNE_CAST_ITERS
+#define SR_TUNE_CAST_ITERS 1
+#endif
+#ifndef SR_TUNE_FP8_ITERS
+#define SR_TUNE_FP8_ITERS 2
+#endif
 #ifndef SR_TUNE_THREADS
 #define SR_TUNE_THREADS 64
 #endif
@@ -676,43 +684,125 @@ __global__ __launch_bounds__(kThreads) void stream_probe_kernel(uint16_t* __rest
 
 // ----------------------------------------------------------------------- standalone SR cast
 
-// A lane owns half a block (4 elements): one 16-byte load and one 8-byte store per lane, every
-// access of the wave contiguous.  The two lanes of a block draw the same Philox block.
+// A lane owns half a block (4 elements) at a time: one 16-byte load and one 8-byte store per lane,
+// every access of the wave contiguous; the two lanes of a block draw the same Philox block.  A
+// workgroup takes kCastIters such rows (all loads first).
+constexpr int kCastIters = SR_TUNE_CAST_ITERS;
+constexpr int kCastChunkElems = kThreads * 4 * kCastIters;
+
 template <bool NT>
 __global__ __launch_bounds__(kThreads) void cast_kernel(const float* __restrict__ src,
                                                         uint16_t* __restrict__ dst, uint64_t n,
                                                         uint32_t seed_lo, uint32_t seed_hi,
                                                         uint32_t step, uint32_t tensor_id)
 {
-    const uint64_t efirst = (uint64_t)blockIdx.x * (uint64_t)(kThreads * 4);
-    if (efirst + (uint64_t)(kThreads * 4) <= n) {                  // wave-uniform
-        const uint64_t e = efirst + (uint64_t)threadIdx.x * 4;
-        const rsrc_t rs = chunk_rsrc<float>(src, (int64_t)efirst, kThreads * 4u);
-        const rsrc_t rd = chunk_rsrc<uint16_t>(dst, (int64_t)efirst, kThreads * 4u);
-        const v4u x = buf_load16<NT>(rs, threadIdx.x * 16u);
-        const u32x4 r = block_bits(e >> 3, STREAM_CAST, tensor_id, step, seed_lo, seed_hi);
-        const bool upper = ((e >> 2) & 1u) != 0;
-        const uint32_t w0 = upper ? r.w[2] : r.w[0], w1 = upper ? r.w[3] : r.w[1];
-        const float y0 = __uint_as_float(x.x), y1 = __uint_as_float(x.y);
-        const float y2 = __uint_as_float(x.z), y3 = __uint_as_float(x.w);
-        const bool nan = __builtin_amdgcn_ballot_w64((y0 != y0) | (y1 != y1) | (y2 != y2) | (y3 != y3)) != 0;
-        v2u o;
-        if (nan) { o.x = sr_pair_nan_safe(y0, y1, w0); o.y = sr_pair_nan_safe(y2, y3, w1); }
-        else     { o.x = sr_pair(y0, y1, w0);          o.y = sr_pair(y2, y3, w1); }
-        buf_store8<NT>(rd, threadIdx.x * 8u, o);
+    const uint64_t cfirst = (uint64_t)blockIdx.x * (uint64_t)kCastChunkElems;
+    if (cfirst + (uint64_t)kCastChunkElems <= n) {                 // wave-uniform
+        const rsrc_t rs = chunk_rsrc<float>(src, (int64_t)cfirst, kCastChunkElems);
+        const rsrc_t rd = chunk_rsrc<uint16_t>(dst, (int64_t)cfirst, kCastChunkElems);
+        v4u xs[kCastIters];
+#pragma unroll
+        for (int it = 0; it < kCastIters; ++it) xs[it] = buf_load16<NT>(rs, (uint32_t)(it * kThreads + threadIdx.x) * 16u);
+#pragma unroll
+        for (int it = 0; it < kCastIters; ++it) {
+            const uint32_t row = (uint32_t)(it * kThreads + threadIdx.x);
+            const uint64_t e = cfirst + (uint64_t)row * 4;
+            const v4u x = xs[it];
+            const u32x4 r = block_bits(e >> 3, STREAM_CAST, tensor_id, step, seed_lo, seed_hi);
+            const bool upper = ((e >> 2) & 1u) != 0;
+            const uint32_t w0 = upper ? r.w[2] : r.w[0], w1 = upper ? r.w[3] : r.w[1];
+            const float y0 = __uint_as_float(x.x), y1 = __uint_as_float(x.y);
+            const float y2 = __uint_as_float(x.z), y3 = __uint_as_float(x.w);
+            const bool nan = __builtin_amdgcn_ballot_w64((y0 != y0) | (y1 != y1) | (y2 != y2) | (y3 != y3)) != 0;
+            v2u o;
+            if (nan) { o.x = sr_pair_nan_safe(y0, y1, w0); o.y = sr_pair_nan_safe(y2, y3, w1); }
+            else     { o.x = sr_pair(y0, y1, w0);          o.y = sr_pair(y2, y3, w1); }
+            buf_store8<NT>(rd, row * 8u, o);
+        }
         return;
     }
-    // Tail chunk: its kThreads/2 blocks, one per lane, the last one element-wise.
+    // Tail chunk: its blocks, one per lane and pass, the last one element-wise.
     const uint64_t nblk = (n + 7) >> 3;
-    const uint64_t b = (uint64_t)blockIdx.x * (uint64_t)(kThreads / 2) + threadIdx.x;
-    if (threadIdx.x >= kThreads / 2 || b >= nblk) return;
-    const int64_t l0 = (int64_t)(b << 3);
-    const bool full = block_inside(l0, n);
-    float y[8];
-    load8_f32<NT>(src, l0, n, full, y);
-    const u32x4 r = block_bits(b, STREAM_CAST, tensor_id, step, seed_lo, seed_hi);
-    const v4u o = any_nan8(y) ? sr8<true>(y, r) : sr8<false>(y, r);
-    store8_bf16<NT>(dst, l0, n, full, o);
+    const uint64_t bfirst = cfirst >> 3;
+    for (uint64_t b = bfirst + threadIdx.x; b < nblk; b += kThreads) {
+        const int64_t l0 = (int64_t)(b << 3);
+        const bool full = block_inside(l0, n);
+        float y[8];
+        load8_f32<NT>(src, l0, n, full, y);
+        const u32x4 r = block_bits(b, STREAM_CAST, tensor_id, step, seed_lo, seed_hi);
+        const v4u o = any_nan8(y) ? sr8<true>(y, r) : sr8<false>(y, r);
+        store8_bf16<NT>(dst, l0, n, full, o);
+    }
+}
+
+// --------------------------------------------------- standalone SR cast to 8-bit formats
+
+// A lane owns four elements: one 16-byte load, one Philox block (a 32-bit word per element), one
+// 4-byte store; every access of the wave is contiguous.  FMT 0: E4M3, 1: E5M2.  The range and NaN
+// rules only matter from the binade that holds the format's largest finite value upwards: they are
+// applied in a branch taken when some lane of the wave holds such a value.
+template <int FMT> struct Fp8 {
+    static constexpr int mb = FMT == 0 ? 3 : 2;
+    static constexpr int ef = FMT == 0 ? 121 : 113;              // exponent field of the smallest normal
+    static constexpr uint32_t top = FMT == 0 ? 0x7Eu : 0x7Cu;
+    static constexpr uint32_t efmax = FMT == 0 ? 127u + 8u : 127u + 15u;   // binade of the largest finite value
+};
+
+template <int FMT>
+__device__ __forceinline__ uint32_t fp8_code(uint32_t bits, uint32_t r32)
+{
+    using P = Fp8<FMT>;
+    return fp8_sign(bits) | fp8_finish<P::top>(bits, sr_fp8_magnitude<P::mb, P::ef>(bits, r32));
+}
+
+constexpr int kFp8Iters = SR_TUNE_FP8_ITERS;     // groups of 4 elements per lane
+constexpr int kFp8ChunkElems = kThreads * 4 * kFp8Iters;
+
+template <int FMT, bool NT>
+__global__ __launch_bounds__(kThreads) void cast_fp8_kernel(const float* __restrict__ src,
+                                                            uint8_t* __restrict__ dst, uint64_t n,
+                                                            uint32_t seed_lo, uint32_t seed_hi,
+                                                            uint32_t step, uint32_t tensor_id)
+{
+    using P = Fp8<FMT>;
+    const uint64_t cfirst = (uint64_t)blockIdx.x * (uint64_t)kFp8ChunkElems;
+    const bool whole = cfirst + (uint64_t)kFp8ChunkElems <= n;       // wave-uniform
+    const rsrc_t rs = chunk_rsrc<float>(src, (int64_t)cfirst, kFp8ChunkElems);
+    const rsrc_t rd = chunk_rsrc<uint8_t>(dst, (int64_t)cfirst, kFp8ChunkElems);
+    v4u xs[kFp8Iters];
+    if (whole) {
+#pragma unroll
+        for (int it = 0; it < kFp8Iters; ++it) xs[it] = buf_load16<NT>(rs, (uint32_t)(it * kThreads + threadIdx.x) * 16u);
+    }
+#pragma unroll
+    for (int it = 0; it < kFp8Iters; ++it) {
+        const uint64_t e = cfirst + (uint64_t)(it * kThreads + threadIdx.x) * 4;
+        if (e >= n) return;
+        const u32x4 r = philox4x32_10((uint32_t)(e >> 2), (STREAM_FP8 << 29) | (uint32_t)(e >> 34), tensor_id, step,
+                                      seed_lo, seed_hi);
+        if (whole) {
+            const v4u x = xs[it];
+            const uint32_t b[4] = {x.x, x.y, x.z, x.w};
+            uint32_t c[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) c[j] = sr_fp8_magnitude<P::mb, P::ef>(b[j], r.w[j]);
+            const uint32_t big = (x.x | x.y | x.z | x.w) & 0x7FFFFFFFu;  // >= the largest magnitude's binade
+            if (__builtin_amdgcn_ballot_w64(big >= (P::efmax << 23)) != 0) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) c[j] = fp8_finish<P::top>(b[j], c[j]);
+            }
+            const uint32_t signs = ((x.x >> 24) & 0x80u) | ((x.y >> 16) & 0x8000u) | ((x.z >> 8) & 0x800000u) |
+                                   (x.w & 0x80000000u);
+            const uint32_t o = (c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24)) | signs;
+            __builtin_amdgcn_raw_buffer_store_b32(o, rd, (int)((uint32_t)(it * kThreads + threadIdx.x) * 4u), 0, NT ? 2 : 0);
+        } else {
+            // tail chunk: element-wise with bounds
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (e + j < n) dst[e + j] = (uint8_t)fp8_code<FMT>(__float_as_uint(src[e + j]), r.w[j]);
+            }
+        }
+    }
 }
 
 // ------------------------------------------------------------------------- gradient norm

@@ -121,13 +121,34 @@ int sr_cast_f32_bf16(const float* d_src, void* d_dst, uint64_t n, uint64_t seed,
     if (n == 0) return SR_OK;
     if (!d_src || !d_dst) return SR_ERR_NULL;
     if (!aligned(d_src, 4) || !aligned(d_dst, 2)) return SR_ERR_ALIGN;
-    const uint64_t nblk = (n + 7) >> 3;
-    const uint64_t per_wg = (uint64_t)kThreads / 2;                 // blocks per workgroup
-    const uint64_t grid = (nblk + per_wg - 1) / per_wg;
+    const uint64_t grid = (n + (uint64_t)kCastChunkElems - 1) / (uint64_t)kCastChunkElems;
     if (grid > kMaxGrid) return SR_ERR_ARG;
     hipLaunchKernelGGL((cast_kernel<kNT>), dim3((uint32_t)grid), dim3(kThreads), 0,
                        static_cast<hipStream_t>(stream), d_src, static_cast<uint16_t*>(d_dst), n,
                        (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), step, tensor_id);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SR_OK : hip_fail(e);
+}
+
+int sr_cast_f32_fp8(const float* d_src, void* d_dst, uint64_t n, uint32_t format, uint64_t seed,
+                    uint32_t step, uint32_t tensor_id, void* stream)
+{
+    if (format != SR_FP8_E4M3 && format != SR_FP8_E5M2) return SR_ERR_ARG;
+    if (n == 0) return SR_OK;
+    if (!d_src || !d_dst) return SR_ERR_NULL;
+    if (!aligned(d_src, 4)) return SR_ERR_ALIGN;
+    if (n > (1ull << 61)) return SR_ERR_ARG;                        // block index must fit 29 + 32 bits
+    const uint64_t per_wg = (uint64_t)kFp8ChunkElems;
+    const uint64_t grid = (n + per_wg - 1) / per_wg;
+    if (grid > kMaxGrid) return SR_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint32_t lo = (uint32_t)(seed & 0xFFFFFFFFu), hi = (uint32_t)(seed >> 32);
+    if (format == SR_FP8_E4M3)
+        hipLaunchKernelGGL((cast_fp8_kernel<0, kNT>), dim3((uint32_t)grid), dim3(kThreads), 0, s, d_src,
+                           static_cast<uint8_t*>(d_dst), n, lo, hi, step, tensor_id);
+    else
+        hipLaunchKernelGGL((cast_fp8_kernel<1, kNT>), dim3((uint32_t)grid), dim3(kThreads), 0, s, d_src,
+                           static_cast<uint8_t*>(d_dst), n, lo, hi, step, tensor_id);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? SR_OK : hip_fail(e);
 }

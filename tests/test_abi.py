@@ -122,6 +122,16 @@ def test_cast_argument_errors():
     assert L.sr_cast_f32_bf16(buf(32), buf(16, 1), 4, 0, 1, 0, None) == B.SR_ERR_ALIGN
 
 
+def test_fp8_cast_argument_errors():
+    L = B.lib()
+    assert L.sr_cast_f32_fp8(None, None, 0, B.SR_FP8_E4M3, 0, 1, 0, None) == B.SR_OK
+    assert L.sr_cast_f32_fp8(buf(32), buf(8), 8, 2, 0, 1, 0, None) == B.SR_ERR_ARG          # unknown format
+    assert L.sr_cast_f32_fp8(None, buf(8), 8, B.SR_FP8_E5M2, 0, 1, 0, None) == B.SR_ERR_NULL
+    assert L.sr_cast_f32_fp8(buf(32), None, 8, B.SR_FP8_E5M2, 0, 1, 0, None) == B.SR_ERR_NULL
+    assert L.sr_cast_f32_fp8(buf(32, 2), buf(8), 4, B.SR_FP8_E4M3, 0, 1, 0, None) == B.SR_ERR_ALIGN
+    assert L.sr_cast_f32_fp8(buf(32), buf(8), (1 << 61) + 1, B.SR_FP8_E4M3, 0, 1, 0, None) == B.SR_ERR_ARG
+
+
 def test_norm_argument_errors():
     L = B.lib()
     t = tensor(numel=100000)
