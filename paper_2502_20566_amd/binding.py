@@ -101,7 +101,7 @@ def lib():
     return _lib
 
 
-def _stream_handle(stream) -> Optional[int]:
+def _stream_handle(stream) -> C.c_void_p:
     if stream is None:
         stream = torch.cuda.current_stream()
     return C.c_void_p(stream.cuda_stream)
@@ -110,6 +110,9 @@ def _stream_handle(stream) -> Optional[int]:
 def _check_dev(t: torch.Tensor, dtype, name: str):
     if not t.is_cuda:
         raise ValueError(f"{name} must be a device tensor")
+    if t.device.index != torch.cuda.current_device():
+        # kernels are launched on the current device's stream with plain pointers
+        raise ValueError(f"{name} lives on {t.device}, the current device is cuda:{torch.cuda.current_device()}")
     if t.dtype != dtype:
         raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
     if not t.is_contiguous():
