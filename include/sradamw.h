@@ -19,6 +19,10 @@
  *     of the tensors.
  *   - Return value: SR_OK (0) or a negative SR_ERR_* code.  Arguments are
  *     validated on the host first; on an argument error nothing is enqueued.
+ *   - Sizes: any tensor that fits in device memory is accepted.  A launch
+ *     holds at most 2^32 - 1 work-items; larger jobs (more than about 3.4e10
+ *     elements of a BF16-moment list, 1.7e10 of an FP32-moment list or of a
+ *     cast) are enqueued as several launches, with identical results.
  *   - Outputs depend only on the input bits, the hyper-parameters, `step`,
  *     `seed`, `tensor_id` and the element's index elem_offset + i -- never on
  *     launch geometry, list order, how a list is split over calls, pointer
@@ -238,6 +242,14 @@ const char* sr_strerror(int code);
 
 /* hipError_t value of the most recent SR_ERR_HIP on the calling thread (0 if none). */
 int sr_last_hip_error(void);
+
+/*
+ * For tests of the multi-launch paths: limit every later launch of this process
+ * to max_workgroups workgroups (0 restores the hardware limit), so that small
+ * inputs are cut into several launches.  Results must not change.  Not
+ * synchronised with calls running on other threads.
+ */
+void sr_debug_set_launch_limit(uint32_t max_workgroups);
 
 /* Library version, major*10000 + minor*100 + patch. */
 int sr_version(void);

@@ -30,7 +30,7 @@ SR_FP8_E4M3, SR_FP8_E5M2 = 0, 1
 
 EXPORTS = ("sr_cast_f32_bf16", "sr_cast_f32_fp8", "grad_global_norm", "sr_adamw_step", "sr_workspace_bytes",
            "sr_grad_accumulate", "sr_accumulate_workspace_bytes", "sr_stream_probe",
-           "sr_strerror", "sr_last_hip_error", "sr_version")
+           "sr_strerror", "sr_last_hip_error", "sr_version", "sr_debug_set_launch_limit")
 
 
 class SrTensor(C.Structure):
@@ -95,6 +95,8 @@ def lib():
         L.sr_strerror.restype = C.c_char_p
         L.sr_last_hip_error.argtypes = []
         L.sr_last_hip_error.restype = C.c_int
+        L.sr_debug_set_launch_limit.argtypes = [C.c_uint32]
+        L.sr_debug_set_launch_limit.restype = None
         L.sr_version.argtypes = []
         L.sr_version.restype = C.c_int
         _lib = L

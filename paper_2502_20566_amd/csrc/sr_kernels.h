@@ -666,9 +666,9 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
 // one wave per workgroup, one block per lane, streaming buffer accesses.
 __global__ __launch_bounds__(kThreads) void stream_probe_kernel(uint16_t* __restrict__ p, const uint16_t* __restrict__ g,
                                                                uint16_t* __restrict__ m, uint16_t* __restrict__ v,
-                                                               uint64_t nblk, uint32_t mask)
+                                                               uint64_t nblk, uint64_t wg0, uint32_t mask)
 {
-    const uint64_t b0 = (uint64_t)blockIdx.x * kThreads, b = b0 + threadIdx.x;
+    const uint64_t b0 = ((uint64_t)blockIdx.x + wg0) * kThreads, b = b0 + threadIdx.x;
     if (b >= nblk) return;
     const int64_t e0 = (int64_t)(b0 << 3);
     const rsrc_t rp = chunk_rsrc<uint16_t>(p, e0, kThreads * 8u), rg = chunk_rsrc<uint16_t>(g, e0, kThreads * 8u);
@@ -693,10 +693,10 @@ constexpr int kCastChunkElems = kThreads * 4 * kCastIters;
 template <bool NT>
 __global__ __launch_bounds__(kThreads) void cast_kernel(const float* __restrict__ src,
                                                         uint16_t* __restrict__ dst, uint64_t n,
-                                                        uint32_t seed_lo, uint32_t seed_hi,
+                                                        uint64_t chunk0, uint32_t seed_lo, uint32_t seed_hi,
                                                         uint32_t step, uint32_t tensor_id)
 {
-    const uint64_t cfirst = (uint64_t)blockIdx.x * (uint64_t)kCastChunkElems;
+    const uint64_t cfirst = ((uint64_t)blockIdx.x + chunk0) * (uint64_t)kCastChunkElems;
     if (cfirst + (uint64_t)kCastChunkElems <= n) {                 // wave-uniform
         const rsrc_t rs = chunk_rsrc<float>(src, (int64_t)cfirst, kCastChunkElems);
         const rsrc_t rd = chunk_rsrc<uint16_t>(dst, (int64_t)cfirst, kCastChunkElems);
@@ -761,11 +761,11 @@ constexpr int kFp8ChunkElems = kThreads * 4 * kFp8Iters;
 template <int FMT, bool NT>
 __global__ __launch_bounds__(kThreads) void cast_fp8_kernel(const float* __restrict__ src,
                                                             uint8_t* __restrict__ dst, uint64_t n,
-                                                            uint32_t seed_lo, uint32_t seed_hi,
+                                                            uint64_t chunk0, uint32_t seed_lo, uint32_t seed_hi,
                                                             uint32_t step, uint32_t tensor_id)
 {
     using P = Fp8<FMT>;
-    const uint64_t cfirst = (uint64_t)blockIdx.x * (uint64_t)kFp8ChunkElems;
+    const uint64_t cfirst = ((uint64_t)blockIdx.x + chunk0) * (uint64_t)kFp8ChunkElems;
     const bool whole = cfirst + (uint64_t)kFp8ChunkElems <= n;       // wave-uniform
     const rsrc_t rs = chunk_rsrc<float>(src, (int64_t)cfirst, kFp8ChunkElems);
     const rsrc_t rd = chunk_rsrc<uint8_t>(dst, (int64_t)cfirst, kFp8ChunkElems);

@@ -5,6 +5,7 @@
 #include "../../include/sradamw.h"
 #include "sr_kernels.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 
@@ -39,7 +40,42 @@ constexpr bool kNT = true;
 // owns half a block.
 constexpr uint64_t kBlocksPerChunkBf16 = (uint64_t)kThreads;
 constexpr uint64_t kBlocksPerChunkFp32 = (uint64_t)kThreads / 2;
-constexpr uint32_t kMaxGrid = 0x7FFFFFFFu;
+// A dispatch packet counts its grid in work-items with 32 bits, so a launch of T-lane workgroups
+// holds at most (2^32 - 1) / T of them.  Larger jobs are cut into several launches (tensors into
+// pieces at counter-block boundaries: a piece is itself a slice with its own elem_offset, so the
+// result does not depend on the cut).  Tests lower the limit to reach those paths with small inputs.
+std::atomic<uint32_t> g_launch_limit{0};
+inline uint32_t max_grid(uint32_t threads)
+{
+    const uint32_t hw = 0xFFFFFFFFu / threads;
+    const uint32_t lim = g_launch_limit.load(std::memory_order_relaxed);
+    return lim && lim < hw ? lim : hw;
+}
+
+// True when the counter indices elem_offset .. elem_offset + numel (rounded up to a block) leave 64 bits.
+inline bool range_wraps(uint64_t elem_offset, uint64_t numel)
+{
+    return numel > UINT64_MAX - 8 || elem_offset > UINT64_MAX - 8 - numel;
+}
+
+// Calls f(local, numel, elem_offset) for consecutive pieces of a tensor slice of `numel` elements
+// whose element 0 has counter index `elem_offset`; every piece spans at most blocks_per_piece
+// counter blocks and all but the first start on a block boundary.  local = index of the piece's
+// first element in the slice.  Stops at the first failure.
+template <class F>
+hipError_t split_tensor(uint64_t numel, uint64_t elem_offset, uint64_t blocks_per_piece, F f)
+{
+    const uint64_t G0 = elem_offset, gblk0 = G0 >> 3;
+    const uint64_t nblk = ((G0 + numel - 1) >> 3) - gblk0 + 1;
+    for (uint64_t b = 0; b < nblk; b += blocks_per_piece) {
+        const uint64_t bend = nblk - b < blocks_per_piece ? nblk : b + blocks_per_piece;
+        const uint64_t gfirst = b == 0 ? G0 : (gblk0 + b) << 3;
+        const uint64_t gend = bend == nblk ? G0 + numel : (gblk0 + bend) << 3;
+        const hipError_t e = f(gfirst - G0, gend - gfirst, gfirst);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
 
 template <uint32_t F, bool VAR>
 hipError_t launch_adamw_v(bool clip, const AdamwBatch& batch, uint32_t n_chunks, hipStream_t stream)
@@ -81,19 +117,28 @@ int sr_version(void) { return 100; }
 
 int sr_last_hip_error(void) { return g_last_hip_error; }
 
+void sr_debug_set_launch_limit(uint32_t max_workgroups)
+{
+    g_launch_limit.store(max_workgroups, std::memory_order_relaxed);
+}
+
 int sr_stream_probe(void* d_p, const void* d_g, void* d_m, void* d_v, uint64_t numel, void* stream)
 {
     const uint64_t nblk = numel >> 3;                 // whole blocks only; a tail is left untouched
     if (nblk == 0) return SR_OK;
     if (!d_p || !d_g || !d_m || !d_v) return SR_ERR_NULL;
     if (!aligned(d_p, 2) || !aligned(d_g, 2) || !aligned(d_m, 2) || !aligned(d_v, 2)) return SR_ERR_ALIGN;
-    const uint64_t grid = (nblk + kThreads - 1) / kThreads;
-    if (grid > kMaxGrid) return SR_ERR_ARG;
-    hipLaunchKernelGGL(stream_probe_kernel, dim3((uint32_t)grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
-                       static_cast<uint16_t*>(d_p), static_cast<const uint16_t*>(d_g), static_cast<uint16_t*>(d_m),
-                       static_cast<uint16_t*>(d_v), nblk, 0u);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? SR_OK : hip_fail(e);
+    const uint64_t wgs = (nblk + kThreads - 1) / kThreads;
+    const uint32_t mg = max_grid(kThreads);
+    for (uint64_t w0 = 0; w0 < wgs; w0 += mg) {
+        const uint32_t grid = (uint32_t)(wgs - w0 < mg ? wgs - w0 : mg);
+        hipLaunchKernelGGL(stream_probe_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                           static_cast<uint16_t*>(d_p), static_cast<const uint16_t*>(d_g), static_cast<uint16_t*>(d_m),
+                           static_cast<uint16_t*>(d_v), nblk, w0, 0u);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return SR_OK;
 }
 
 const char* sr_strerror(int code)
@@ -121,13 +166,17 @@ int sr_cast_f32_bf16(const float* d_src, void* d_dst, uint64_t n, uint64_t seed,
     if (n == 0) return SR_OK;
     if (!d_src || !d_dst) return SR_ERR_NULL;
     if (!aligned(d_src, 4) || !aligned(d_dst, 2)) return SR_ERR_ALIGN;
-    const uint64_t grid = (n + (uint64_t)kCastChunkElems - 1) / (uint64_t)kCastChunkElems;
-    if (grid > kMaxGrid) return SR_ERR_ARG;
-    hipLaunchKernelGGL((cast_kernel<kNT>), dim3((uint32_t)grid), dim3(kThreads), 0,
-                       static_cast<hipStream_t>(stream), d_src, static_cast<uint16_t*>(d_dst), n,
-                       (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), step, tensor_id);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? SR_OK : hip_fail(e);
+    const uint64_t chunks = (n + (uint64_t)kCastChunkElems - 1) / (uint64_t)kCastChunkElems;
+    const uint32_t mg = max_grid(kThreads);
+    for (uint64_t c0 = 0; c0 < chunks; c0 += mg) {
+        const uint32_t grid = (uint32_t)(chunks - c0 < mg ? chunks - c0 : mg);
+        hipLaunchKernelGGL((cast_kernel<kNT>), dim3(grid), dim3(kThreads), 0,
+                           static_cast<hipStream_t>(stream), d_src, static_cast<uint16_t*>(d_dst), n, c0,
+                           (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), step, tensor_id);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return SR_OK;
 }
 
 int sr_cast_f32_fp8(const float* d_src, void* d_dst, uint64_t n, uint32_t format, uint64_t seed,
@@ -138,19 +187,22 @@ int sr_cast_f32_fp8(const float* d_src, void* d_dst, uint64_t n, uint32_t format
     if (!d_src || !d_dst) return SR_ERR_NULL;
     if (!aligned(d_src, 4)) return SR_ERR_ALIGN;
     if (n > (1ull << 61)) return SR_ERR_ARG;                        // block index must fit 29 + 32 bits
-    const uint64_t per_wg = (uint64_t)kFp8ChunkElems;
-    const uint64_t grid = (n + per_wg - 1) / per_wg;
-    if (grid > kMaxGrid) return SR_ERR_ARG;
+    const uint64_t chunks = (n + (uint64_t)kFp8ChunkElems - 1) / (uint64_t)kFp8ChunkElems;
+    const uint32_t mg = max_grid(kThreads);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t lo = (uint32_t)(seed & 0xFFFFFFFFu), hi = (uint32_t)(seed >> 32);
-    if (format == SR_FP8_E4M3)
-        hipLaunchKernelGGL((cast_fp8_kernel<0, kNT>), dim3((uint32_t)grid), dim3(kThreads), 0, s, d_src,
-                           static_cast<uint8_t*>(d_dst), n, lo, hi, step, tensor_id);
-    else
-        hipLaunchKernelGGL((cast_fp8_kernel<1, kNT>), dim3((uint32_t)grid), dim3(kThreads), 0, s, d_src,
-                           static_cast<uint8_t*>(d_dst), n, lo, hi, step, tensor_id);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? SR_OK : hip_fail(e);
+    for (uint64_t c0 = 0; c0 < chunks; c0 += mg) {
+        const uint32_t grid = (uint32_t)(chunks - c0 < mg ? chunks - c0 : mg);
+        if (format == SR_FP8_E4M3)
+            hipLaunchKernelGGL((cast_fp8_kernel<0, kNT>), dim3(grid), dim3(kThreads), 0, s, d_src,
+                               static_cast<uint8_t*>(d_dst), n, c0, lo, hi, step, tensor_id);
+        else
+            hipLaunchKernelGGL((cast_fp8_kernel<1, kNT>), dim3(grid), dim3(kThreads), 0, s, d_src,
+                               static_cast<uint8_t*>(d_dst), n, c0, lo, hi, step, tensor_id);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return SR_OK;
 }
 
 int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_norm_out,
@@ -164,7 +216,6 @@ int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_no
         if (tensors[i].numel == 0) continue;
         if (!tensors[i].g) return SR_ERR_NULL;
         if (!aligned(tensors[i].g, 2)) return SR_ERR_ALIGN;
-        if (tensors[i].numel > (uint64_t)kMaxGrid * kNormChunkElems) return SR_ERR_ARG;
         total_chunks += (tensors[i].numel + kNormChunkElems - 1) / kNormChunkElems;
     }
     if (total_chunks > 0xFFFFFFFFull) return SR_ERR_ARG;
@@ -188,19 +239,22 @@ int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_no
         nb = 0; chunks_in_batch = 0;
         return hipGetLastError();
     };
+    const uint32_t mg = max_grid(kNormThreads);
+    const uint64_t piece_elems = (uint64_t)mg * kNormChunkElems;      // whole chunks: same partial sums however cut
     for (uint32_t i = 0; i < n_tensors; ++i) {
-        const uint64_t numel = tensors[i].numel;
-        if (numel == 0) continue;
-        const uint32_t nch = (uint32_t)((numel + kNormChunkElems - 1) / kNormChunkElems);
-        if (nb == kNormMaxBatch || (uint64_t)chunks_in_batch + nch > kMaxGrid) {
-            const hipError_t e = flush();
-            if (e != hipSuccess) return hip_fail(e);
+        for (uint64_t off = 0; off < tensors[i].numel; off += piece_elems) {
+            const uint64_t numel = tensors[i].numel - off < piece_elems ? tensors[i].numel - off : piece_elems;
+            const uint32_t nch = (uint32_t)((numel + kNormChunkElems - 1) / kNormChunkElems);
+            if (nb == kNormMaxBatch || (uint64_t)chunks_in_batch + nch > mg) {
+                const hipError_t e = flush();
+                if (e != hipSuccess) return hip_fail(e);
+            }
+            batch.t[nb].g = static_cast<const uint16_t*>(tensors[i].g) + off;
+            batch.t[nb].numel = numel;
+            batch.chunk_start[nb] = chunks_in_batch;
+            chunks_in_batch += nch;
+            ++nb;
         }
-        batch.t[nb].g = static_cast<const uint16_t*>(tensors[i].g);
-        batch.t[nb].numel = numel;
-        batch.chunk_start[nb] = chunks_in_batch;
-        chunks_in_batch += nch;
-        ++nb;
     }
     hipError_t e = flush();
     if (e != hipSuccess) return hip_fail(e);
@@ -234,11 +288,9 @@ int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scal
         if (t.numel == 0) continue;
         if (!t.acc || !t.grad) return SR_ERR_NULL;
         if (!aligned(t.acc, 2) || !aligned(t.grad, 2)) return SR_ERR_ALIGN;
-        if (t.elem_offset + t.numel < t.numel) return SR_ERR_ARG;
+        if (range_wraps(t.elem_offset, t.numel)) return SR_ERR_ARG;
         const uint64_t nblk = ((t.elem_offset + t.numel - 1) >> 3) - (t.elem_offset >> 3) + 1;
-        const uint64_t nch = (nblk + blocks_per_chunk - 1) / blocks_per_chunk;
-        if (nch > kMaxGrid) return SR_ERR_ARG;
-        total_chunks += nch;
+        total_chunks += (nblk + blocks_per_chunk - 1) / blocks_per_chunk;
     }
     if (total_chunks > 0xFFFFFFFFull) return SR_ERR_ARG;
     if (d_norm_out && total_chunks) {
@@ -269,25 +321,31 @@ int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scal
         nb = 0; chunks_in_batch = 0;
         return hipGetLastError();
     };
+    const uint32_t mg = max_grid(kAccThreads);
     for (uint32_t i = 0; i < n_tensors; ++i) {
         const sr_accum_t& t = tensors[i];
         if (t.numel == 0) continue;
-        const uint64_t nblk = ((t.elem_offset + t.numel - 1) >> 3) - (t.elem_offset >> 3) + 1;
-        const uint32_t nch = (uint32_t)((nblk + blocks_per_chunk - 1) / blocks_per_chunk);
-        if (nb == kAccMaxBatch || (uint64_t)chunks_in_batch + nch > kMaxGrid) {
-            const hipError_t e = flush();
-            if (e != hipSuccess) return hip_fail(e);
-        }
-        AccDesc& d = batch.t[nb];
-        d.acc = static_cast<uint16_t*>(t.acc);
-        d.g = static_cast<const uint16_t*>(t.grad);
-        d.numel = t.numel;
-        d.elem_offset = t.elem_offset;
-        d.tensor_id = t.tensor_id;
-        d.pad_ = 0;
-        batch.chunk_start[nb] = chunks_in_batch;
-        chunks_in_batch += nch;
-        ++nb;
+        const hipError_t pe = split_tensor(t.numel, t.elem_offset, (uint64_t)mg * blocks_per_chunk,
+                                           [&](uint64_t local, uint64_t numel, uint64_t goff) -> hipError_t {
+            const uint64_t nblk = ((goff + numel - 1) >> 3) - (goff >> 3) + 1;
+            const uint32_t nch = (uint32_t)((nblk + blocks_per_chunk - 1) / blocks_per_chunk);
+            if (nb == kAccMaxBatch || (uint64_t)chunks_in_batch + nch > mg) {
+                const hipError_t e = flush();
+                if (e != hipSuccess) return e;
+            }
+            AccDesc& d = batch.t[nb];
+            d.acc = static_cast<uint16_t*>(t.acc) + local;
+            d.g = static_cast<const uint16_t*>(t.grad) + local;
+            d.numel = numel;
+            d.elem_offset = goff;
+            d.tensor_id = t.tensor_id;
+            d.pad_ = 0;
+            batch.chunk_start[nb] = chunks_in_batch;
+            chunks_in_batch += nch;
+            ++nb;
+            return hipSuccess;
+        });
+        if (pe != hipSuccess) return hip_fail(pe);
     }
     hipError_t e = flush();
     if (e != hipSuccess) return hip_fail(e);
@@ -354,9 +412,7 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
         if (!aligned(t.p, 2) || !aligned(t.g, 2) || !aligned(t.m, moment_align) || !aligned(t.v, moment_align))
             return SR_ERR_ALIGN;
         if ((master && !aligned(t.aux, 4)) || (kahan && !aligned(t.aux, 2))) return SR_ERR_ALIGN;
-        if (t.elem_offset + t.numel < t.numel) return SR_ERR_ARG;          // index range wraps
-        const uint64_t nblk = ((t.elem_offset + t.numel - 1) >> 3) - (t.elem_offset >> 3) + 1;
-        if ((nblk + kBlocksPerChunkFp32 - 1) / kBlocksPerChunkFp32 > kMaxGrid) return SR_ERR_ARG;
+        if (range_wraps(t.elem_offset, t.numel)) return SR_ERR_ARG;
     }
 
     AdamwBatch batch;
@@ -390,29 +446,36 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
         nb = 0; chunks_in_batch = 0;
         return e;
     };
+    const uint32_t mg = max_grid(kThreads);
+    const uint64_t per_chunk = fp32m ? kBlocksPerChunkFp32 : kBlocksPerChunkBf16;
+    const uint64_t moment_size = fp32m ? 4 : 2, aux_size = master ? 4 : 2;
     for (uint32_t i = 0; i < n_tensors; ++i) {
         const sr_tensor_t& t = tensors[i];
         if (t.numel == 0) continue;
-        const uint64_t nblk = ((t.elem_offset + t.numel - 1) >> 3) - (t.elem_offset >> 3) + 1;
-        const uint64_t per_chunk = fp32m ? kBlocksPerChunkFp32 : kBlocksPerChunkBf16;
-        const uint32_t nch = (uint32_t)((nblk + per_chunk - 1) / per_chunk);
-        if (nb == kMaxBatch || (uint64_t)chunks_in_batch + nch > kMaxGrid) {
-            const hipError_t e = flush();
-            if (e != hipSuccess) return hip_fail(e);
-        }
-        TensorDesc& d = batch.t[nb];
-        d.p = static_cast<uint16_t*>(t.p);
-        d.g = static_cast<const uint16_t*>(t.g);
-        d.m = t.m;
-        d.v = t.v;
-        d.aux = (master || kahan) ? t.aux : nullptr;
-        d.numel = t.numel;
-        d.elem_offset = t.elem_offset;
-        d.tensor_id = t.tensor_id;
-        d.flags = (t.elem_offset & 7u) == 0 ? DESC_VEC : 0u;
-        batch.chunk_start[nb] = chunks_in_batch;
-        chunks_in_batch += nch;
-        ++nb;
+        const hipError_t pe = split_tensor(t.numel, t.elem_offset, (uint64_t)mg * per_chunk,
+                                           [&](uint64_t local, uint64_t numel, uint64_t goff) -> hipError_t {
+            const uint64_t nblk = ((goff + numel - 1) >> 3) - (goff >> 3) + 1;
+            const uint32_t nch = (uint32_t)((nblk + per_chunk - 1) / per_chunk);
+            if (nb == kMaxBatch || (uint64_t)chunks_in_batch + nch > mg) {
+                const hipError_t e = flush();
+                if (e != hipSuccess) return e;
+            }
+            TensorDesc& d = batch.t[nb];
+            d.p = static_cast<uint16_t*>(t.p) + local;
+            d.g = static_cast<const uint16_t*>(t.g) + local;
+            d.m = static_cast<char*>(t.m) + local * moment_size;
+            d.v = static_cast<char*>(t.v) + local * moment_size;
+            d.aux = (master || kahan) ? static_cast<char*>(t.aux) + local * aux_size : nullptr;
+            d.numel = numel;
+            d.elem_offset = goff;
+            d.tensor_id = t.tensor_id;
+            d.flags = (goff & 7u) == 0 ? DESC_VEC : 0u;
+            batch.chunk_start[nb] = chunks_in_batch;
+            chunks_in_batch += nch;
+            ++nb;
+            return hipSuccess;
+        });
+        if (pe != hipSuccess) return hip_fail(pe);
     }
     const hipError_t e = flush();
     return e == hipSuccess ? SR_OK : hip_fail(e);
