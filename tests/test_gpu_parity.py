@@ -777,6 +777,51 @@ def test_optimizer_object_drives_the_same_steps():
         for a, b in zip(params, ref_p):
             assert torch.equal(a.detach().view(-1).view(torch.int16), b.view(torch.int16))
         if t == 3:                                            # resume into a fresh object
-            sd = {k: ([x_.clone() for x_ in v_] if isinstance(v_, list) else v_) for k, v_ in opt.state_dict().items()}
+            sd = opt.state_dict()
+            sd["state"] = [{k: v_.clone() for k, v_ in st.items()} for st in sd["state"]]
             opt = SRAdamW(params, lr=1.0, max_norm=0.5, seed=0)
             opt.load_state_dict(sd)
+
+
+def test_optimizer_parameter_groups_and_torch_scheduler():
+    """Two groups (weights with decay, biases and gains without), a torch LR scheduler driving
+    `param_groups`, FP32 moments: equal to direct calls with one list per group, global tensor ids
+    and one norm over all gradients."""
+    from paper_2502_20566_amd.optimizer import SRAdamW
+    torch.manual_seed(1)
+    model = torch.nn.Sequential(torch.nn.Linear(40, 72), torch.nn.LayerNorm(72), torch.nn.Linear(72, 8)).to(DEV).to(torch.bfloat16)
+    decay = [p for p in model.parameters() if p.ndim == 2]
+    no_decay = [p for p in model.parameters() if p.ndim < 2]
+    opt = SRAdamW([{"params": decay}, {"params": no_decay, "weight_decay": 0.0, "lr": 2e-3}], lr=1e-3,
+                  betas=(0.9, 0.99), max_norm=1.0, seed=5, strategy="fp32_moments")
+    sched = torch.optim.lr_scheduler.LambdaLR(opt, lambda e: 1.0 / (1 + e))
+    groups = [decay, no_decay]
+    ref_p = [[p.detach().clone().view(-1) for p in g] for g in groups]
+    ref_m = [[torch.zeros(p.numel(), device=DEV) for p in g] for g in groups]
+    ref_v = [[torch.zeros(p.numel(), device=DEV) for p in g] for g in groups]
+    norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+    x = torch.randn(16, 40, device=DEV, dtype=torch.bfloat16)
+    for t in range(1, 5):
+        model(x).float().pow(2).mean().backward()
+        grads = [[p.grad.detach().clone().view(-1) for p in g] for g in groups]
+        lrs = [g["lr"] for g in opt.param_groups]
+        assert lrs == pytest.approx([1e-3 / t, 2e-3 / t])
+        opt.step()
+        opt.zero_grad()
+        sched.step()
+        flat_g = grads[0] + grads[1]
+        every = B.TensorList(ref_p[0] + ref_p[1], flat_g, flat_g, flat_g)
+        ws = torch.empty(max(every.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
+        B.grad_global_norm(every, norm, ws)
+        first = 0
+        for gi in range(2):
+            tl = B.TensorList(ref_p[gi], grads[gi], ref_m[gi], ref_v[gi], True,
+                              tensor_ids=list(range(first, first + len(groups[gi]))))
+            first += len(groups[gi])
+            hyper = dict(lr=lrs[gi], beta1=0.9, beta2=0.99, eps=1e-8, weight_decay=0.1 if gi == 0 else 0.0)
+            B.sr_adamw_step(tl, hyper, t, 5, B.SR_FLAG_FP32_MOMENTS, norm, 1.0)
+        torch.cuda.synchronize()
+        for g, rp, rm in zip(groups, ref_p, ref_m):
+            for a, b, m in zip(g, rp, rm):
+                assert torch.equal(a.detach().view(-1).view(torch.int16), b.view(torch.int16))
+                assert torch.equal(opt.state[a]["exp_avg"], m)
