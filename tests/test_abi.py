@@ -53,6 +53,37 @@ def test_library_exports_every_declared_symbol():
     assert C.sizeof(B.SrTensor) == 64 and C.sizeof(B.SrHyper) == 20
 
 
+def test_header_is_plain_c_and_struct_layouts_match_the_binding(tmp_path):
+    """include/sradamw.h compiles as C99 on its own, and the struct layouts the C compiler derives
+    from it are the ones the ctypes binding uses."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no host C compiler")
+    fields = {"sr_tensor_t": ["p", "g", "m", "v", "aux", "numel", "elem_offset", "tensor_id", "reserved"],
+              "sr_accum_t": ["acc", "grad", "numel", "elem_offset", "tensor_id", "reserved"],
+              "sr_hyper_t": ["lr", "beta1", "beta2", "eps", "weight_decay"]}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "sradamw.h"', 'int main(void) {']
+    for st, fs in fields.items():
+        lines.append(f'printf("{st} %zu", sizeof({st}));')
+        for f in fs:
+            lines.append(f'printf(" %zu", offsetof({st}, {f}));')
+        lines.append('printf("\\n");')
+    lines += ['return 0; }']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    ct = {"sr_tensor_t": B.SrTensor, "sr_accum_t": B.SrAccum, "sr_hyper_t": B.SrHyper}
+    for line in filter(None, out):
+        name, size, *offs = line.split()
+        assert int(size) == C.sizeof(ct[name])
+        assert [int(o) for o in offs] == [getattr(ct[name], f).offset for f in fields[name]]
+
+
 def test_strerror_covers_all_codes():
     L = B.lib()
     msgs = {c: L.sr_strerror(c).decode() for c in (0, -1, -2, -3, -4, -5, -99)}
