@@ -21,6 +21,18 @@ inline int hip_fail(hipError_t e)
     return SR_ERR_HIP;
 }
 
+// Launch with the launch's own status (a status left behind by an unrelated earlier call of the
+// application on this thread is neither reported nor cleared).  Argument types are taken from the
+// kernel's signature, so every argument is converted before its address is passed.
+template <class T> struct same_type { using type = T; };
+template <class... P>
+inline hipError_t launch(void (*kernel)(P...), uint32_t grid, uint32_t block, hipStream_t stream,
+                         typename same_type<P>::type... args)
+{
+    void* ptrs[] = {const_cast<void*>(static_cast<const void*>(&args))...};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), dim3(grid), dim3(block), ptrs, 0, stream);
+}
+
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // beta^t by repeated squaring in binary64.
@@ -80,9 +92,8 @@ hipError_t split_tensor(uint64_t numel, uint64_t elem_offset, uint64_t blocks_pe
 template <uint32_t F, bool VAR>
 hipError_t launch_adamw_v(bool clip, const AdamwBatch& batch, uint32_t n_chunks, hipStream_t stream)
 {
-    if (clip) hipLaunchKernelGGL((adamw_kernel<F, true, kNT, VAR>), dim3(n_chunks), dim3(kThreads), 0, stream, batch);
-    else      hipLaunchKernelGGL((adamw_kernel<F, false, kNT, VAR>), dim3(n_chunks), dim3(kThreads), 0, stream, batch);
-    return hipGetLastError();
+    return clip ? launch(adamw_kernel<F, true, kNT, VAR>, n_chunks, kThreads, stream, batch)
+                : launch(adamw_kernel<F, false, kNT, VAR>, n_chunks, kThreads, stream, batch);
 }
 
 // The default arithmetic runs in kernels compiled without the variant branches.
@@ -132,10 +143,9 @@ int sr_stream_probe(void* d_p, const void* d_g, void* d_m, void* d_v, uint64_t n
     const uint32_t mg = max_grid(kThreads);
     for (uint64_t w0 = 0; w0 < wgs; w0 += mg) {
         const uint32_t grid = (uint32_t)(wgs - w0 < mg ? wgs - w0 : mg);
-        hipLaunchKernelGGL(stream_probe_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
-                           static_cast<uint16_t*>(d_p), static_cast<const uint16_t*>(d_g), static_cast<uint16_t*>(d_m),
-                           static_cast<uint16_t*>(d_v), nblk, w0, 0u);
-        const hipError_t e = hipGetLastError();
+        const hipError_t e = launch(stream_probe_kernel, grid, kThreads, static_cast<hipStream_t>(stream),
+                                    static_cast<uint16_t*>(d_p), static_cast<const uint16_t*>(d_g),
+                                    static_cast<uint16_t*>(d_m), static_cast<uint16_t*>(d_v), nblk, w0, 0u);
         if (e != hipSuccess) return hip_fail(e);
     }
     return SR_OK;
@@ -170,10 +180,9 @@ int sr_cast_f32_bf16(const float* d_src, void* d_dst, uint64_t n, uint64_t seed,
     const uint32_t mg = max_grid(kThreads);
     for (uint64_t c0 = 0; c0 < chunks; c0 += mg) {
         const uint32_t grid = (uint32_t)(chunks - c0 < mg ? chunks - c0 : mg);
-        hipLaunchKernelGGL((cast_kernel<kNT>), dim3(grid), dim3(kThreads), 0,
-                           static_cast<hipStream_t>(stream), d_src, static_cast<uint16_t*>(d_dst), n, c0,
-                           (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), step, tensor_id);
-        const hipError_t e = hipGetLastError();
+        const hipError_t e = launch(cast_kernel<kNT>, grid, kThreads, static_cast<hipStream_t>(stream), d_src,
+                                    static_cast<uint16_t*>(d_dst), n, c0, (uint32_t)(seed & 0xFFFFFFFFu),
+                                    (uint32_t)(seed >> 32), step, tensor_id);
         if (e != hipSuccess) return hip_fail(e);
     }
     return SR_OK;
@@ -193,13 +202,9 @@ int sr_cast_f32_fp8(const float* d_src, void* d_dst, uint64_t n, uint32_t format
     const uint32_t lo = (uint32_t)(seed & 0xFFFFFFFFu), hi = (uint32_t)(seed >> 32);
     for (uint64_t c0 = 0; c0 < chunks; c0 += mg) {
         const uint32_t grid = (uint32_t)(chunks - c0 < mg ? chunks - c0 : mg);
-        if (format == SR_FP8_E4M3)
-            hipLaunchKernelGGL((cast_fp8_kernel<0, kNT>), dim3(grid), dim3(kThreads), 0, s, d_src,
-                               static_cast<uint8_t*>(d_dst), n, c0, lo, hi, step, tensor_id);
-        else
-            hipLaunchKernelGGL((cast_fp8_kernel<1, kNT>), dim3(grid), dim3(kThreads), 0, s, d_src,
-                               static_cast<uint8_t*>(d_dst), n, c0, lo, hi, step, tensor_id);
-        const hipError_t e = hipGetLastError();
+        const hipError_t e = format == SR_FP8_E4M3
+            ? launch(cast_fp8_kernel<0, kNT>, grid, kThreads, s, d_src, static_cast<uint8_t*>(d_dst), n, c0, lo, hi, step, tensor_id)
+            : launch(cast_fp8_kernel<1, kNT>, grid, kThreads, s, d_src, static_cast<uint8_t*>(d_dst), n, c0, lo, hi, step, tensor_id);
         if (e != hipSuccess) return hip_fail(e);
     }
     return SR_OK;
@@ -234,10 +239,10 @@ int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_no
         batch.n_tensors = nb;
         batch.partial_base = base;
         batch.chunk_start[nb] = chunks_in_batch;
-        hipLaunchKernelGGL(sumsq_partial_kernel, dim3(chunks_in_batch), dim3(kNormThreads), 0, s, batch, partials);
+        const hipError_t e = launch(sumsq_partial_kernel, chunks_in_batch, kNormThreads, s, batch, partials);
         base += chunks_in_batch;
         nb = 0; chunks_in_batch = 0;
-        return hipGetLastError();
+        return e;
     };
     const uint32_t mg = max_grid(kNormThreads);
     const uint64_t piece_elems = (uint64_t)mg * kNormChunkElems;      // whole chunks: same partial sums however cut
@@ -258,8 +263,7 @@ int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_no
     }
     hipError_t e = flush();
     if (e != hipSuccess) return hip_fail(e);
-    hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(kFinalThreads), 0, s, partials, (uint32_t)total_chunks, d_norm_out);
-    e = hipGetLastError();
+    e = launch(sumsq_final_kernel, 1, kFinalThreads, s, partials, (uint32_t)total_chunks, d_norm_out);
     return e == hipSuccess ? SR_OK : hip_fail(e);
 }
 
@@ -316,10 +320,10 @@ int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scal
         batch.n_tensors = nb;
         batch.partial_base = base;
         batch.chunk_start[nb] = chunks_in_batch;
-        hipLaunchKernelGGL(accumulate_kernel, dim3(chunks_in_batch), dim3(kAccThreads), 0, s, batch, partials);
+        const hipError_t e = launch(accumulate_kernel, chunks_in_batch, kAccThreads, s, batch, partials);
         base += chunks_in_batch;
         nb = 0; chunks_in_batch = 0;
-        return hipGetLastError();
+        return e;
     };
     const uint32_t mg = max_grid(kAccThreads);
     for (uint32_t i = 0; i < n_tensors; ++i) {
@@ -356,14 +360,12 @@ int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scal
         double* level = partials;
         while (n_level > kReduceAbove) {
             const uint32_t n_next = (n_level + kReduceFan - 1) / kReduceFan;
-            hipLaunchKernelGGL(sumsq_reduce_kernel, dim3(n_next), dim3(kReduceThreads), 0, s, level, n_level, level + n_level);
-            e = hipGetLastError();
+            e = launch(sumsq_reduce_kernel, n_next, kReduceThreads, s, level, n_level, level + n_level);
             if (e != hipSuccess) return hip_fail(e);
             level += n_level;
             n_level = n_next;
         }
-        hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(kFinalThreads), 0, s, level, n_level, d_norm_out);
-        e = hipGetLastError();
+        e = launch(sumsq_final_kernel, 1, kFinalThreads, s, level, n_level, d_norm_out);
         if (e != hipSuccess) return hip_fail(e);
     }
     return SR_OK;
