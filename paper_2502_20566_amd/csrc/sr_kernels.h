@@ -1,6 +1,7 @@
 // Kernels of the SR-AdamW update path for gfx950 (wave64): the fused multi-tensor update
 // (Algorithm 1 lines 5-10 of arXiv 2502.20566 with stochastically rounded write-backs), the
-// standalone SR cast, and the two-pass global gradient norm.
+// standalone SR casts (to BF16; to the OCP 8-bit formats as an extension), the BF16 gradient
+// accumulation with SR, the two-pass global gradient norm, and a no-arithmetic traffic probe.
 //
 // Work decomposition shared by all kernels: a tensor is cut into 8-element blocks aligned to the
 // RNG counter (block index = element index >> 3, so one Philox call serves one 128-bit BF16
