@@ -348,6 +348,23 @@ def main():
         ceiling = {"kind": "4-read/3-write copy of the same buffers, no arithmetic (sr_stream_probe)",
                    "ms": probe_ms, "GBps": 14 * numel / (probe_ms * 1e-3) / 1e9}
 
+    # a plain device copy of the same footprint per buffer (1 read : 1 write), torch's copy kernel
+    device_copy = None
+    if ceiling is not None:
+        big = max(range(len(params)), key=lambda i: params[i].numel())
+        src_t, dst_t = params[big], grads[big]                 # the gradients are not needed any more
+        dst_t.copy_(src_t)
+        torch.cuda.synchronize()
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(3):
+            dst_t.copy_(src_t)
+        c1.record()
+        torch.cuda.synchronize()
+        copy_ms = c0.elapsed_time(c1) / 3
+        device_copy = {"kind": "torch copy_ of the largest parameter tensor into its gradient buffer",
+                       "bytes": 4 * src_t.numel(), "ms": copy_ms, "GBps": 4 * src_t.numel() / (copy_ms * 1e-3) / 1e9}
+
     if args.calibrate_copy:
         src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -389,7 +406,7 @@ def main():
                      "kernel": "adamw_kernel" if cfg.clip is None and len(params) <= 56 else
                      "all launches of a step (norm passes + adamw_kernel per 56 tensors)", "avg_launch_ms": dev_avg_ms,
                      "median_launch_ms": float(np.median(dev_ms)), "min_launch_ms": float(np.min(dev_ms)),
-                     "copy_ceiling": ceiling,
+                     "copy_ceiling": ceiling, "device_copy": device_copy,
                      "frac_of_copy_ceiling": None if ceiling is None else
                      (MODES[mode][3] * numel / (dev_avg_ms * 1e-3) / 1e9) / ceiling["GBps"]},
         "cpu_baseline": cpu,
