@@ -157,6 +157,17 @@ int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_no
                      void* d_workspace, uint64_t workspace_bytes, void* stream);
 
 /*
+ * The same two passes, leaving the binary64 sum of squares S itself in
+ * *d_sumsq_out (device, 8-byte aligned) instead of (float) sqrt(S): what a
+ * job whose gradients are sharded over ranks adds up (one all-reduce of a
+ * double) before it takes the root and hands the norm to sr_adamw_step
+ * (Algorithm 1 runs data-parallel; the clip needs the norm of the whole
+ * gradient).  Arguments and workspace as for grad_global_norm.
+ */
+int grad_sum_of_squares(const sr_tensor_t* tensors, uint32_t n_tensors, double* d_sumsq_out,
+                        void* d_workspace, uint64_t workspace_bytes, void* stream);
+
+/*
  * One AdamW step with stochastically rounded write-backs over a tensor list
  * (Algorithm 1, lines 5-10; eps outside the root).  Per element, in binary32
  * with one rounding per operation and no fused multiply-add:

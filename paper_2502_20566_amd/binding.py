@@ -28,7 +28,7 @@ SR_ACC_FIRST = 2
 
 SR_FP8_E4M3, SR_FP8_E5M2 = 0, 1
 
-EXPORTS = ("sr_cast_f32_bf16", "sr_cast_f32_fp8", "grad_global_norm", "sr_adamw_step", "sr_workspace_bytes",
+EXPORTS = ("sr_cast_f32_bf16", "sr_cast_f32_fp8", "grad_global_norm", "grad_sum_of_squares", "sr_adamw_step", "sr_workspace_bytes",
            "sr_grad_accumulate", "sr_accumulate_workspace_bytes", "sr_stream_probe",
            "sr_strerror", "sr_last_hip_error", "sr_version", "sr_debug_set_launch_limit")
 
@@ -79,6 +79,8 @@ def lib():
         L.grad_global_norm.argtypes = [C.POINTER(SrTensor), C.c_uint32, C.c_void_p, C.c_void_p,
                                        C.c_uint64, C.c_void_p]
         L.grad_global_norm.restype = C.c_int
+        L.grad_sum_of_squares.argtypes = L.grad_global_norm.argtypes
+        L.grad_sum_of_squares.restype = C.c_int
         L.sr_adamw_step.argtypes = [C.POINTER(SrTensor), C.c_uint32, C.POINTER(SrHyper), C.c_uint32,
                                     C.c_uint64, C.c_uint32, C.c_void_p, C.c_float, C.c_void_p]
         L.sr_adamw_step.restype = C.c_int
@@ -214,6 +216,17 @@ def grad_global_norm(tl: TensorList, norm_out: torch.Tensor, workspace: torch.Te
                                 workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc != SR_OK:
         raise SrError(rc, "grad_global_norm")
+
+
+def grad_sum_of_squares(tl: TensorList, sumsq_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    """sumsq_out: float64 device tensor with one element (the sum of squares, not its root)."""
+    _check_dev(sumsq_out, torch.float64, "sumsq_out")
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous device tensor")
+    rc = lib().grad_sum_of_squares(tl.array, tl.n, sumsq_out.data_ptr(), workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if rc != SR_OK:
+        raise SrError(rc, "grad_sum_of_squares")
 
 
 def sr_adamw_step(tl: TensorList, hyper: dict, step: int, seed: int, flags: int = 0,

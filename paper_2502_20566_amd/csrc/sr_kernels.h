@@ -958,9 +958,11 @@ __global__ __launch_bounds__(kReduceThreads) void sumsq_reduce_kernel(const doub
     }
 }
 
-// Pass 2: one workgroup adds the partial sums in a fixed order and writes (float) sqrt(S).
+// Pass 2: one workgroup adds the partial sums in a fixed order and writes (float) sqrt(S) to `out`
+// and/or S itself to `out_sumsq` (either may be null).
 __global__ __launch_bounds__(kFinalThreads) void sumsq_final_kernel(const double* __restrict__ partials,
-                                                                   uint32_t n_partials, float* __restrict__ out)
+                                                                   uint32_t n_partials, float* __restrict__ out,
+                                                                   double* __restrict__ out_sumsq)
 {
     __shared__ double wsum[kFinalThreads / 64];
     double acc = 0.0;
@@ -973,7 +975,8 @@ __global__ __launch_bounds__(kFinalThreads) void sumsq_final_kernel(const double
         double s = 0.0;
 #pragma unroll
         for (int w = 0; w < kFinalThreads / 64; ++w) s += wsum[w];
-        *out = (float)__builtin_sqrt(s);
+        if (out) *out = (float)__builtin_sqrt(s);
+        if (out_sumsq) *out_sumsq = s;
     }
 }
 

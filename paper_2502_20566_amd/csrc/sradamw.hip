@@ -210,12 +210,12 @@ int sr_cast_f32_fp8(const float* d_src, void* d_dst, uint64_t n, uint32_t format
     return SR_OK;
 }
 
-int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_norm_out,
-                     void* d_workspace, uint64_t workspace_bytes, void* stream)
+static int sum_of_squares(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_norm_out, double* d_sumsq_out,
+                          void* d_workspace, uint64_t workspace_bytes, void* stream)
 {
-    if (!d_norm_out) return SR_ERR_NULL;
+    if (!d_norm_out && !d_sumsq_out) return SR_ERR_NULL;
     if (n_tensors && !tensors) return SR_ERR_NULL;
-    if (!aligned(d_norm_out, 4)) return SR_ERR_ALIGN;
+    if (!aligned(d_norm_out, 4) || !aligned(d_sumsq_out, 8)) return SR_ERR_ALIGN;
     uint64_t total_chunks = 0;
     for (uint32_t i = 0; i < n_tensors; ++i) {
         if (tensors[i].numel == 0) continue;
@@ -263,8 +263,20 @@ int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_no
     }
     hipError_t e = flush();
     if (e != hipSuccess) return hip_fail(e);
-    e = launch(sumsq_final_kernel, 1, kFinalThreads, s, partials, (uint32_t)total_chunks, d_norm_out);
+    e = launch(sumsq_final_kernel, 1, kFinalThreads, s, partials, (uint32_t)total_chunks, d_norm_out, d_sumsq_out);
     return e == hipSuccess ? SR_OK : hip_fail(e);
+}
+
+int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_norm_out,
+                     void* d_workspace, uint64_t workspace_bytes, void* stream)
+{
+    return sum_of_squares(tensors, n_tensors, d_norm_out, nullptr, d_workspace, workspace_bytes, stream);
+}
+
+int grad_sum_of_squares(const sr_tensor_t* tensors, uint32_t n_tensors, double* d_sumsq_out,
+                        void* d_workspace, uint64_t workspace_bytes, void* stream)
+{
+    return sum_of_squares(tensors, n_tensors, nullptr, d_sumsq_out, d_workspace, workspace_bytes, stream);
 }
 
 uint64_t sr_accumulate_workspace_bytes(uint32_t n_tensors, uint64_t total_numel)
@@ -365,7 +377,7 @@ int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scal
             level += n_level;
             n_level = n_next;
         }
-        e = launch(sumsq_final_kernel, 1, kFinalThreads, s, level, n_level, d_norm_out);
+        e = launch(sumsq_final_kernel, 1, kFinalThreads, s, level, n_level, d_norm_out, nullptr);
         if (e != hipSuccess) return hip_fail(e);
     }
     return SR_OK;

@@ -178,6 +178,16 @@ def test_norm_argument_errors():
     assert L.grad_global_norm(arr, 1, out, ws, 4096, None) == B.SR_ERR_NULL
 
 
+def test_sum_of_squares_argument_errors():
+    L = B.lib()
+    arr = (B.SrTensor * 1)(tensor(numel=100000))
+    ws = buf(4096)
+    assert L.grad_sum_of_squares(arr, 1, None, ws, 4096, None) == B.SR_ERR_NULL
+    assert L.grad_sum_of_squares(arr, 1, buf(16, 4), ws, 4096, None) == B.SR_ERR_ALIGN
+    assert L.grad_sum_of_squares(arr, 1, buf(16), None, 0, None) == B.SR_ERR_WORKSPACE
+    assert L.grad_sum_of_squares(arr, 1, buf(16), ws, 8, None) == B.SR_ERR_WORKSPACE
+
+
 def test_binding_rejects_host_tensors_and_wrong_dtypes():
     x = torch.zeros(8, dtype=torch.float32)
     y = torch.zeros(8, dtype=torch.bfloat16)

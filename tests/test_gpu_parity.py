@@ -492,6 +492,31 @@ def test_norm_matches_oracle_on_gpt_list_and_misaligned_views():
     assert np.isnan(_gpu_norm(grads))
 
 
+def test_sum_of_squares_of_shards_adds_up_to_the_global_norm():
+    """A gradient list split over four ranks: each rank's binary64 sum of squares, added on the host
+    as one all-reduce of a double would, rooted and rounded once, is the norm of the whole list."""
+    grads = W.make_grads(W.gpt_shapes(48, 2, 192, 1001, 32), DEV, 9, 1e-3, 0.01, 1.0)
+    whole = B.TensorList(grads, grads, grads, grads)
+    ws = torch.empty(max(whole.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
+    norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+    B.grad_global_norm(whole, norm, ws)
+    total = 0.0
+    for r in range(4):
+        part = grads[r::4]
+        tl = B.TensorList(part, part, part, part)
+        s = torch.zeros(1, dtype=torch.float64, device=DEV)
+        B.grad_sum_of_squares(tl, s, ws)
+        torch.cuda.synchronize()
+        want = sum(float((g.double() ** 2).sum().item()) for g in part)
+        assert abs(float(s.item()) - want) <= 1e-12 * want
+        total += float(s.item())
+    got = float(np.float32(np.sqrt(total)))
+    full = float(norm.item())
+    assert got == full or abs(got - full) <= float(np.spacing(np.float32(full)))
+    assert full == ref.grad_global_norm([to_np(g) for g in grads]) or \
+        abs(full - ref.grad_global_norm([to_np(g) for g in grads])) <= 1e-6 * full
+
+
 def test_norm_is_reproducible():
     g = W.make_grads(W.gpt_shapes(64, 2, 256, 5003, 64), DEV, 5, 1e-3)
     assert len({_gpu_norm(g) for _ in range(3)}) == 1
