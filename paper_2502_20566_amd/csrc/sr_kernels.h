@@ -823,7 +823,6 @@ __device__ __forceinline__ double wave_sum(double x)
 // values it wrote, so the global norm of the accumulated gradient costs no second pass over it.
 __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(const AccBatch B, double* __restrict__ partials)
 {
-    __shared__ double wsum[kAccThreads / 64];
     const uint32_t chunk = blockIdx.x;
     const uint32_t ti = find_tensor(B.chunk_start, B.n_tensors, chunk);
     const AccDesc& T = B.t[ti];
@@ -871,24 +870,37 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(const AccBatch 
         if (B.mode & ACC_NORM) {
             float w[8];
             unpack8(o, w);
+            if (full) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                // lanes of a partial block wrote only elements inside the tensor
-                const int64_t l = l0 + j;
-                const double wd = (l >= 0 && (uint64_t)l < numel) ? (double)w[j] : 0.0;
-                sq = __builtin_fma(wd, wd, sq);
+                for (int j = 0; j < 8; ++j) {
+                    const double wd = (double)w[j];
+                    sq = __builtin_fma(wd, wd, sq);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    // lanes of a partial block wrote only elements inside the tensor
+                    const int64_t l = l0 + j;
+                    const double wd = (l >= 0 && (uint64_t)l < numel) ? (double)w[j] : 0.0;
+                    sq = __builtin_fma(wd, wd, sq);
+                }
             }
         }
     }
     if (B.mode & ACC_NORM) {
         sq = wave_sum(sq);
-        if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = sq;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            double t = wsum[0];
+        if constexpr (kAccThreads == 64) {                     // one wave: its sum is the chunk's
+            if (threadIdx.x == 0) partials[B.partial_base + chunk] = sq;
+        } else {
+            __shared__ double wsum[kAccThreads / 64];
+            if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = sq;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                double t = wsum[0];
 #pragma unroll
-            for (int w = 1; w < kAccThreads / 64; ++w) t += wsum[w];
-            partials[B.partial_base + chunk] = t;
+                for (int w = 1; w < kAccThreads / 64; ++w) t += wsum[w];
+                partials[B.partial_base + chunk] = t;
+            }
         }
     }
 }
