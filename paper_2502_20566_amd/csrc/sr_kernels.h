@@ -141,6 +141,19 @@ __device__ __forceinline__ void store_v4(void* ptr, v4u x)
 }
 
 typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+typedef v2u v2u_a2 __attribute__((aligned(2)));
+template <bool NT>
+__device__ __forceinline__ v2u load_v2(const void* ptr)
+{
+    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const v2u_a2*>(ptr));
+    return *reinterpret_cast<const v2u_a2*>(ptr);
+}
+template <bool NT>
+__device__ __forceinline__ void store_v2(void* ptr, v2u x)
+{
+    if (NT) __builtin_nontemporal_store(x, reinterpret_cast<v2u_a2*>(ptr));
+    else *reinterpret_cast<v2u_a2*>(ptr) = x;
+}
 
 // Buffer accesses of the fast paths.  A workgroup describes its own span of each array (base =
 // first byte of the chunk, wave-uniform, in scalar registers; size = the chunk's bytes) and every
@@ -620,30 +633,45 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
         const uint64_t efirst = cl * (uint64_t)(kThreads * 4);
         if (vec && efirst + (uint64_t)(kThreads * 4) <= numel) {          // wave-uniform
             const uint64_t e = efirst + (uint64_t)threadIdx.x * 4;
-            const uint32_t o8 = threadIdx.x * 8u, o16 = threadIdx.x * 16u;
-            const rsrc_t rp = chunk_rsrc<uint16_t>(T.p, (int64_t)efirst, kThreads * 4u);
-            const rsrc_t rg = chunk_rsrc<uint16_t>(T.g, (int64_t)efirst, kThreads * 4u);
-            const rsrc_t rm = chunk_rsrc<float>(T.m, (int64_t)efirst, kThreads * 4u);
-            const rsrc_t rv = chunk_rsrc<float>(T.v, (int64_t)efirst, kThreads * 4u);
-            const rsrc_t rx = chunk_rsrc<float>(T.aux, (int64_t)efirst, kThreads * 4u);   // master parameters
-            LaneRegs<4> L;
-            if (M::master) floats4(buf_load16<NT>(rx, o16), L.aux);
-            else unpack4(buf_load8<NT>(rp, o8), L.p);
-            unpack4(buf_load8<NT>(rg, o8), L.g);
-            floats4(buf_load16<NT>(rm, o16), L.m);
-            floats4(buf_load16<NT>(rv, o16), L.v);
             uint32_t pw[2] = {0, 0};
-            if (!M::rnep) {
-                const u32x4 r = block_bits((G0 + e) >> 3, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
-                const bool upper = (threadIdx.x & 1u) != 0;                // elements 4..7 of the block
-                pw[0] = upper ? r.w[2] : r.w[0];
-                pw[1] = upper ? r.w[3] : r.w[1];
+            LaneRegs<4> L;
+            if constexpr (M::master) {
+                // buffer accesses (measured 29.8 ms against 30.9 ms with global ones on 6.66e9 elements)
+                const uint32_t o8 = threadIdx.x * 8u, o16 = threadIdx.x * 16u;
+                const rsrc_t rp = chunk_rsrc<uint16_t>(T.p, (int64_t)efirst, kThreads * 4u);
+                const rsrc_t rg = chunk_rsrc<uint16_t>(T.g, (int64_t)efirst, kThreads * 4u);
+                const rsrc_t rm = chunk_rsrc<float>(T.m, (int64_t)efirst, kThreads * 4u);
+                const rsrc_t rv = chunk_rsrc<float>(T.v, (int64_t)efirst, kThreads * 4u);
+                const rsrc_t rx = chunk_rsrc<float>(T.aux, (int64_t)efirst, kThreads * 4u);   // master parameters
+                floats4(buf_load16<NT>(rx, o16), L.aux);
+                unpack4(buf_load8<NT>(rg, o8), L.g);
+                floats4(buf_load16<NT>(rm, o16), L.m);
+                floats4(buf_load16<NT>(rv, o16), L.v);
+                update_lane<F, CLIP, VAR, 4>(L, S, c, pw, pw, pw);
+                buf_store8<NT>(rp, o8, words2(L.po));
+                buf_store16<NT>(rm, o16, bits4(L.m));
+                buf_store16<NT>(rv, o16, bits4(L.v));
+                buf_store16<NT>(rx, o16, bits4(L.aux));
+            } else {
+                // global accesses: with BF16 parameters read and written 8 bytes per lane this mix
+                // is 3% faster than with buffer accesses (23.1 against 23.8 ms)
+                float* mp = static_cast<float*>(T.m) + e;
+                float* vp = static_cast<float*>(T.v) + e;
+                unpack4(load_v2<NT>(T.p + e), L.p);
+                unpack4(load_v2<NT>(T.g + e), L.g);
+                floats4(load_v4<NT, 4>(mp), L.m);
+                floats4(load_v4<NT, 4>(vp), L.v);
+                if (!M::rnep) {
+                    const u32x4 r = block_bits((G0 + e) >> 3, STREAM_P, tensor_id, S.step, S.seed_lo, S.seed_hi);
+                    const bool upper = (threadIdx.x & 1u) != 0;            // elements 4..7 of the block
+                    pw[0] = upper ? r.w[2] : r.w[0];
+                    pw[1] = upper ? r.w[3] : r.w[1];
+                }
+                update_lane<F, CLIP, VAR, 4>(L, S, c, pw, pw, pw);
+                store_v2<NT>(T.p + e, words2(L.po));
+                store_v4<NT, 4>(mp, bits4(L.m));
+                store_v4<NT, 4>(vp, bits4(L.v));
             }
-            update_lane<F, CLIP, VAR, 4>(L, S, c, pw, pw, pw);
-            buf_store8<NT>(rp, o8, words2(L.po));
-            buf_store16<NT>(rm, o16, bits4(L.m));
-            buf_store16<NT>(rv, o16, bits4(L.v));
-            if (M::master) buf_store16<NT>(rx, o16, bits4(L.aux));
             return;
         }
         // Tail chunk, or counter blocks that do not start at element 0: the chunk's kThreads/2
