@@ -208,8 +208,8 @@ typedef struct sr_accum {
 /*
  * BF16 gradient accumulation over micro-batches with a stochastically rounded
  * write-back, and (optionally) the global norm of the result in the same pass.
- * "Every tensor in BF16" (Section 3) includes the gradient buffer that micro-
- * batches accumulate into (gradient accumulation steps: Section 5.2 "Memory");
+ * Section 3 keeps all training tensors in BF16; that includes the gradient
+ * buffer that micro-batches accumulate into (accumulation steps: Section 5.2);
  * nearest rounding would stop accumulating once acc dwarfs the micro-gradient
  * (the x + u example of Section 2.1), SR does not in expectation.
  * Per element, binary32, one rounding per operation:
@@ -239,8 +239,8 @@ uint64_t sr_workspace_bytes(uint32_t n_tensors, uint64_t total_numel);
 
 /*
  * Measurement aid, not part of the method: the memory traffic of the BF16 step
- * (8 bytes read, 6 written per element: the 14 bytes per element of "every
- * tensor in BF16", Section 3) with no arithmetic -- reads p, g, m, v and writes
+ * (8 bytes read, 6 written per element: the 14 bytes per element of an
+ * all-BF16 state, Section 3) with no arithmetic -- reads p, g, m, v and writes
  * p, m, v back UNCHANGED, in the launch geometry of sr_adamw_step.  Its time on
  * the caller's own buffers is the rate this access pattern can reach on them,
  * the ceiling the step is compared with.  BF16 arrays [numel], 2-byte aligned;
