@@ -836,11 +836,30 @@ __global__ __launch_bounds__(kThreads) void cast_fp8_kernel(const float* __restr
 
 // ------------------------------------------------------------------------- gradient norm
 
+// x of the lane that a DPP control selects (0.0 where the control selects none or the row is masked).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_read(double x)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, ROW_MASK, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, ROW_MASK, 0xF, true);
+    return __hiloint2double(hi, lo);
+}
+
+// Sum of x over the 64 lanes in a fixed order, returned in every lane: running sums inside each row
+// of 16 lanes (row_shr 1, 2, 4, 8), then row 0's total into row 1 and row 2's into row 3
+// (row_bcast:15), then the lower half's total into the upper half (row_bcast:31); lane 63 holds the
+// wave's sum.  Register-to-register moves: no trip through the LDS crossbar as with ds_bpermute.
 __device__ __forceinline__ double wave_sum(double x)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
-    return x;                                   // lane 0 holds the wave's sum
+    x += dpp_read<0x111, 0xF>(x);
+    x += dpp_read<0x112, 0xF>(x);
+    x += dpp_read<0x114, 0xF>(x);
+    x += dpp_read<0x118, 0xF>(x);
+    x += dpp_read<0x142, 0xA>(x);
+    x += dpp_read<0x143, 0xC>(x);
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), 63);
+    return __hiloint2double(hi, lo);
 }
 
 // ----------------------------------------------------------------- gradient accumulation
