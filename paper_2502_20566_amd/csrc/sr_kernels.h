@@ -795,21 +795,18 @@ __global__ __launch_bounds__(kThreads) void cast_fp8_kernel(const float* __restr
 {
     using P = Fp8<FMT>;
     const uint64_t cfirst = ((uint64_t)blockIdx.x + chunk0) * (uint64_t)kFp8ChunkElems;
-    const bool whole = cfirst + (uint64_t)kFp8ChunkElems <= n;       // wave-uniform
-    const rsrc_t rs = chunk_rsrc<float>(src, (int64_t)cfirst, kFp8ChunkElems);
-    const rsrc_t rd = chunk_rsrc<uint8_t>(dst, (int64_t)cfirst, kFp8ChunkElems);
-    v4u xs[kFp8Iters];
-    if (whole) {
+    if (cfirst + (uint64_t)kFp8ChunkElems <= n) {                     // wave-uniform: a whole chunk
+        const rsrc_t rs = chunk_rsrc<float>(src, (int64_t)cfirst, kFp8ChunkElems);
+        const rsrc_t rd = chunk_rsrc<uint8_t>(dst, (int64_t)cfirst, kFp8ChunkElems);
+        v4u xs[kFp8Iters];
 #pragma unroll
         for (int it = 0; it < kFp8Iters; ++it) xs[it] = buf_load16<NT>(rs, (uint32_t)(it * kThreads + threadIdx.x) * 16u);
-    }
 #pragma unroll
-    for (int it = 0; it < kFp8Iters; ++it) {
-        const uint64_t e = cfirst + (uint64_t)(it * kThreads + threadIdx.x) * 4;
-        if (e >= n) return;
-        const u32x4 r = philox4x32_10((uint32_t)(e >> 2), (STREAM_FP8 << 29) | (uint32_t)(e >> 34), tensor_id, step,
-                                      seed_lo, seed_hi);
-        if (whole) {
+        for (int it = 0; it < kFp8Iters; ++it) {
+            const uint32_t row = (uint32_t)(it * kThreads) + threadIdx.x;
+            const uint64_t e = cfirst + (uint64_t)row * 4;
+            const u32x4 r = philox4x32_10((uint32_t)(e >> 2), (STREAM_FP8 << 29) | (uint32_t)(e >> 34), tensor_id, step,
+                                          seed_lo, seed_hi);
             const v4u x = xs[it];
             const uint32_t b[4] = {x.x, x.y, x.z, x.w};
             uint32_t c[4];
@@ -823,13 +820,20 @@ __global__ __launch_bounds__(kThreads) void cast_fp8_kernel(const float* __restr
             const uint32_t signs = ((x.x >> 24) & 0x80u) | ((x.y >> 16) & 0x8000u) | ((x.z >> 8) & 0x800000u) |
                                    (x.w & 0x80000000u);
             const uint32_t o = (c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24)) | signs;
-            __builtin_amdgcn_raw_buffer_store_b32(o, rd, (int)((uint32_t)(it * kThreads + threadIdx.x) * 4u), 0, NT ? 2 : 0);
-        } else {
-            // tail chunk: element-wise with bounds
+            __builtin_amdgcn_raw_buffer_store_b32(o, rd, (int)(row * 4u), 0, NT ? 2 : 0);
+        }
+        return;
+    }
+    // tail chunk: element-wise with bounds
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (e + j < n) dst[e + j] = (uint8_t)fp8_code<FMT>(__float_as_uint(src[e + j]), r.w[j]);
-            }
+    for (int it = 0; it < kFp8Iters; ++it) {
+        const uint64_t e = cfirst + (uint64_t)(it * kThreads + threadIdx.x) * 4;
+        if (e >= n) return;
+        const u32x4 r = philox4x32_10((uint32_t)(e >> 2), (STREAM_FP8 << 29) | (uint32_t)(e >> 34), tensor_id, step,
+                                      seed_lo, seed_hi);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (e + j < n) dst[e + j] = (uint8_t)fp8_code<FMT>(__float_as_uint(src[e + j]), r.w[j]);
         }
     }
 }
