@@ -895,14 +895,22 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(const AccBatch 
         const int64_t l0 = (int64_t)((gblk0 + b) << 3) - (int64_t)G0;
         const bool full = block_inside(l0, numel);
         const uint32_t off = (uint32_t)(it * kAccThreads + threadIdx.x) * 16u;
-        float a[8], g[8], s[8];
-        unpack8(full ? buf_load16<true>(rg, off) : load8_bf16<false>(T.g, l0, numel, false), g);
-        if (first) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) a[j] = 0.0f;
-        } else {
-            unpack8(full ? buf_load16<true>(ra, off) : load8_bf16<false>(T.acc, l0, numel, false), a);
+        // whole blocks: buffer loads first, the Philox draw (which needs no data) while they are
+        // in flight; blocks at a tensor's ragged ends: element-wise with bounds
+        v4u gq = {}, aq = {};
+        if (full) {
+            gq = buf_load16<true>(rg, off);
+            if (!first) aq = buf_load16<true>(ra, off);
         }
+        u32x4 r = {};
+        if (!rne) r = block_bits(gblk0 + b, STREAM_ACC, T.tensor_id, B.micro_step, B.seed_lo, B.seed_hi);
+        if (!full) {
+            gq = load8_bf16<false>(T.g, l0, numel, false);
+            if (!first) aq = load8_bf16<false>(T.acc, l0, numel, false);
+        }
+        float a[8], g[8], s[8];
+        unpack8(gq, g);
+        unpack8(aq, a);                                          // zeros for the first micro-batch
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float t = B.scale * g[j];
@@ -913,7 +921,6 @@ __global__ __launch_bounds__(kAccThreads) void accumulate_kernel(const AccBatch 
             o.x = rne_pair(s[0], s[1]); o.y = rne_pair(s[2], s[3]);
             o.z = rne_pair(s[4], s[5]); o.w = rne_pair(s[6], s[7]);
         } else {
-            const u32x4 r = block_bits(gblk0 + b, STREAM_ACC, T.tensor_id, B.micro_step, B.seed_lo, B.seed_hi);
             o = any_nan8(s) ? sr8<true>(s, r) : sr8<false>(s, r);
         }
         if (full) buf_store16<true>(ra, off, o);
