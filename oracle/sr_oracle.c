@@ -256,14 +256,18 @@ uint32_t ref_r32(uint64_t seed, uint32_t step, uint32_t tensor_id, uint64_t i, u
 }
 
 /* Eq.(2) on an 8-bit grid, by the interval definition on VALUES: lo = largest
- * grid magnitude <= |y|, hi = next one, k = floor(2^32 (|y|-lo)/(hi-lo)), and
- * the magnitude becomes hi exactly when r32 + k >= 2^32 (probability k/2^32,
- * which is (|y|-lo)/(hi-lo) itself whenever that has at most 32 fractional
- * bits: always for |y| at or above the smallest subnormal times 2^-9).  Sign
- * kept.  Out of range: E5M2 follows the binary16-like rule (a magnitude above
- * 57344 has hi = 65536, emitted as infinity; infinities pass); E4M3 has no
- * infinity and saturates (magnitudes >= 448, infinities included, become 448).
- * NaN becomes S.1111111 in either format. */
+ * grid magnitude <= |y|, hi = next one.  The draw has D = 23 - mb bits, as many
+ * as binary32 has below the format's mantissa (20 for E4M3, 21 for E5M2): the
+ * top D bits of the element's 32-bit random word.  k = floor(2^D (|y|-lo)/(hi-lo))
+ * and the magnitude becomes hi exactly when r_D + k >= 2^D (probability k/2^D).
+ * For every |y| at or above the format's smallest normal, (|y|-lo)/(hi-lo) has
+ * at most D fractional bits, so the probability is Eq.(2)'s exactly; below it
+ * (the fixed spacing of the subnormal range) the fraction is truncated to D
+ * bits, a bias of less than 2^-D of one spacing.  Sign kept.  Out of range:
+ * E5M2 follows the binary16-like rule (a magnitude above 57344 has hi = 65536,
+ * emitted as infinity; infinities pass); E4M3 has no infinity and saturates
+ * (magnitudes >= 448, infinities included, become 448).  NaN becomes S.1111111
+ * in either format. */
 uint8_t ref_sr_round_fp8(float y, uint32_t r32, int format)
 {
     const int mb = format == 0 ? 3 : 2, emin = format == 0 ? -6 : -14;
@@ -282,8 +286,11 @@ uint8_t ref_sr_round_fp8(float y, uint32_t r32, int format)
         double spacing = ldexp(1.0, E - mb);
         double t = a / spacing;                      /* exact: power-of-two scale  */
         double n = floor(t);
-        double k = floor((t - n) * 4294967296.0);    /* t - n exact; scaled exactly */
-        if ((double)r32 + k >= 4294967296.0) n += 1.0;
+        const int D = 23 - mb;
+        double scale = ldexp(1.0, D);
+        double k = floor((t - n) * scale);           /* t - n exact; scaled exactly */
+        double rD = (double)(r32 >> (32 - D));       /* the draw: top D bits of the word */
+        if (rD + k >= scale) n += 1.0;
         mag = n * spacing;
         if (mag > maxfin) mag = INFINITY;            /* E5M2 only: hi = 65536      */
     }

@@ -13,6 +13,14 @@ from oracle import ref
 
 FMTS = {ref.E4M3: (torch.float8_e4m3fn, 448.0), ref.E5M2: (torch.float8_e5m2, 57344.0)}
 TWO32 = 1 << 32
+DRAW_BITS = {ref.E4M3: 20, ref.E5M2: 21}          # binary32's 23 fraction bits minus the format's 3 / 2
+MIN_NORMAL = {ref.E4M3: Fraction(1, 1 << 6), ref.E5M2: Fraction(1, 1 << 14)}
+
+
+def word(draw, fmt, low_ones=False):
+    """A 32-bit random word whose top D bits are `draw`; the bits below are not part of the draw."""
+    low = 32 - DRAW_BITS[fmt]
+    return (draw << low) | (((1 << low) - 1) if low_ones else 0)
 
 
 def table(fmt):
@@ -53,9 +61,12 @@ def neighbours(a: Fraction, fmt):
 
 @pytest.mark.parametrize("fmt", [ref.E4M3, ref.E5M2])
 def test_rounding_law_is_exact_at_the_threshold_draw(fmt):
-    """For y in a cell [lo, hi): k = floor(2^32 (|y|-lo)/(hi-lo)); draw 2^32-k-1 keeps lo, draw
-    2^32-k gives hi.  Values span the subnormal range, binade edges and the top cell."""
+    """For y in a cell [lo, hi): k = floor(2^D (|y|-lo)/(hi-lo)) with D draw bits (the top D bits of
+    the word); draw 2^D-k-1 keeps lo, draw 2^D-k gives hi, whatever the word's lower bits hold.  At or
+    above the smallest normal the fraction has at most D bits (the probability is Eq.(2)'s exactly);
+    below it the fraction is truncated.  Values span the subnormal range, binade edges, the top cell."""
     _, maxfin = FMTS[fmt]
+    D = DRAW_BITS[fmt]
     rng = np.random.default_rng(8 + fmt)
     tiny = 2.0 ** (-9 if fmt == ref.E4M3 else -16)
     ys = np.concatenate([
@@ -64,32 +75,39 @@ def test_rounding_law_is_exact_at_the_threshold_draw(fmt):
         np.array([v * s for v, _ in table(fmt)[1:] for s in (1 - 2.0 ** -24, 1 + 2.0 ** -23)]),
     ]).astype(np.float32)
     ys = ys[np.abs(ys) < maxfin]
-    checked_up = checked_dn = 0
+    checked_up = checked_dn = exact = truncated = 0
     for y in ys:
         a = Fraction(float(abs(y)))
         (lo, clo), hi = neighbours(a, fmt)
         sign = 0x80 if np.signbit(y) else 0
         assert hi is not None
-        k = (a - lo) * TWO32 // (hi[0] - lo)
-        assert 0 <= k < TWO32
+        k = (a - lo) * (1 << D) // (hi[0] - lo)
+        assert 0 <= k < (1 << D)
         if k > 0:
-            assert ref.sr_round_fp8(y, TWO32 - k, fmt) == sign | hi[1]
+            assert ref.sr_round_fp8(y, word((1 << D) - k, fmt), fmt) == sign | hi[1]
+            assert ref.sr_round_fp8(y, word((1 << D) - k, fmt, True), fmt) == sign | hi[1]
             checked_up += 1
-        assert ref.sr_round_fp8(y, TWO32 - k - 1, fmt) == sign | clo
+        assert ref.sr_round_fp8(y, word((1 << D) - k - 1, fmt, True), fmt) == sign | clo
+        assert ref.sr_round_fp8(y, word((1 << D) - k - 1, fmt), fmt) == sign | clo
         assert ref.sr_round_fp8(y, 0, fmt) == sign | clo
         checked_dn += 1
-        if (a - lo) * TWO32 % (hi[0] - lo) == 0:           # probability exact: E[Q(y)] = y
-            assert lo + (hi[0] - lo) * Fraction(k, TWO32) == a
-    assert checked_up > 1000 and checked_dn > 1000
+        rem = (a - lo) * (1 << D) % (hi[0] - lo)
+        if a >= MIN_NORMAL[fmt]:                               # probability exact: E[Q(y)] = y
+            assert rem == 0 and lo + (hi[0] - lo) * Fraction(k, 1 << D) == a
+            exact += 1
+        elif rem != 0:                                         # truncated: short by less than 2^-D of a cell
+            assert 0 < a - (lo + (hi[0] - lo) * Fraction(k, 1 << D)) < (hi[0] - lo) * Fraction(1, 1 << D)
+            truncated += 1
+    assert checked_up > 1000 and checked_dn > 1000 and exact > 800 and truncated > 50
 
 
 def test_top_cell_and_out_of_range():
     # E5M2: above 57344 the upper neighbour is 2^16, emitted as infinity
     y = np.float32(60000.0)
-    k = (Fraction(60000) - 57344) * TWO32 // (65536 - 57344)
-    assert ref.sr_round_fp8(y, TWO32 - k, ref.E5M2) == 0x7C
-    assert ref.sr_round_fp8(y, TWO32 - k - 1, ref.E5M2) == 0x7B
-    assert ref.sr_round_fp8(-y, TWO32 - k, ref.E5M2) == 0xFC
+    k = (Fraction(60000) - 57344) * (1 << 21) // (65536 - 57344)
+    assert ref.sr_round_fp8(y, word((1 << 21) - k, ref.E5M2), ref.E5M2) == 0x7C
+    assert ref.sr_round_fp8(y, word((1 << 21) - k - 1, ref.E5M2, True), ref.E5M2) == 0x7B
+    assert ref.sr_round_fp8(-y, word((1 << 21) - k, ref.E5M2), ref.E5M2) == 0xFC
     assert ref.sr_round_fp8(np.float32(1e30), 0, ref.E5M2) == 0x7C          # beyond 2^16: infinity
     assert ref.sr_round_fp8(np.float32(np.inf), 0, ref.E5M2) == 0x7C
     assert ref.sr_round_fp8(np.float32(-np.inf), 7, ref.E5M2) == 0xFC
