@@ -18,6 +18,9 @@ namespace sr {
 // ones (finer interleaving of the seven streams in time), and more blocks per lane are slower.
 // Rows of 4 elements per lane in the cast kernels.  Measured on 6.66e9 elements: BF16 cast 6.06 /
 // 6.10 / 7.04 ms with 1 / 2 / 4 rows; 8-bit cast 6.07 / 5.64 / 5.64 ms.
+#ifndef SR_TUNE_FP8_NOHW
+#define SR_TUNE_FP8_NOHW 0
+#endif
 #ifndef SR_TUNE_CAST_ITERS
 #define SR_TUNE_CAST_ITERS 1
 #endif
@@ -809,17 +812,33 @@ __global__ __launch_bounds__(kThreads) void cast_fp8_kernel(const float* __restr
                                           seed_lo, seed_hi);
             const v4u x = xs[it];
             const uint32_t b[4] = {x.x, x.y, x.z, x.w};
-            uint32_t c[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) c[j] = sr_fp8_magnitude<P::mb, P::ef>(b[j], r.w[j]);
-            const uint32_t big = (x.x | x.y | x.z | x.w) & 0x7FFFFFFFu;  // >= the largest magnitude's binade
-            if (__builtin_amdgcn_ballot_w64(big >= (P::efmax << 23)) != 0) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) c[j] = fp8_finish<P::top>(b[j], c[j]);
+            // the largest of the four magnitudes, as encodings (NaNs compare above everything)
+            const uint32_t big = max(max(x.x & 0x7FFFFFFFu, x.y & 0x7FFFFFFFu), max(x.z & 0x7FFFFFFFu, x.w & 0x7FFFFFFFu));
+            uint32_t o;
+            if (SR_TUNE_FP8_NOHW || __builtin_amdgcn_ballot_w64(big >= (P::efmax << 23)) != 0) {
+                // some lane holds a value in the format's top binade or above (or an infinity or a
+                // NaN): the range rules apply, integer path for the whole wave
+                o = fp8_code<FMT>(b[0], r.w[0]) | (fp8_code<FMT>(b[1], r.w[1]) << 8) |
+                    (fp8_code<FMT>(b[2], r.w[2]) << 16) | (fp8_code<FMT>(b[3], r.w[3]) << 24);
+            } else {
+                // below the top binade the conversion instruction of the chip computes the same
+                // function of (value, random word): it adds the word's top 23 - mb bits to the
+                // dropped fraction cut to as many bits and keeps the carry, subnormal results
+                // included (checked against the by-value oracle on every binary32 encoding)
+                int w = 0;
+                if (FMT == 0) {
+                    w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(x.x), (int)r.w[0], w, 0);
+                    w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(x.y), (int)r.w[1], w, 1);
+                    w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(x.z), (int)r.w[2], w, 2);
+                    w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(x.w), (int)r.w[3], w, 3);
+                } else {
+                    w = __builtin_amdgcn_cvt_sr_bf8_f32(__uint_as_float(x.x), (int)r.w[0], w, 0);
+                    w = __builtin_amdgcn_cvt_sr_bf8_f32(__uint_as_float(x.y), (int)r.w[1], w, 1);
+                    w = __builtin_amdgcn_cvt_sr_bf8_f32(__uint_as_float(x.z), (int)r.w[2], w, 2);
+                    w = __builtin_amdgcn_cvt_sr_bf8_f32(__uint_as_float(x.w), (int)r.w[3], w, 3);
+                }
+                o = (uint32_t)w;
             }
-            const uint32_t signs = ((x.x >> 24) & 0x80u) | ((x.y >> 16) & 0x8000u) | ((x.z >> 8) & 0x800000u) |
-                                   (x.w & 0x80000000u);
-            const uint32_t o = (c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24)) | signs;
             __builtin_amdgcn_raw_buffer_store_b32(o, rd, (int)(row * 4u), 0, NT ? 2 : 0);
         }
         return;

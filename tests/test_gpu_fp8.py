@@ -1,6 +1,7 @@
 """GPU parity of sr_cast_f32_fp8 (extension: Eq.(2) of Section 2.1 on the OCP 8-bit grids) against the
-CPU oracle, bit for bit, through the C ABI.  The kernel works on encodings (one 64-bit shift of the
-significand, carry of a 32-bit add); the oracle on values (frexp/floor/ldexp and a search of the
+CPU oracle, bit for bit, through the C ABI.  The kernel works on encodings (the chip's conversion
+instruction for waves that hold nothing near the top of the format's range, else a split of the
+significand and the carry of an add); the oracle on values (frexp/floor/ldexp and a search of the
 decoded grid): they share nothing but the published formats and the Philox layout."""
 import numpy as np
 import pytest
@@ -95,6 +96,27 @@ def test_fp8_cast_strided_sweep_of_all_encodings(gfmt, ofmt):
     bits = np.concatenate([sweep] + bands)
     got = gpu_cast(from_bits(bits), gfmt, 3, 8, 6)
     want = ref.sr_cast_f32_fp8(bits.view(np.float32), ofmt, 3, 8, 6)
+    bad = np.flatnonzero(got != want)
+    assert bad.size == 0, (hex(int(bits[bad[0]])), got[bad[0]], want[bad[0]])
+
+
+@pytest.mark.parametrize("gfmt,ofmt", FMTS)
+def test_fp8_cast_wave_with_a_value_near_the_top_of_the_range(gfmt, ofmt):
+    """A wave takes the integer path as a whole when one of its 256 values lies in the format's top
+    binade or above, is infinite or a NaN.  Plant one such value in every wave of a sweep over all
+    exponents (every 251st encoding and the band around the smallest normal), so that the integer
+    path meets subnormal results, binade edges and zeros too, and must agree with the oracle there
+    as the conversion instruction does in the other tests."""
+    sweep = np.arange(0, 1 << 32, 251, dtype=np.uint64).astype(np.uint32)
+    c = int(np.float32(2.0 ** (-6 if ofmt == ref.E4M3 else -14)).view(np.uint32))
+    band = np.arange(c - (1 << 18), c + (1 << 18), dtype=np.uint64).astype(np.uint32)
+    bits = np.concatenate([sweep, band])
+    top = np.array([300.0, -447.0, np.inf, np.nan] if ofmt == ref.E4M3 else [40000.0, -57000.0, -np.inf, np.nan],
+                   dtype=np.float32).view(np.uint32)
+    where = np.arange(7, bits.size, 256)
+    bits[where] = top[np.arange(where.size) % 4]
+    got = gpu_cast(from_bits(bits), gfmt, 12, 9, 4)
+    want = ref.sr_cast_f32_fp8(bits.view(np.float32), ofmt, 12, 9, 4)
     bad = np.flatnonzero(got != want)
     assert bad.size == 0, (hex(int(bits[bad[0]])), got[bad[0]], want[bad[0]])
 
