@@ -21,6 +21,7 @@ FLAG_MASTER_FP32 = 8
 FLAG_KAHAN = 16
 FLAG_EPS_IN_ROOT = 32
 FLAG_DIV_BIAS = 64
+FLAG_FP8_MOMENTS = 128
 
 STREAM_PARAM, STREAM_M, STREAM_V, STREAM_CAST, STREAM_ACC = 0, 1, 2, 3, 4
 ACC_RNE = 1
@@ -79,6 +80,14 @@ def lib():
                                           C.c_uint32, C.c_uint64, C.POINTER(Scalars),
                                           C.c_uint32, C.c_uint64, C.c_uint32, C.c_int]
         L.ref_sr_adamw_tensor.restype = None
+        u8p = C.POINTER(C.c_uint8)
+        L.ref_sr_adamw_tensor_fp8m.argtypes = [u16p, u16p, u8p, u8p, C.c_uint64, C.c_uint32, C.c_uint64,
+                                               C.POINTER(Scalars), C.c_uint32, C.c_uint64, C.c_uint32,
+                                               C.c_int, C.c_int, C.c_int]
+        L.ref_sr_adamw_tensor_fp8m.restype = None
+        L.ref_adamw_unrounded_fp8m.argtypes = [u16p, u16p, u8p, u8p, C.c_uint64, C.POINTER(Scalars),
+                                               C.c_uint32, C.c_int, C.c_int, f32p, f32p, f32p]
+        L.ref_adamw_unrounded_fp8m.restype = None
         L.ref_grad_accumulate.argtypes = [u16p, u16p, C.c_uint64, C.c_float, C.c_uint32, C.c_uint64,
                                           C.c_uint32, C.c_uint64, C.c_uint32, C.c_int]
         L.ref_grad_accumulate.restype = None
@@ -246,6 +255,28 @@ def sr_adamw_tensor(p, g, m, v, tensor_id, scalars: Scalars, step, seed, flags=0
                               flags, nthreads)
 
 
+def _u8(a):
+    assert a.dtype == np.uint8 and a.flags.c_contiguous
+    return a.ctypes.data_as(C.POINTER(C.c_uint8))
+
+
+def sr_adamw_tensor_fp8m(p, g, m8, v8, tensor_id, scalars: Scalars, step, seed, m_exp, v_exp, flags=0,
+                         elem_offset=0, nthreads=0):
+    """One tensor with 8-bit moments (m8: E4M3 codes of m * 2^m_exp, v8: E5M2 codes of v * 2^v_exp),
+    in place over p, m8, v8."""
+    assert p.size == g.size == m8.size == v8.size and abs(m_exp) <= 100 and abs(v_exp) <= 100
+    lib().ref_sr_adamw_tensor_fp8m(_u16(p), _u16(g), _u8(m8), _u8(v8), p.size, tensor_id, elem_offset,
+                                   C.byref(scalars), step, seed, flags, m_exp, v_exp, nthreads)
+
+
+def adamw_unrounded_fp8m(p, g, m8, v8, scalars: Scalars, m_exp, v_exp, flags=0):
+    n = p.size
+    y, m1, v1 = np.empty(n, np.float32), np.empty(n, np.float32), np.empty(n, np.float32)
+    lib().ref_adamw_unrounded_fp8m(_u16(p), _u16(g), _u8(m8), _u8(v8), n, C.byref(scalars), flags,
+                                   m_exp, v_exp, _f32(y), _f32(m1), _f32(v1))
+    return y, m1, v1
+
+
 def sr_adamw_step(tensors, hyper, step, seed, flags=0, norm=None, max_norm=0.0, nthreads=0):
     """Multi-tensor step: `tensors` is a list of dicts with numpy arrays p, g, m, v and
     optional tensor_id (default: list index) and elem_offset (default 0).
@@ -253,8 +284,12 @@ def sr_adamw_step(tensors, hyper, step, seed, flags=0, norm=None, max_norm=0.0, 
     s = adamw_scalars(hyper["lr"], hyper["beta1"], hyper["beta2"], hyper["eps"],
                       hyper["weight_decay"], step, norm, max_norm)
     for idx, t in enumerate(tensors):
-        sr_adamw_tensor(t["p"], t["g"], t["m"], t["v"], t.get("tensor_id", idx), s, step, seed,
-                        flags, t.get("elem_offset", 0), nthreads, aux=t.get("aux"))
+        if flags & FLAG_FP8_MOMENTS:
+            sr_adamw_tensor_fp8m(t["p"], t["g"], t["m"], t["v"], t.get("tensor_id", idx), s, step, seed,
+                                 t["m_exp"], t["v_exp"], flags & ~FLAG_FP8_MOMENTS, t.get("elem_offset", 0), nthreads)
+        else:
+            sr_adamw_tensor(t["p"], t["g"], t["m"], t["v"], t.get("tensor_id", idx), s, step, seed,
+                            flags, t.get("elem_offset", 0), nthreads, aux=t.get("aux"))
     return s
 
 

@@ -35,7 +35,10 @@
  * Algorithm 1 on tiny inputs, torch.optim.AdamW on FP32 state, exact norms;
  * for the 8-bit extension (the conclusion's FP8 remark; the formats are the
  * OCP ones, not the paper's): torch's float8 decoders for the grids, exact
- * rational thresholds on brute-force neighbours, torch's nearest conversion.
+ * rational thresholds on brute-force neighbours, torch's nearest conversion;
+ * for the update with 8-bit moments: bit equality with the BF16-moment path on
+ * states both can hold (values from torch's decoders), exact-rational write-back
+ * thresholds with draws read from the Philox streams, means over 4000 seeds.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -53,6 +56,7 @@
 #define REF_FLAG_KAHAN       16u
 #define REF_FLAG_EPS_IN_ROOT 32u
 #define REF_FLAG_DIV_BIAS    64u
+#define REF_FLAG_FP8_MOMENTS 128u
 
 /* ---------------------------------------------------------------- RNG --- */
 
@@ -485,6 +489,60 @@ void ref_sr_adamw_tensor(uint16_t* p, const uint16_t* g, void* m, void* v, void*
             ((uint16_t*)m)[i] = ref_sr_round(m1, ref_r16(seed, step, tensor_id, gi, 1u));
             ((uint16_t*)v)[i] = ref_sr_round(v1, ref_r16(seed, step, tensor_id, gi, 2u));
         }
+    }
+}
+
+/* Extension (the conclusion names FP8 as the next target of SR and says no more):
+ * one tensor of one step with the moments held in 8 bits, m as E4M3 and v as E5M2
+ * codes, one byte per element, each with a power-of-two scale per tensor:
+ *     m = decode(m8) * 2^-m_exp,      v = decode(v8) * 2^-v_exp           (exact)
+ *     y, m1, v1 by adamw_element as for every other strategy
+ *     m8 <- Q_SR,E4M3(m1 * 2^m_exp),  v8 <- Q_SR,E5M2(v1 * 2^v_exp)
+ * The two products are binary32 multiplications (exact unless the product leaves
+ * binary32's normal range).  Q_SR is ref_sr_round_fp8 with the element's 16-bit
+ * draws of output streams 1 and 2 -- the same draws the BF16 moments use -- placed
+ * in the top half of the 32-bit word: the rounding sees k = floor(2^16 frac) of the
+ * dropped fraction (bias below 2^-16 of one grid spacing).  The parameter is
+ * written back as in the BF16 strategies: SR with stream 0, or nearest with
+ * REF_FLAG_RNE_PARAMS.  |m_exp|, |v_exp| <= 100 keeps the decode exact. */
+void ref_sr_adamw_tensor_fp8m(uint16_t* p, const uint16_t* g, uint8_t* m8, uint8_t* v8,
+                              uint64_t numel, uint32_t tensor_id, uint64_t elem_offset,
+                              const ref_scalars_t* s, uint32_t step, uint64_t seed,
+                              uint32_t flags, int m_exp, int v_exp, int nthreads)
+{
+    const int rnep = (flags & REF_FLAG_RNE_PARAMS) != 0;
+    const float m_scale = (float)ldexp(1.0, m_exp), v_scale = (float)ldexp(1.0, v_exp);
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+    #pragma omp parallel for schedule(static)
+    for (int64_t ii = 0; ii < (int64_t)numel; ++ii) {
+        uint64_t i = (uint64_t)ii;
+        uint64_t gi = elem_offset + i;
+        float pi = bf16_bits_to_float(p[i]);
+        float gr = bf16_bits_to_float(g[i]);
+        float mi = (float)ldexp(ref_fp8_decode(m8[i], 0), -m_exp);
+        float vi = (float)ldexp(ref_fp8_decode(v8[i], 1), -v_exp);
+        float y, m1, v1;
+        adamw_element(s, flags, pi, gr, mi, vi, &y, &m1, &v1, NULL);
+        p[i] = rnep ? ref_rne_round(y) : ref_sr_round(y, ref_r16(seed, step, tensor_id, gi, 0u));
+        float ms = m1 * m_scale;
+        float vs = v1 * v_scale;
+        m8[i] = ref_sr_round_fp8(ms, ref_r16(seed, step, tensor_id, gi, 1u) << 16, 0);
+        v8[i] = ref_sr_round_fp8(vs, ref_r16(seed, step, tensor_id, gi, 2u) << 16, 1);
+    }
+}
+
+/* The unrounded results of the same step (for the checks of its arithmetic). */
+void ref_adamw_unrounded_fp8m(const uint16_t* p, const uint16_t* g, const uint8_t* m8, const uint8_t* v8,
+                              uint64_t numel, const ref_scalars_t* s, uint32_t flags, int m_exp, int v_exp,
+                              float* y, float* m1, float* v1)
+{
+    for (uint64_t i = 0; i < numel; ++i) {
+        float mi = (float)ldexp(ref_fp8_decode(m8[i], 0), -m_exp);
+        float vi = (float)ldexp(ref_fp8_decode(v8[i], 1), -v_exp);
+        adamw_element(s, flags, bf16_bits_to_float(p[i]), bf16_bits_to_float(g[i]), mi, vi,
+                      &y[i], &m1[i], &v1[i], NULL);
     }
 }
 
