@@ -31,6 +31,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published peak
 #   fp32_moments  2+2+4+4 read, 2+4+4 written                              12 + 10 = 22
 #   kahan         BF16 p,g,m,v,c read + p,m,v,c written                    10 + 8  = 18
 #   master        x32,g,m32,v32 read + x32,p16,m32,v32 written (O2 style)  14 + 14 = 28
+#   fp8_moments   2+2+1+1 read, 2+1+1 written (extension: E4M3 m, E5M2 v)   6 + 4  = 10
 MODES = {
     "sr": ((), False, None, 14),
     "rne_moments": (("SR_FLAG_RNE_MOMENTS",), False, None, 14),
@@ -38,7 +39,16 @@ MODES = {
     "fp32_moments": (("SR_FLAG_FP32_MOMENTS",), True, None, 22),
     "kahan": (("SR_FLAG_KAHAN",), False, "bf16", 18),
     "master": (("SR_FLAG_MASTER_FP32", "SR_FLAG_FP32_MOMENTS"), True, "f32", 28),
+    "fp8_moments": (("SR_FLAG_FP8_MOMENTS",), False, None, 10),
 }
+
+
+def fp8_scale_exponents(cfg):
+    """Power-of-two scales of the 8-bit moments for a workload: eight gradient standard deviations
+    (outliers included) map to the top of E4M3 for m, their square to the top of E5M2 for v."""
+    import math
+    g = 8.0 * max(cfg.grad_std, cfg.outlier_std if cfg.outlier_frac > 0 else 0.0)
+    return int(math.floor(math.log2(448.0 / g))), int(math.floor(math.log2(57344.0 / (g * g))))
 
 
 def algorithmic_bytes_per_element(mode, clip) -> int:
@@ -46,7 +56,7 @@ def algorithmic_bytes_per_element(mode, clip) -> int:
     return MODES[mode][3] + (2 if clip is not None else 0)
 
 
-def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags):
+def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags, fp8_exps=None):
     """Time the CPU oracle (as it stands) on a bounded window of the same workload and check the
     GPU against it on that window.  `state` holds flat device tensors p, g, m, v, aux (first
     tensor; aux may be None).  `flags`: the step's flag bits (same values on both sides)."""
@@ -60,6 +70,8 @@ def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags):
             s = t[lo:lo + n]
             return W.bf16_to_u16_numpy(s) if s.dtype == torch.bfloat16 else s.cpu().numpy().copy()
         d = dict(p=cp(p), g=cp(g), m=cp(m), v=cp(v), tensor_id=0, elem_offset=lo)
+        if fp8_exps is not None:
+            d["m_exp"], d["v_exp"] = fp8_exps
         if aux is not None:
             d["aux"] = cp(aux)
         return d
@@ -72,7 +84,10 @@ def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags):
     sub_ulp = None
     if aux is None:
         sc = ref.adamw_scalars(step=step_no, **cfg.hyper)
-        y, _, _ = ref.adamw_unrounded(w0["p"], w0["g"], w0["m"], w0["v"], sc, flags)
+        if fp8_exps is not None:
+            y, _, _ = ref.adamw_unrounded_fp8m(w0["p"], w0["g"], w0["m"], w0["v"], sc, *fp8_exps)
+        else:
+            y, _, _ = ref.adamw_unrounded(w0["p"], w0["g"], w0["m"], w0["v"], sc, flags)
         p32 = ref.bf16_bits_to_f32(w0["p"])
         sub_ulp = float(np.mean(np.abs(y.astype(np.float64) - p32) < np.spacing(np.abs(p32)).astype(np.float64) * 65536.0))
     t0 = time.perf_counter()
@@ -238,13 +253,19 @@ def main():
 
     params = W.make_params(cfg.shapes, dev, W.data_seed(cfg.index, 0), cfg.param_std)
     ms, vs = W.make_moments(cfg.shapes, dev, fp32_moments)
+    fp8_exps = None
+    if mode == "fp8_moments":
+        fp8_exps = fp8_scale_exponents(cfg)
+        ms = [torch.zeros(m.numel(), dtype=torch.uint8, device=dev) for m in ms]
+        vs = [torch.zeros(v.numel(), dtype=torch.uint8, device=dev) for v in vs]
     grads = [torch.empty_like(p) for p in params]
     aux = None
     if aux_kind == "f32":
         aux = [p.float() for p in params]                 # binary32 master parameters
     elif aux_kind == "bf16":
         aux = [torch.zeros_like(p) for p in params]       # Kahan compensation starts at zero
-    tl = B.TensorList(params, grads, ms, vs, fp32_moments, aux=aux)
+    tl = B.TensorList(params, grads, ms, vs, fp32_moments, aux=aux,
+                      fp8_exponents=None if fp8_exps is None else [fp8_exps] * len(params))
     norm = torch.zeros(1, dtype=torch.float32, device=dev)
     ws = torch.empty(max(tl.workspace_bytes(), 256), dtype=torch.uint8, device=dev)
     numel = tl.total_numel
@@ -272,7 +293,7 @@ def main():
     if not args.no_cpu_baseline:
         cpu, check = cpu_baseline(W, B, torch, cfg, (params[0], grads[0], ms[0], vs[0],
                                                      None if aux is None else aux[0]), t, cfg.seed,
-                                  args.cpu_seconds, flags)
+                                  args.cpu_seconds, flags, fp8_exps)
         if cfg.clip is not None:
             cpu["sample"] += " (oracle timed without the clip scale)"
 
@@ -284,7 +305,7 @@ def main():
         lo, n, w = check
         got_p = W.bf16_to_u16_numpy(params[0][lo:lo + n])
         bad = int((got_p != w["p"]).sum())
-        if fp32_moments:
+        if fp32_moments or fp8_exps is not None:
             bad += int((ms[0][lo:lo + n].cpu().numpy() != w["m"]).sum())
             bad += int((vs[0][lo:lo + n].cpu().numpy() != w["v"]).sum())
         else:
@@ -399,7 +420,8 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}", "numel": numel, "tensors": len(params),
-                   "mode": mode, "moments": "fp32" if fp32_moments else "bf16", "clip": cfg.clip,
+                   "mode": mode, "moments": "fp32" if fp32_moments else "e4m3/e5m2" if fp8_exps else "bf16",
+                   "fp8_scale_exponents": fp8_exps, "clip": cfg.clip,
                    "warm_steps": warm, "bytes_per_element": bpe, "hip_graph": bool(args.graph)},
         "hbm_GBps": bpe * numel / (ms_per_step * 1e-3) / 1e9,
         "pct_of_hbm_peak": 100.0 * bpe * numel / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,

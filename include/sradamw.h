@@ -82,6 +82,22 @@ extern "C" {
                                    7-8 as printed, m'/(1-beta1^t) and v'/(1-beta2^t) with
                                    1-beta^t formed in binary64 and rounded once, instead of
                                    multiplications by the rounded reciprocals              */
+/* A storage format of the moments (not one of the paper's strategies). */
+#define SR_FLAG_FP8_MOMENTS 128u /* extension (the paper's conclusion names FP8 as the next
+                                   target of SR and gives no design): m and v are 8-bit
+                                   codes, one byte per element, m in E4M3 and v in E5M2
+                                   (see sr_cast_f32_fp8 for the formats), each with a
+                                   power-of-two scale per tensor given in the tensor's
+                                   `reserved` field: m = decode(m8) 2^-m_exp,
+                                   v = decode(v8) 2^-v_exp, the update as for every other
+                                   strategy, m8 <- Q_SR(m' 2^m_exp), v8 <- Q_SR(v' 2^v_exp)
+                                   with the element's 16-bit draws of streams 1 and 2 in
+                                   the top half of the 32-bit random word of
+                                   sr_cast_f32_fp8's rule (the fraction is cut to 16
+                                   bits).  10 bytes moved per element instead of 14.
+                                   Combines with SR_FLAG_RNE_PARAMS, SR_FLAG_EPS_IN_ROOT
+                                   and SR_FLAG_DIV_BIAS only.  NaN codes stay NaN codes;
+                                   NaN signs and payloads are not specified.            */
 
 /* One tensor of the multi-tensor list. */
 typedef struct sr_tensor {
@@ -96,7 +112,9 @@ typedef struct sr_tensor {
     uint64_t    elem_offset; /* index of element 0 in the RNG counter; 0 for a whole
                                 tensor, the shard's start for a slice of a larger one     */
     uint32_t    tensor_id;   /* RNG counter word; keep it stable across steps and ranks   */
-    uint32_t    reserved;    /* must be 0                                                 */
+    uint32_t    reserved;    /* must be 0; with SR_FLAG_FP8_MOMENTS: m_exp in bits 0-7 and
+                                v_exp in bits 8-15, two's complement, each in [-100, 100],
+                                bits 16-31 zero                                           */
 } sr_tensor_t;
 
 /* Hyper-parameters of Algorithm 1: alpha_t, beta_1, beta_2, epsilon, lambda. */

@@ -6,7 +6,7 @@ library is missing or a call fails, an exception is raised.
 """
 import ctypes as C
 import os
-from typing import List, Optional, Sequence
+from typing import List, Optional, Sequence, Tuple
 
 import torch  # imported before the library so that one HIP runtime serves both
 
@@ -22,6 +22,7 @@ SR_FLAG_MASTER_FP32 = 8
 SR_FLAG_KAHAN = 16
 SR_FLAG_EPS_IN_ROOT = 32
 SR_FLAG_DIV_BIAS = 64
+SR_FLAG_FP8_MOMENTS = 128
 
 SR_ACC_RNE = 1
 SR_ACC_FIRST = 2
@@ -131,14 +132,22 @@ class TensorList:
                  ms: Sequence[torch.Tensor], vs: Sequence[torch.Tensor], fp32_moments: bool = False,
                  tensor_ids: Optional[Sequence[int]] = None,
                  elem_offsets: Optional[Sequence[int]] = None,
-                 aux: Optional[Sequence[torch.Tensor]] = None):
+                 aux: Optional[Sequence[torch.Tensor]] = None,
+                 fp8_exponents: Optional[Sequence[Tuple[int, int]]] = None):
         """aux: per-tensor auxiliary arrays for the comparison strategies -- float32 master
-        parameters (SR_FLAG_MASTER_FP32) or bfloat16 Kahan compensation (SR_FLAG_KAHAN)."""
+        parameters (SR_FLAG_MASTER_FP32) or bfloat16 Kahan compensation (SR_FLAG_KAHAN).
+        fp8_exponents: per-tensor (m_exp, v_exp) for SR_FLAG_FP8_MOMENTS; ms and vs are then one
+        byte per element (uint8 or a torch float8 dtype)."""
         n = len(params)
         if not (len(grads) == len(ms) == len(vs) == n):
             raise ValueError("params, grads, ms, vs must have the same length")
         mdt = torch.float32 if fp32_moments else torch.bfloat16
+        if fp8_exponents is not None:
+            if fp32_moments or len(fp8_exponents) != n:
+                raise ValueError("fp8_exponents: one (m_exp, v_exp) per tensor, not with fp32_moments")
+            mdt = None                                        # any one-byte dtype
         self.fp32_moments = fp32_moments
+        self.fp8_moments = fp8_exponents is not None
         self.n = n
         self.array = (SrTensor * max(n, 1))()
         self.keep = (list(params), list(grads), list(ms), list(vs), None if aux is None else list(aux))
@@ -150,8 +159,10 @@ class TensorList:
             p, g, m, v = params[i], grads[i], ms[i], vs[i]
             _check_dev(p, torch.bfloat16, f"params[{i}]")
             _check_dev(g, torch.bfloat16, f"grads[{i}]")
-            _check_dev(m, mdt, f"ms[{i}]")
-            _check_dev(v, mdt, f"vs[{i}]")
+            for name, x in (("ms", m), ("vs", v)):
+                if mdt is None and x.element_size() != 1:
+                    raise ValueError(f"{name}[{i}] must hold one byte per element")
+                _check_dev(x, x.dtype if mdt is None else mdt, f"{name}[{i}]")
             if not (p.numel() == g.numel() == m.numel() == v.numel()):
                 raise ValueError(f"tensor {i}: p, g, m, v differ in size")
             e = self.array[i]
@@ -169,6 +180,11 @@ class TensorList:
             e.elem_offset = 0 if elem_offsets is None else int(elem_offsets[i])
             e.tensor_id = i if tensor_ids is None else int(tensor_ids[i])
             e.reserved = 0
+            if fp8_exponents is not None:
+                m_exp, v_exp = (int(x) for x in fp8_exponents[i])
+                if not (-100 <= m_exp <= 100 and -100 <= v_exp <= 100):
+                    raise ValueError("fp8 scale exponents must lie in [-100, 100]")
+                e.reserved = (m_exp & 0xFF) | ((v_exp & 0xFF) << 8)
             self.total_numel += p.numel()
 
     def workspace_bytes(self) -> int:
@@ -235,6 +251,8 @@ def sr_adamw_step(tl: TensorList, hyper: dict, step: int, seed: int, flags: int 
     grad_global_norm, or None for no clipping."""
     if bool(flags & SR_FLAG_FP32_MOMENTS) != tl.fp32_moments:
         raise ValueError("SR_FLAG_FP32_MOMENTS does not match the moment dtype of the list")
+    if bool(flags & SR_FLAG_FP8_MOMENTS) != tl.fp8_moments:
+        raise ValueError("SR_FLAG_FP8_MOMENTS needs a list built with fp8_exponents (and only such a list)")
     if (flags & SR_FLAG_MASTER_FP32) and tl.n and tl.aux_dtype != torch.float32:
         raise ValueError("SR_FLAG_MASTER_FP32 needs float32 aux tensors in the list")
     if (flags & SR_FLAG_KAHAN) and tl.n and tl.aux_dtype != torch.bfloat16:

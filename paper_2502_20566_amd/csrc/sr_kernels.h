@@ -58,7 +58,9 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 typedef v4u v4u_a2 __attribute__((aligned(2)));
 typedef v4u v4u_a4 __attribute__((aligned(4)));
 
-enum : uint32_t { DESC_VEC = 1u };     // elem_offset % 8 == 0: blocks of the RNG counter start at element 0
+// DESC_VEC: elem_offset % 8 == 0, blocks of the RNG counter start at element 0.  With 8-bit moments
+// bits 8-15 and 16-23 hold the scale exponents of m and v (two's complement, |e| <= 100).
+enum : uint32_t { DESC_VEC = 1u, DESC_MEXP_SHIFT = 8u, DESC_VEXP_SHIFT = 16u };
 
 struct TensorDesc {
     uint16_t* p;
@@ -311,6 +313,137 @@ __device__ __forceinline__ uint32_t find_tensor(const uint32_t* start, uint32_t 
     return lo;
 }
 
+// ---------------------------------------------------------------------- 8-bit formats
+
+// FMT 0: E4M3, 1: E5M2 (the OCP 8-bit formats).
+template <int FMT> struct Fp8 {
+    static constexpr int mb = FMT == 0 ? 3 : 2;
+    static constexpr int ef = FMT == 0 ? 121 : 113;              // exponent field of the smallest normal
+    static constexpr uint32_t top = FMT == 0 ? 0x7Eu : 0x7Cu;
+    static constexpr uint32_t efmax = FMT == 0 ? 127u + 8u : 127u + 15u;   // binade of the largest finite value
+};
+
+// One element on the integer path: every range and NaN rule applied.
+template <int FMT>
+__device__ __forceinline__ uint32_t fp8_code(uint32_t bits, uint32_t r32)
+{
+    using P = Fp8<FMT>;
+    return fp8_sign(bits) | fp8_finish<P::top>(bits, sr_fp8_magnitude<P::mb, P::ef>(bits, r32));
+}
+
+// Four elements into one word.  `ranged`: some value of the wave lies in the format's top binade
+// or above, is infinite or a NaN (wave-uniform): the integer path with the range rules; otherwise
+// the chip's conversion instruction, which computes the same function of (value, random word)
+// below the top binade: it adds the word's top 23 - mb bits to the dropped fraction cut to as
+// many bits and keeps the carry, subnormal results included (checked against the by-value
+// oracle on every binary32 encoding).
+template <int FMT>
+__device__ __forceinline__ uint32_t fp8_encode4(const uint32_t (&b)[4], const uint32_t (&r)[4], bool ranged)
+{
+    if (ranged)
+        return fp8_code<FMT>(b[0], r[0]) | (fp8_code<FMT>(b[1], r[1]) << 8) |
+               (fp8_code<FMT>(b[2], r[2]) << 16) | (fp8_code<FMT>(b[3], r[3]) << 24);
+    int w = 0;
+    if (FMT == 0) {
+        w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(b[0]), (int)r[0], w, 0);
+        w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(b[1]), (int)r[1], w, 1);
+        w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(b[2]), (int)r[2], w, 2);
+        w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(b[3]), (int)r[3], w, 3);
+    } else {
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(__uint_as_float(b[0]), (int)r[0], w, 0);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(__uint_as_float(b[1]), (int)r[1], w, 1);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(__uint_as_float(b[2]), (int)r[2], w, 2);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(__uint_as_float(b[3]), (int)r[3], w, 3);
+    }
+    return (uint32_t)w;
+}
+
+// The largest magnitude among four encodings, as an encoding (NaNs compare above everything).
+__device__ __forceinline__ uint32_t max_magnitude4(const uint32_t (&b)[4])
+{
+    return max(max(b[0] & 0x7FFFFFFFu, b[1] & 0x7FFFFFFFu), max(b[2] & 0x7FFFFFFFu, b[3] & 0x7FFFFFFFu));
+}
+
+// Eight codes (two words) to binary32, times `inv_scale` (a power of two: exact).  The chip's
+// conversion decodes every code of both formats as the OCP tables say (checked on all 256);
+// NaN codes give a quiet NaN.
+template <int FMT>
+__device__ __forceinline__ void fp8_decode8(v2u codes, float inv_scale, float (&out)[8])
+{
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    f2 q[4];
+    if (FMT == 0) {
+        q[0] = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes.x, false); q[1] = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes.x, true);
+        q[2] = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes.y, false); q[3] = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes.y, true);
+    } else {
+        q[0] = __builtin_amdgcn_cvt_pk_f32_bf8((int)codes.x, false); q[1] = __builtin_amdgcn_cvt_pk_f32_bf8((int)codes.x, true);
+        q[2] = __builtin_amdgcn_cvt_pk_f32_bf8((int)codes.y, false); q[3] = __builtin_amdgcn_cvt_pk_f32_bf8((int)codes.y, true);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { out[2 * j] = q[j].x * inv_scale; out[2 * j + 1] = q[j].y * inv_scale; }
+}
+
+// Eight codes starting at element l0 of `base`, element-wise, zeros outside [0, numel).
+__device__ __forceinline__ v2u load8_u8(const uint8_t* base, int64_t l0, uint64_t numel)
+{
+    uint32_t w[2] = {0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t l = l0 + j;
+        const uint32_t c = (l >= 0 && (uint64_t)l < numel) ? base[l] : 0u;
+        w[j >> 2] |= c << (8 * (j & 3));
+    }
+    v2u r; r.x = w[0]; r.y = w[1];
+    return r;
+}
+__device__ __forceinline__ void store8_u8(uint8_t* base, int64_t l0, uint64_t numel, v2u codes)
+{
+    const uint32_t w[2] = {codes.x, codes.y};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t l = l0 + j;
+        if (l >= 0 && (uint64_t)l < numel) base[l] = (uint8_t)(w[j >> 2] >> (8 * (j & 3)));
+    }
+}
+
+// The write-back of a lane's eight new moments as 8-bit codes: m * m_scale to E4M3 and
+// v * v_scale to E5M2, each with the element's 16-bit draw of its stream (mw, vw: two draws per
+// word, low half for the even element, as for BF16 moments) in the top half of the random word.
+// `nan`: some value of the wave may be a NaN (wave-uniform; the maxima below skip NaNs).
+__device__ __forceinline__ void fp8_moments_out(const float (&m)[8], const float (&v)[8], float m_scale, float v_scale,
+                                                const uint32_t* mw, const uint32_t* vw, bool nan, v2u& mo, v2u& vo)
+{
+    float ms[8], vs[8];
+    uint32_t mr[8], vr[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        ms[j] = m[j] * m_scale;
+        vs[j] = v[j] * v_scale;
+        mr[j] = (j & 1) ? (mw[j >> 1] & 0xFFFF0000u) : (mw[j >> 1] << 16);
+        vr[j] = (j & 1) ? (vw[j >> 1] & 0xFFFF0000u) : (vw[j >> 1] << 16);
+    }
+    // the range rules apply from the formats' top binades upwards (2^8 for E4M3, 2^15 for E5M2;
+    // a negative v cannot arise from the update but may be loaded: its magnitude counts)
+    float mmax = 0.0f, vmax = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        mmax = __builtin_fmaxf(mmax, __builtin_fabsf(ms[j]));
+        vmax = __builtin_fmaxf(vmax, __builtin_fabsf(vs[j]));
+    }
+    const bool ranged = nan || __builtin_amdgcn_ballot_w64(mmax >= 256.0f || vmax >= 32768.0f) != 0;   // wave-uniform
+    const uint32_t ml[4] = {__float_as_uint(ms[0]), __float_as_uint(ms[1]), __float_as_uint(ms[2]), __float_as_uint(ms[3])};
+    const uint32_t mh[4] = {__float_as_uint(ms[4]), __float_as_uint(ms[5]), __float_as_uint(ms[6]), __float_as_uint(ms[7])};
+    const uint32_t vl[4] = {__float_as_uint(vs[0]), __float_as_uint(vs[1]), __float_as_uint(vs[2]), __float_as_uint(vs[3])};
+    const uint32_t vh[4] = {__float_as_uint(vs[4]), __float_as_uint(vs[5]), __float_as_uint(vs[6]), __float_as_uint(vs[7])};
+    const uint32_t mrl[4] = {mr[0], mr[1], mr[2], mr[3]}, mrh[4] = {mr[4], mr[5], mr[6], mr[7]};
+    const uint32_t vrl[4] = {vr[0], vr[1], vr[2], vr[3]}, vrh[4] = {vr[4], vr[5], vr[6], vr[7]};
+    mo.x = fp8_encode4<0>(ml, mrl, ranged); mo.y = fp8_encode4<0>(mh, mrh, ranged);
+    vo.x = fp8_encode4<1>(vl, vrl, ranged); vo.y = fp8_encode4<1>(vh, vrh, ranged);
+}
+
+// The power of two 2^e as a binary32 value (|e| <= 100).
+__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((uint32_t)(127 + e) << 23); }
+
 // ---------------------------------------------------------------------------- fused update
 
 // Variant of the step, from the ABI's flag bits (same values as SR_FLAG_* in sradamw.h).
@@ -319,9 +452,10 @@ struct Mode {
     static constexpr bool fp32m  = (F & 1u) != 0;                 // binary32 moments, stored unrounded
     static constexpr bool master = (F & 8u) != 0;                 // aux = binary32 master parameters
     static constexpr bool kahan  = (F & 16u) != 0;                // aux = BF16 Kahan compensation
-    static constexpr bool rnem   = !fp32m && (kahan || (F & 2u)); // BF16 moments rounded to nearest
+    static constexpr bool fp8m   = (F & 128u) != 0;               // 8-bit moments: m E4M3, v E5M2, scaled
+    static constexpr bool rnem   = !fp32m && !fp8m && (kahan || (F & 2u)); // BF16 moments rounded to nearest
     static constexpr bool rnep   = master || kahan || (F & 4u);   // BF16 parameter rounded to nearest
-    static constexpr bool srm    = !fp32m && !rnem;               // BF16 moments stochastically rounded
+    static constexpr bool srm    = !fp32m && !fp8m && !rnem;      // BF16 moments stochastically rounded
     static constexpr bool aux    = master || kahan;
     static constexpr bool half   = fp32m;                         // fast path: a lane owns half a block
 };
@@ -367,11 +501,12 @@ struct LaneRegs {
     uint32_t po[N / 2], mo[N / 2], vo[N / 2], ao[N / 2];   // out: packed BF16 pairs (p; BF16 m, v; Kahan c)
 };
 
-// The update of a lane's N elements and the write-back roundings.  pw, mw, vw: the random words of
+// The update of a lane's N elements and the write-back roundings (8-bit moments are left unrounded
+// in L.m, L.v for fp8_moments_out).  pw, mw, vw: the random words of
 // the lane's elements for the three output streams (16 bits per element; only read where the mode
 // rounds stochastically).
 template <uint32_t F, bool CLIP, bool VAR, int N>
-__device__ __forceinline__ void update_lane(LaneRegs<N>& L, const StepScalars& S, float c,
+__device__ __forceinline__ bool update_lane(LaneRegs<N>& L, const StepScalars& S, float c,
                                             const uint32_t* pw, const uint32_t* mw, const uint32_t* vw)
 {
     using M = Mode<F>;
@@ -384,7 +519,7 @@ __device__ __forceinline__ void update_lane(LaneRegs<N>& L, const StepScalars& S
     // folded over the wave so that the guarded roundings are a branch no wave takes in practice
     // (as per-lane selects they were 100 of the 680 vector instructions of a wave).
     bool nan = false;
-    if (!M::rnep || M::srm) {
+    if (!M::rnep || M::srm || M::fp8m) {
         bool lane_nan = false;
 #pragma unroll
         for (int j = 0; j < N; ++j) lane_nan |= (y[j] != y[j]);
@@ -446,6 +581,7 @@ __device__ __forceinline__ void update_lane(LaneRegs<N>& L, const StepScalars& S
             }
         }
     }
+    return nan;      // wave-uniform: some lane's new parameter (hence possibly a new moment) is a NaN
 }
 
 __device__ __forceinline__ void unpack4(v2u x, float (&out)[4])
@@ -496,7 +632,7 @@ __device__ __forceinline__ void block_draws(const TensorDesc& T, const StepScala
     using M = Mode<F>;
     rp = {}; rm = {}; rv = {};
     if (!M::rnep) rp = block_bits(gblk, STREAM_P, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
-    if (M::srm) {
+    if (M::srm || M::fp8m) {
         rm = block_bits(gblk, STREAM_M, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
         rv = block_bits(gblk, STREAM_V, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
     }
@@ -514,15 +650,21 @@ __device__ __forceinline__ void inner_block(const TensorDesc& T, const StepScala
     const uint32_t o16 = lane * 16u, o32 = lane * 32u;          // byte offsets in BF16 / binary32 arrays
     const rsrc_t rp = chunk_rsrc<uint16_t>(T.p, lc0, span * 8u);
     const rsrc_t rg = chunk_rsrc<uint16_t>(T.g, lc0, span * 8u);
-    const rsrc_t rm = M::fp32m ? chunk_rsrc<float>(T.m, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.m, lc0, span * 8u);
-    const rsrc_t rv = M::fp32m ? chunk_rsrc<float>(T.v, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.v, lc0, span * 8u);
+    const rsrc_t rm = M::fp32m ? chunk_rsrc<float>(T.m, lc0, span * 8u)
+                    : M::fp8m  ? chunk_rsrc<uint8_t>(T.m, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.m, lc0, span * 8u);
+    const rsrc_t rv = M::fp32m ? chunk_rsrc<float>(T.v, lc0, span * 8u)
+                    : M::fp8m  ? chunk_rsrc<uint8_t>(T.v, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.v, lc0, span * 8u);
     const rsrc_t ra = M::master ? chunk_rsrc<float>(T.aux, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.aux, lc0, span * 8u);
     v4u pq = {}, aq = {}, mq0 = {}, mq1 = {}, vq0 = {}, vq1 = {}, xq0 = {}, xq1 = {};
+    v2u m8 = {}, v8 = {};
     if (!M::master) pq = buf_load16<NT>(rp, o16);
     const v4u gq = buf_load16<NT>(rg, o16);
     if (M::fp32m) {
         mq0 = buf_load16<NT>(rm, o32); mq1 = buf_load16<NT>(rm, o32 + 16u);
         vq0 = buf_load16<NT>(rv, o32); vq1 = buf_load16<NT>(rv, o32 + 16u);
+    } else if (M::fp8m) {
+        m8 = buf_load8<NT>(rm, lane * 8u);
+        v8 = buf_load8<NT>(rv, lane * 8u);
     } else {
         mq0 = buf_load16<NT>(rm, o16);
         vq0 = buf_load16<NT>(rv, o16);
@@ -536,15 +678,22 @@ __device__ __forceinline__ void inner_block(const TensorDesc& T, const StepScala
     LaneRegs<8> L;
     if (!M::master) unpack8(pq, L.p);
     unpack8(gq, L.g);
-    if (M::fp32m) { floats8(mq0, mq1, L.m); floats8(vq0, vq1, L.v); }
-    else          { unpack8(mq0, L.m); unpack8(vq0, L.v); }
+    const int m_exp = (int)(int8_t)(T.flags >> DESC_MEXP_SHIFT), v_exp = (int)(int8_t)(T.flags >> DESC_VEXP_SHIFT);
+    if (M::fp32m)     { floats8(mq0, mq1, L.m); floats8(vq0, vq1, L.v); }
+    else if (M::fp8m) { fp8_decode8<0>(m8, pow2f(-m_exp), L.m); fp8_decode8<1>(v8, pow2f(-v_exp), L.v); }
+    else              { unpack8(mq0, L.m); unpack8(vq0, L.v); }
     if (M::master) floats8(xq0, xq1, L.aux);
     if (M::kahan) unpack8(aq, L.aux);
-    update_lane<F, CLIP, VAR, 8>(L, S, c, dp.w, dm.w, dv.w);
+    const bool nan = update_lane<F, CLIP, VAR, 8>(L, S, c, dp.w, dm.w, dv.w);
     buf_store16<NT>(rp, o16, words4(L.po));
     if (M::fp32m) {
         buf_store16<NT>(rm, o32, bits4lo(L.m)); buf_store16<NT>(rm, o32 + 16u, bits4hi(L.m));
         buf_store16<NT>(rv, o32, bits4lo(L.v)); buf_store16<NT>(rv, o32 + 16u, bits4hi(L.v));
+    } else if (M::fp8m) {
+        v2u mo, vo;
+        fp8_moments_out(L.m, L.v, pow2f(m_exp), pow2f(v_exp), dm.w, dv.w, nan, mo, vo);
+        buf_store8<NT>(rm, lane * 8u, mo);
+        buf_store8<NT>(rv, lane * 8u, vo);
     } else {
         buf_store16<NT>(rm, o16, words4(L.mo));
         buf_store16<NT>(rv, o16, words4(L.vo));
@@ -565,9 +714,13 @@ __device__ __forceinline__ void edge_block(const TensorDesc& T, const StepScalar
     LaneRegs<8> L;
     if (!M::master) unpack8(load8_bf16<false>(T.p, l0, numel, false), L.p);
     unpack8(load8_bf16<false>(T.g, l0, numel, false), L.g);
+    const int m_exp = (int)(int8_t)(T.flags >> DESC_MEXP_SHIFT), v_exp = (int)(int8_t)(T.flags >> DESC_VEXP_SHIFT);
     if (M::fp32m) {
         load8_f32<false>(static_cast<const float*>(T.m), l0, numel, false, L.m);
         load8_f32<false>(static_cast<const float*>(T.v), l0, numel, false, L.v);
+    } else if (M::fp8m) {
+        fp8_decode8<0>(load8_u8(static_cast<const uint8_t*>(T.m), l0, numel), pow2f(-m_exp), L.m);
+        fp8_decode8<1>(load8_u8(static_cast<const uint8_t*>(T.v), l0, numel), pow2f(-v_exp), L.v);
     } else {
         unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.m), l0, numel, false), L.m);
         unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.v), l0, numel, false), L.v);
@@ -576,11 +729,16 @@ __device__ __forceinline__ void edge_block(const TensorDesc& T, const StepScalar
     if (M::kahan) unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.aux), l0, numel, false), L.aux);
     u32x4 dp, dm, dv;
     block_draws<F>(T, S, gblk, dp, dm, dv);
-    update_lane<F, CLIP, VAR, 8>(L, S, c, dp.w, dm.w, dv.w);
+    const bool nan = update_lane<F, CLIP, VAR, 8>(L, S, c, dp.w, dm.w, dv.w);
     store8_bf16<false>(T.p, l0, numel, false, words4(L.po));
     if (M::fp32m) {
         store8_f32<false>(static_cast<float*>(T.m), l0, numel, false, L.m);
         store8_f32<false>(static_cast<float*>(T.v), l0, numel, false, L.v);
+    } else if (M::fp8m) {
+        v2u mo, vo;
+        fp8_moments_out(L.m, L.v, pow2f(m_exp), pow2f(v_exp), dm.w, dv.w, nan, mo, vo);
+        store8_u8(static_cast<uint8_t*>(T.m), l0, numel, mo);
+        store8_u8(static_cast<uint8_t*>(T.v), l0, numel, vo);
     } else {
         store8_bf16<false>(static_cast<uint16_t*>(T.m), l0, numel, false, words4(L.mo));
         store8_bf16<false>(static_cast<uint16_t*>(T.v), l0, numel, false, words4(L.vo));
@@ -773,20 +931,6 @@ __global__ __launch_bounds__(kThreads) void cast_kernel(const float* __restrict_
 // 4-byte store; every access of the wave is contiguous.  FMT 0: E4M3, 1: E5M2.  The range and NaN
 // rules only matter from the binade that holds the format's largest finite value upwards: they are
 // applied in a branch taken when some lane of the wave holds such a value.
-template <int FMT> struct Fp8 {
-    static constexpr int mb = FMT == 0 ? 3 : 2;
-    static constexpr int ef = FMT == 0 ? 121 : 113;              // exponent field of the smallest normal
-    static constexpr uint32_t top = FMT == 0 ? 0x7Eu : 0x7Cu;
-    static constexpr uint32_t efmax = FMT == 0 ? 127u + 8u : 127u + 15u;   // binade of the largest finite value
-};
-
-template <int FMT>
-__device__ __forceinline__ uint32_t fp8_code(uint32_t bits, uint32_t r32)
-{
-    using P = Fp8<FMT>;
-    return fp8_sign(bits) | fp8_finish<P::top>(bits, sr_fp8_magnitude<P::mb, P::ef>(bits, r32));
-}
-
 constexpr int kFp8Iters = SR_TUNE_FP8_ITERS;     // groups of 4 elements per lane
 constexpr int kFp8ChunkElems = kThreads * 4 * kFp8Iters;
 
@@ -812,33 +956,11 @@ __global__ __launch_bounds__(kThreads) void cast_fp8_kernel(const float* __restr
                                           seed_lo, seed_hi);
             const v4u x = xs[it];
             const uint32_t b[4] = {x.x, x.y, x.z, x.w};
-            // the largest of the four magnitudes, as encodings (NaNs compare above everything)
-            const uint32_t big = max(max(x.x & 0x7FFFFFFFu, x.y & 0x7FFFFFFFu), max(x.z & 0x7FFFFFFFu, x.w & 0x7FFFFFFFu));
-            uint32_t o;
-            if (SR_TUNE_FP8_NOHW || __builtin_amdgcn_ballot_w64(big >= (P::efmax << 23)) != 0) {
-                // some lane holds a value in the format's top binade or above (or an infinity or a
-                // NaN): the range rules apply, integer path for the whole wave
-                o = fp8_code<FMT>(b[0], r.w[0]) | (fp8_code<FMT>(b[1], r.w[1]) << 8) |
-                    (fp8_code<FMT>(b[2], r.w[2]) << 16) | (fp8_code<FMT>(b[3], r.w[3]) << 24);
-            } else {
-                // below the top binade the conversion instruction of the chip computes the same
-                // function of (value, random word): it adds the word's top 23 - mb bits to the
-                // dropped fraction cut to as many bits and keeps the carry, subnormal results
-                // included (checked against the by-value oracle on every binary32 encoding)
-                int w = 0;
-                if (FMT == 0) {
-                    w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(x.x), (int)r.w[0], w, 0);
-                    w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(x.y), (int)r.w[1], w, 1);
-                    w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(x.z), (int)r.w[2], w, 2);
-                    w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(x.w), (int)r.w[3], w, 3);
-                } else {
-                    w = __builtin_amdgcn_cvt_sr_bf8_f32(__uint_as_float(x.x), (int)r.w[0], w, 0);
-                    w = __builtin_amdgcn_cvt_sr_bf8_f32(__uint_as_float(x.y), (int)r.w[1], w, 1);
-                    w = __builtin_amdgcn_cvt_sr_bf8_f32(__uint_as_float(x.z), (int)r.w[2], w, 2);
-                    w = __builtin_amdgcn_cvt_sr_bf8_f32(__uint_as_float(x.w), (int)r.w[3], w, 3);
-                }
-                o = (uint32_t)w;
-            }
+            // the range rules apply when some lane holds a value in the format's top binade or
+            // above (or an infinity or a NaN): integer path for the whole wave
+            const bool ranged = SR_TUNE_FP8_NOHW ||
+                                __builtin_amdgcn_ballot_w64(max_magnitude4(b) >= (P::efmax << 23)) != 0;
+            const uint32_t o = fp8_encode4<FMT>(b, r.w, ranged);
             __builtin_amdgcn_raw_buffer_store_b32(o, rd, (int)(row * 4u), 0, NT ? 2 : 0);
         }
         return;

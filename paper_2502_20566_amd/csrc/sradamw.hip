@@ -116,6 +116,8 @@ hipError_t launch_adamw_variant(uint32_t flags, bool clip, const AdamwBatch& b, 
         case SR_FLAG_FP32_MOMENTS | SR_FLAG_RNE_PARAMS:       return launch_adamw<SR_FLAG_FP32_MOMENTS | SR_FLAG_RNE_PARAMS>(clip, b, n, s);
         case SR_FLAG_FP32_MOMENTS | SR_FLAG_MASTER_FP32:      return launch_adamw<SR_FLAG_FP32_MOMENTS | SR_FLAG_MASTER_FP32>(clip, b, n, s);
         case SR_FLAG_KAHAN:                                   return launch_adamw<SR_FLAG_KAHAN>(clip, b, n, s);
+        case SR_FLAG_FP8_MOMENTS:                             return launch_adamw<SR_FLAG_FP8_MOMENTS>(clip, b, n, s);
+        case SR_FLAG_FP8_MOMENTS | SR_FLAG_RNE_PARAMS:        return launch_adamw<SR_FLAG_FP8_MOMENTS | SR_FLAG_RNE_PARAMS>(clip, b, n, s);
         default:                                              return hipErrorInvalidValue;   // unreachable after validation
     }
 }
@@ -391,7 +393,7 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     if (n_tensors && !tensors) return SR_ERR_NULL;
     if (step == 0) return SR_ERR_ARG;
     if (flags & ~(SR_FLAG_FP32_MOMENTS | SR_FLAG_RNE_MOMENTS | SR_FLAG_RNE_PARAMS | SR_FLAG_MASTER_FP32 |
-                  SR_FLAG_KAHAN | SR_FLAG_EPS_IN_ROOT | SR_FLAG_DIV_BIAS))
+                  SR_FLAG_KAHAN | SR_FLAG_EPS_IN_ROOT | SR_FLAG_DIV_BIAS | SR_FLAG_FP8_MOMENTS))
         return SR_ERR_ARG;
     // variants of the arithmetic combine with any strategy and do not select a kernel
     uint32_t variant = 0;
@@ -400,6 +402,7 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     flags &= ~(SR_FLAG_EPS_IN_ROOT | SR_FLAG_DIV_BIAS);
     if ((flags & SR_FLAG_MASTER_FP32) && flags != (SR_FLAG_MASTER_FP32 | SR_FLAG_FP32_MOMENTS)) return SR_ERR_ARG;
     if ((flags & SR_FLAG_KAHAN) && flags != SR_FLAG_KAHAN) return SR_ERR_ARG;
+    if ((flags & SR_FLAG_FP8_MOMENTS) && (flags & ~(SR_FLAG_FP8_MOMENTS | SR_FLAG_RNE_PARAMS))) return SR_ERR_ARG;
     const sr_hyper_t h = *hyper;
     if (!std::isfinite(h.lr) || !std::isfinite(h.eps) || !std::isfinite(h.weight_decay) ||
         !std::isfinite(h.beta1) || !std::isfinite(h.beta2)) return SR_ERR_ARG;
@@ -414,12 +417,19 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     if (fp32m) flags &= ~SR_FLAG_RNE_MOMENTS;                      // no BF16 moment write-back to round
     const bool master = (flags & SR_FLAG_MASTER_FP32) != 0;
     const bool kahan = (flags & SR_FLAG_KAHAN) != 0;
-    const uintptr_t moment_align = fp32m ? 4 : 2;
+    const bool fp8m = (flags & SR_FLAG_FP8_MOMENTS) != 0;
+    const uintptr_t moment_align = fp32m ? 4 : fp8m ? 1 : 2;
 
     // Validate the whole list before anything is enqueued.
     for (uint32_t i = 0; i < n_tensors; ++i) {
         const sr_tensor_t& t = tensors[i];
-        if (t.reserved != 0) return SR_ERR_ARG;
+        if (fp8m) {
+            // the scale exponents of m (bits 0-7) and v (bits 8-15), two's complement
+            const int m_exp = (int8_t)(t.reserved & 0xFFu), v_exp = (int8_t)((t.reserved >> 8) & 0xFFu);
+            if ((t.reserved >> 16) != 0 || m_exp < -100 || m_exp > 100 || v_exp < -100 || v_exp > 100) return SR_ERR_ARG;
+        } else if (t.reserved != 0) {
+            return SR_ERR_ARG;
+        }
         if (t.numel == 0) continue;
         if (!t.p || !t.g || !t.m || !t.v) return SR_ERR_NULL;
         if ((master || kahan) && !t.aux) return SR_ERR_NULL;
@@ -462,7 +472,7 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     };
     const uint32_t mg = max_grid(kThreads);
     const uint64_t per_chunk = fp32m ? kBlocksPerChunkFp32 : kBlocksPerChunkBf16;
-    const uint64_t moment_size = fp32m ? 4 : 2, aux_size = master ? 4 : 2;
+    const uint64_t moment_size = fp32m ? 4 : fp8m ? 1 : 2, aux_size = master ? 4 : 2;
     for (uint32_t i = 0; i < n_tensors; ++i) {
         const sr_tensor_t& t = tensors[i];
         if (t.numel == 0) continue;
@@ -483,7 +493,7 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
             d.numel = numel;
             d.elem_offset = goff;
             d.tensor_id = t.tensor_id;
-            d.flags = (goff & 7u) == 0 ? DESC_VEC : 0u;
+            d.flags = ((goff & 7u) == 0 ? DESC_VEC : 0u) | (fp8m ? (t.reserved & 0xFFFFu) << DESC_MEXP_SHIFT : 0u);
             batch.chunk_start[nb] = chunks_in_batch;
             chunks_in_batch += nch;
             ++nb;

@@ -14,7 +14,7 @@ rounding strategy, the clip and the seed belong to the optimizer.  All replicas 
 job must use the same `seed` and the same parameter order (Algorithm 1, lines 9 and 11: shared
 randomness): the k-th parameter over all groups gets RNG tensor id k.
 """
-from typing import List, Optional, Sequence
+from typing import List, Optional, Sequence, Tuple
 
 import torch
 
@@ -27,15 +27,23 @@ _STRATEGIES = {
     "fp32_moments": B.SR_FLAG_FP32_MOMENTS,
     "kahan": B.SR_FLAG_KAHAN,
     "master": B.SR_FLAG_MASTER_FP32 | B.SR_FLAG_FP32_MOMENTS,
+    "fp8_moments": B.SR_FLAG_FP8_MOMENTS,                         # extension: m as E4M3, v as E5M2 codes
 }
 
 
 class SRAdamW(torch.optim.Optimizer):
     def __init__(self, params, lr: float = 1e-3, betas=(0.9, 0.95), eps: float = 1e-8,
                  weight_decay: float = 0.1, max_norm: Optional[float] = None, seed: int = 0,
-                 strategy: str = "sr", eps_in_root: bool = False, divide_bias_correction: bool = False):
+                 strategy: str = "sr", eps_in_root: bool = False, divide_bias_correction: bool = False,
+                 fp8_exponents: Optional[Tuple[int, int]] = None):
+        """fp8_exponents = (m_exp, v_exp): with strategy "fp8_moments" the moments are stored as
+        Q_SR(m 2^m_exp) in E4M3 and Q_SR(v 2^v_exp) in E5M2 (one byte each); choose the exponents so
+        that the largest |m| 2^m_exp stays below 448 and the largest v 2^v_exp below 57344 (larger
+        values saturate or become infinite)."""
         if strategy not in _STRATEGIES:
             raise ValueError(f"strategy must be one of {sorted(_STRATEGIES)}")
+        if (strategy == "fp8_moments") != (fp8_exponents is not None):
+            raise ValueError('fp8_exponents goes with strategy "fp8_moments" (and is required by it)')
         super().__init__(params, dict(lr=lr, betas=tuple(betas), eps=eps, weight_decay=weight_decay))
         self.strategy = strategy
         self.flags = _STRATEGIES[strategy]
@@ -44,10 +52,11 @@ class SRAdamW(torch.optim.Optimizer):
         if divide_bias_correction:
             self.flags |= B.SR_FLAG_DIV_BIAS
         self.fp32_moments = bool(self.flags & B.SR_FLAG_FP32_MOMENTS)
+        self.fp8_exponents = None if fp8_exponents is None else (int(fp8_exponents[0]), int(fp8_exponents[1]))
         self.max_norm = max_norm
         self.seed = seed
         self.t = 0
-        mdt = torch.float32 if self.fp32_moments else torch.bfloat16
+        mdt = torch.float32 if self.fp32_moments else torch.uint8 if self.fp8_exponents else torch.bfloat16
         self._flat: List[List[torch.Tensor]] = []                 # per group: flat views of the parameters
         dev = None
         for group in self.param_groups:
@@ -82,7 +91,9 @@ class SRAdamW(torch.optim.Optimizer):
                 aux = [s["aux"] for s in st] if (n and "aux" in st[0]) else None
                 per_group.append(B.TensorList(flat, [g.view(-1) for g in grads[k:k + n]],
                                               [s["exp_avg"] for s in st], [s["exp_avg_sq"] for s in st],
-                                              self.fp32_moments, tensor_ids=list(range(k, k + n)), aux=aux))
+                                              self.fp32_moments, tensor_ids=list(range(k, k + n)), aux=aux,
+                                              fp8_exponents=None if self.fp8_exponents is None
+                                              else [self.fp8_exponents] * n))
                 k += n
             everything = None
             if self.max_norm is not None:                         # the norm runs over all groups at once
@@ -133,13 +144,15 @@ class SRAdamW(torch.optim.Optimizer):
         the state tensors, in parameter order.  (torch's own packing would cast binary32 moments of
         BF16 parameters to BF16 on load, so the format is ours.)"""
         params = self._all_params()
-        return dict(t=self.t, seed=self.seed, strategy=self.strategy,
+        return dict(t=self.t, seed=self.seed, strategy=self.strategy, fp8_exponents=self.fp8_exponents,
                     param_groups=[{k: v for k, v in g.items() if k != "params"} for g in self.param_groups],
                     state=[dict(self.state[p]) for p in params])
 
     def load_state_dict(self, sd: dict) -> None:
         if sd.get("strategy", self.strategy) != self.strategy:
             raise ValueError(f"checkpoint was written with strategy {sd['strategy']!r}, this optimizer uses {self.strategy!r}")
+        if sd.get("fp8_exponents") is not None and tuple(sd["fp8_exponents"]) != self.fp8_exponents:
+            raise ValueError(f"checkpoint uses fp8 scale exponents {sd['fp8_exponents']}, this optimizer {self.fp8_exponents}")
         self.t, self.seed = sd["t"], sd["seed"]
         for group, saved in zip(self.param_groups, sd["param_groups"]):
             group.update(saved)

@@ -107,7 +107,12 @@ def test_adamw_argument_errors():
     assert step([t], hyper=(float("nan"), 0.9, 0.95, 1e-8, 0.1)) == B.SR_ERR_ARG
     assert step([t], hyper=(1e-3, 0.9, 0.95, float("inf"), 0.1)) == B.SR_ERR_ARG
     assert step([t], hyper=(1e-3, 0.9, 0.95, 1e-8, float("nan"))) == B.SR_ERR_ARG
-    assert step([t], flags=128) == B.SR_ERR_ARG
+    assert step([t], flags=256) == B.SR_ERR_ARG
+    for bad in (128 | 1, 128 | 2, 128 | 8 | 1, 128 | 16):        # 8-bit moments combine with few flags
+        assert step([t], flags=bad) == B.SR_ERR_ARG
+    assert step([tensor(reserved=0x10000)], flags=128) == B.SR_ERR_ARG
+    assert step([tensor(reserved=101)], flags=128) == B.SR_ERR_ARG           # m_exp out of range
+    assert step([tensor(reserved=(256 - 101) << 8)], flags=128) == B.SR_ERR_ARG   # v_exp = -101
     # comparison strategies: exact flag combinations and an aux tensor are required
     assert step([t], flags=B.SR_FLAG_MASTER_FP32) == B.SR_ERR_ARG
     assert step([t], flags=B.SR_FLAG_KAHAN | B.SR_FLAG_FP32_MOMENTS) == B.SR_ERR_ARG
