@@ -163,6 +163,45 @@ def test_config5_full_size_windows_through_warm_start():
     assert float((v_end > 0).mean()) > 0.99
 
 
+def test_config5_full_size_windows_8_bit_moments():
+    """The 6.7B flat buffer with the moments held in 8 bits (extension), 40 steps from zero: the
+    oracle follows the same windows, codes and parameters bit for bit (NaN codes as NaN codes)."""
+    import bench
+    cfg = W.config(5)
+    exps = bench.fp8_scale_exponents(cfg)
+    params = W.make_params(cfg.shapes, DEV, W.data_seed(cfg.index, 0), cfg.param_std)
+    n = params[0].numel()
+    ms = [torch.zeros(n, dtype=torch.uint8, device=DEV)]
+    vs = [torch.zeros(n, dtype=torch.uint8, device=DEV)]
+    grads = [torch.empty_like(params[0])]
+    tl = B.TensorList(params, grads, ms, vs, fp8_exponents=[exps])
+    rng = np.random.default_rng(58)
+    w = 1 << 16
+    picks = [(0, w), (n - w, w), ((1 << 32) - w // 2, w), ((1 << 32) + 3, w - 5), (n - 7, 7), (12345, 999)]
+    picks += [(int(rng.integers(0, n - w)), w) for _ in range(10)]
+    host = [dict(p=to_np(params[0][lo:lo + k]), m=to_np(ms[0][lo:lo + k]), v=to_np(vs[0][lo:lo + k]),
+                 m_exp=exps[0], v_exp=exps[1], tensor_id=0, elem_offset=lo) for lo, k in picks]
+    for t in range(1, 41):
+        W.fill_grads(grads, W.data_seed(5, t), cfg.grad_std)
+        B.sr_adamw_step(tl, cfg.hyper, t, cfg.seed, B.SR_FLAG_FP8_MOMENTS)
+        torch.cuda.synchronize()
+        for h, (lo, k) in zip(host, picks):
+            h["g"] = to_np(grads[0][lo:lo + k])
+        ref.sr_adamw_step(host, cfg.hyper, t, cfg.seed, ref.FLAG_FP8_MOMENTS)
+        if t in (1, 2, 20, 40):
+            bad = 0
+            for h, (lo, k) in zip(host, picks):
+                bad += same_bf16(to_np(params[0][lo:lo + k]), h["p"])
+                gm, gv = to_np(ms[0][lo:lo + k]), to_np(vs[0][lo:lo + k])
+                bad += int(((gm != h["m"]) & ~((gm & 0x7F) == 0x7F)).sum())
+                bad += int(((gv != h["v"]) & ~((gv & 0x7F) > 0x7C)).sum())
+            assert bad == 0, f"config 5, 8-bit moments, step {t}: {bad} mismatches"
+    # the state lives inside the formats: nothing saturated, nothing infinite, most of v alive
+    m_end, v_end = host[0]["m"], host[0]["v"]
+    assert not ((m_end & 0x7F) >= 0x7E).any() and not (v_end >= 0x7C).any()
+    assert float((v_end > 0).mean()) > 0.99
+
+
 def test_cast_every_binary32_encoding():
     """All 2^32 binary32 encodings (every exponent, subnormal, infinity and NaN payload), each with
     the draw its index gets: the GPU cast equals the by-value oracle bit for bit."""

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+import test_gpu_fp8_moments as F8
 import test_gpu_parity as P
 from oracle import ref
 from paper_2502_20566_amd import binding as B
@@ -26,6 +27,13 @@ def limit():
 def test_update_and_norm_cut_into_many_launches_match_the_oracle(limit, mode, wgs):
     limit(wgs)
     P.test_adamw_ragged_misaligned_and_offset_tensors(mode)
+
+
+@pytest.mark.parametrize("wgs", [1, 4])
+def test_update_with_8_bit_moments_cut_into_many_launches(limit, wgs):
+    limit(wgs)
+    F8.test_fp8_moments_many_steps_with_clip_and_offsets()
+    F8.test_fp8_moments_every_code_as_input(0)
 
 
 @pytest.mark.parametrize("wgs", [1, 5])
