@@ -364,23 +364,59 @@ __device__ __forceinline__ uint32_t max_magnitude4(const uint32_t (&b)[4])
     return max(max(b[0] & 0x7FFFFFFFu, b[1] & 0x7FFFFFFFu), max(b[2] & 0x7FFFFFFFu, b[3] & 0x7FFFFFFFu));
 }
 
-// Eight codes (two words) to binary32, times `inv_scale` (a power of two: exact).  The chip's
-// conversion decodes every code of both formats as the OCP tables say (checked on all 256);
-// NaN codes give a quiet NaN.
+// Eight codes (two words) to binary32, times the power of two `inv_scale`, in one instruction per
+// pair: the chip's scaled conversion multiplies the decoded value by 2^floor(log2 inv_scale),
+// exactly, and decodes every code of both formats as the OCP tables say (checked on all 256, with
+// several scales); NaN codes give a quiet NaN.
 template <int FMT>
 __device__ __forceinline__ void fp8_decode8(v2u codes, float inv_scale, float (&out)[8])
 {
     typedef float f2 __attribute__((ext_vector_type(2)));
     f2 q[4];
     if (FMT == 0) {
-        q[0] = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes.x, false); q[1] = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes.x, true);
-        q[2] = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes.y, false); q[3] = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes.y, true);
+        q[0] = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8((int)codes.x, inv_scale, false);
+        q[1] = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8((int)codes.x, inv_scale, true);
+        q[2] = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8((int)codes.y, inv_scale, false);
+        q[3] = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8((int)codes.y, inv_scale, true);
     } else {
-        q[0] = __builtin_amdgcn_cvt_pk_f32_bf8((int)codes.x, false); q[1] = __builtin_amdgcn_cvt_pk_f32_bf8((int)codes.x, true);
-        q[2] = __builtin_amdgcn_cvt_pk_f32_bf8((int)codes.y, false); q[3] = __builtin_amdgcn_cvt_pk_f32_bf8((int)codes.y, true);
+        q[0] = __builtin_amdgcn_cvt_scalef32_pk_f32_bf8((int)codes.x, inv_scale, false);
+        q[1] = __builtin_amdgcn_cvt_scalef32_pk_f32_bf8((int)codes.x, inv_scale, true);
+        q[2] = __builtin_amdgcn_cvt_scalef32_pk_f32_bf8((int)codes.y, inv_scale, false);
+        q[3] = __builtin_amdgcn_cvt_scalef32_pk_f32_bf8((int)codes.y, inv_scale, true);
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { out[2 * j] = q[j].x * inv_scale; out[2 * j + 1] = q[j].y * inv_scale; }
+    for (int j = 0; j < 4; ++j) { out[2 * j] = q[j].x; out[2 * j + 1] = q[j].y; }
+}
+
+// Four values times the power of two `scale` into one word of codes.  Not `ranged` (no scaled
+// value of the wave reaches the format's top binade, none is a NaN): the chip's scaled conversion,
+// which rounds x / 2^floor(log2 inv_scale) -- the exact product, binary32 subnormal inputs
+// included -- by the rule of fp8_encode4 (checked against that rule on 4e6 values per scale).  The
+// product as a binary32 multiplication, which is what the definition says, can differ from the
+// exact one only where it underflows, and there both give a zero with the product's sign.
+// `ranged`: the multiplication and the integer path.
+template <int FMT>
+__device__ __forceinline__ uint32_t fp8_encode4_scaled(const float (&x)[4], const uint32_t (&r)[4], float scale,
+                                                       float inv_scale, bool ranged)
+{
+    if (ranged) {
+        const uint32_t b[4] = {__float_as_uint(x[0] * scale), __float_as_uint(x[1] * scale),
+                               __float_as_uint(x[2] * scale), __float_as_uint(x[3] * scale)};
+        return fp8_encode4<FMT>(b, r, true);
+    }
+    int w = 0;
+    if (FMT == 0) {
+        w = __builtin_amdgcn_cvt_scalef32_sr_fp8_f32(w, x[0], r[0], inv_scale, 0);
+        w = __builtin_amdgcn_cvt_scalef32_sr_fp8_f32(w, x[1], r[1], inv_scale, 1);
+        w = __builtin_amdgcn_cvt_scalef32_sr_fp8_f32(w, x[2], r[2], inv_scale, 2);
+        w = __builtin_amdgcn_cvt_scalef32_sr_fp8_f32(w, x[3], r[3], inv_scale, 3);
+    } else {
+        w = __builtin_amdgcn_cvt_scalef32_sr_bf8_f32(w, x[0], r[0], inv_scale, 0);
+        w = __builtin_amdgcn_cvt_scalef32_sr_bf8_f32(w, x[1], r[1], inv_scale, 1);
+        w = __builtin_amdgcn_cvt_scalef32_sr_bf8_f32(w, x[2], r[2], inv_scale, 2);
+        w = __builtin_amdgcn_cvt_scalef32_sr_bf8_f32(w, x[3], r[3], inv_scale, 3);
+    }
+    return (uint32_t)w;
 }
 
 // Eight codes starting at element l0 of `base`, element-wise, zeros outside [0, numel).
@@ -406,43 +442,41 @@ __device__ __forceinline__ void store8_u8(uint8_t* base, int64_t l0, uint64_t nu
     }
 }
 
-// The write-back of a lane's eight new moments as 8-bit codes: m * m_scale to E4M3 and
-// v * v_scale to E5M2, each with the element's 16-bit draw of its stream (mw, vw: two draws per
+// The power of two 2^e as a binary32 value (|e| <= 126).
+__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((uint32_t)(127 + e) << 23); }
+
+// The write-back of a lane's eight new moments as 8-bit codes: m * 2^m_exp to E4M3 and
+// v * 2^v_exp to E5M2, each with the element's 16-bit draw of its stream (mw, vw: two draws per
 // word, low half for the even element, as for BF16 moments) in the top half of the random word.
 // `nan`: some value of the wave may be a NaN (wave-uniform; the maxima below skip NaNs).
-__device__ __forceinline__ void fp8_moments_out(const float (&m)[8], const float (&v)[8], float m_scale, float v_scale,
+__device__ __forceinline__ void fp8_moments_out(const float (&m)[8], const float (&v)[8], int m_exp, int v_exp,
                                                 const uint32_t* mw, const uint32_t* vw, bool nan, v2u& mo, v2u& vo)
 {
-    float ms[8], vs[8];
     uint32_t mr[8], vr[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        ms[j] = m[j] * m_scale;
-        vs[j] = v[j] * v_scale;
         mr[j] = (j & 1) ? (mw[j >> 1] & 0xFFFF0000u) : (mw[j >> 1] << 16);
         vr[j] = (j & 1) ? (vw[j >> 1] & 0xFFFF0000u) : (vw[j >> 1] << 16);
     }
-    // the range rules apply from the formats' top binades upwards (2^8 for E4M3, 2^15 for E5M2;
-    // a negative v cannot arise from the update but may be loaded: its magnitude counts)
+    // the range rules apply from the formats' top binades upwards: scaled magnitudes of 2^8 for
+    // E4M3 and 2^15 for E5M2 (a negative v cannot arise from the update but may be loaded: its
+    // magnitude counts)
     float mmax = 0.0f, vmax = 0.0f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        mmax = __builtin_fmaxf(mmax, __builtin_fabsf(ms[j]));
-        vmax = __builtin_fmaxf(vmax, __builtin_fabsf(vs[j]));
+        mmax = __builtin_fmaxf(mmax, __builtin_fabsf(m[j]));
+        vmax = __builtin_fmaxf(vmax, __builtin_fabsf(v[j]));
     }
-    const bool ranged = nan || __builtin_amdgcn_ballot_w64(mmax >= 256.0f || vmax >= 32768.0f) != 0;   // wave-uniform
-    const uint32_t ml[4] = {__float_as_uint(ms[0]), __float_as_uint(ms[1]), __float_as_uint(ms[2]), __float_as_uint(ms[3])};
-    const uint32_t mh[4] = {__float_as_uint(ms[4]), __float_as_uint(ms[5]), __float_as_uint(ms[6]), __float_as_uint(ms[7])};
-    const uint32_t vl[4] = {__float_as_uint(vs[0]), __float_as_uint(vs[1]), __float_as_uint(vs[2]), __float_as_uint(vs[3])};
-    const uint32_t vh[4] = {__float_as_uint(vs[4]), __float_as_uint(vs[5]), __float_as_uint(vs[6]), __float_as_uint(vs[7])};
+    const bool lane_ranged = mmax >= pow2f(8 - m_exp) || vmax >= pow2f(15 - v_exp);
+    const bool ranged = nan || __builtin_amdgcn_ballot_w64(lane_ranged) != 0;   // wave-uniform
+    const float ml[4] = {m[0], m[1], m[2], m[3]}, mh[4] = {m[4], m[5], m[6], m[7]};
+    const float vl[4] = {v[0], v[1], v[2], v[3]}, vh[4] = {v[4], v[5], v[6], v[7]};
     const uint32_t mrl[4] = {mr[0], mr[1], mr[2], mr[3]}, mrh[4] = {mr[4], mr[5], mr[6], mr[7]};
     const uint32_t vrl[4] = {vr[0], vr[1], vr[2], vr[3]}, vrh[4] = {vr[4], vr[5], vr[6], vr[7]};
-    mo.x = fp8_encode4<0>(ml, mrl, ranged); mo.y = fp8_encode4<0>(mh, mrh, ranged);
-    vo.x = fp8_encode4<1>(vl, vrl, ranged); vo.y = fp8_encode4<1>(vh, vrh, ranged);
+    const float ms = pow2f(m_exp), mi = pow2f(-m_exp), vs = pow2f(v_exp), vi = pow2f(-v_exp);
+    mo.x = fp8_encode4_scaled<0>(ml, mrl, ms, mi, ranged); mo.y = fp8_encode4_scaled<0>(mh, mrh, ms, mi, ranged);
+    vo.x = fp8_encode4_scaled<1>(vl, vrl, vs, vi, ranged); vo.y = fp8_encode4_scaled<1>(vh, vrh, vs, vi, ranged);
 }
-
-// The power of two 2^e as a binary32 value (|e| <= 100).
-__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((uint32_t)(127 + e) << 23); }
 
 // ---------------------------------------------------------------------------- fused update
 
@@ -691,7 +725,7 @@ __device__ __forceinline__ void inner_block(const TensorDesc& T, const StepScala
         buf_store16<NT>(rv, o32, bits4lo(L.v)); buf_store16<NT>(rv, o32 + 16u, bits4hi(L.v));
     } else if (M::fp8m) {
         v2u mo, vo;
-        fp8_moments_out(L.m, L.v, pow2f(m_exp), pow2f(v_exp), dm.w, dv.w, nan, mo, vo);
+        fp8_moments_out(L.m, L.v, m_exp, v_exp, dm.w, dv.w, nan, mo, vo);
         buf_store8<NT>(rm, lane * 8u, mo);
         buf_store8<NT>(rv, lane * 8u, vo);
     } else {
@@ -736,7 +770,7 @@ __device__ __forceinline__ void edge_block(const TensorDesc& T, const StepScalar
         store8_f32<false>(static_cast<float*>(T.v), l0, numel, false, L.v);
     } else if (M::fp8m) {
         v2u mo, vo;
-        fp8_moments_out(L.m, L.v, pow2f(m_exp), pow2f(v_exp), dm.w, dv.w, nan, mo, vo);
+        fp8_moments_out(L.m, L.v, m_exp, v_exp, dm.w, dv.w, nan, mo, vo);
         store8_u8(static_cast<uint8_t*>(T.m), l0, numel, mo);
         store8_u8(static_cast<uint8_t*>(T.v), l0, numel, vo);
     } else {

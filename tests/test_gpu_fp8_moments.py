@@ -129,6 +129,20 @@ def test_fp8_moments_top_of_range_and_nan_gradients():
     assert st.host[0]["m"][5] & 0x7F == 0x7F
 
 
+@pytest.mark.parametrize("exps,g_scale", [((100, 100), 2.0 ** -12), ((100, 100), 2.0 ** -24), ((-100, -100), 1.0),
+                                          ((97, -3), 2.0 ** -20), ((-100, 100), 2.0 ** 8)])
+def test_fp8_moments_extreme_scales(exps, g_scale):
+    """The largest scale exponents, with gradients so small (or large) that new moments are binary32
+    subnormals, that their scaled values fall into the 8-bit formats' subnormal ranges or below them,
+    or that squares overflow: the scaled conversion of the kernel and the multiply-then-round of the
+    definition must still agree in every element."""
+    st = State([2048 + 3, 517], [exps, exps], seed=31, views=1)
+    rng = np.random.default_rng(6)
+    for t in (1, 2, 3):
+        st.step(t, 77, g_scale=g_scale, rng=rng)
+        st.check(f"exponents {exps}, step {t}")
+
+
 def test_fp8_moments_arguments():
     n = 64
     p = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
