@@ -163,3 +163,43 @@ def test_fp8_moments_arguments():
     tl.array[0].reserved = 0x10000
     with pytest.raises(B.SrError):
         B.sr_adamw_step(tl, HYP, 1, 0, FP8)
+
+
+def test_optimizer_object_with_8_bit_moments_and_resume():
+    """SRAdamW(strategy="fp8_moments") equals direct calls through the binding (which the tests above
+    pin to the oracle), through a resume from state_dict; a checkpoint written with other scale
+    exponents is refused."""
+    from paper_2502_20566_amd.optimizer import SRAdamW
+    torch.manual_seed(0)
+    model = torch.nn.Sequential(torch.nn.Linear(48, 80), torch.nn.Tanh(), torch.nn.Linear(80, 6)).to(DEV).to(torch.bfloat16)
+    params = list(model.parameters())
+    exps = (13, 27)
+    ref_p = [p.detach().clone().view(-1) for p in params]
+    ref_m = [torch.zeros(p.numel(), dtype=torch.uint8, device=DEV) for p in ref_p]
+    ref_v = [torch.zeros(p.numel(), dtype=torch.uint8, device=DEV) for p in ref_p]
+    opt = SRAdamW(params, lr=2e-3, seed=9, strategy="fp8_moments", fp8_exponents=exps)
+    hyper = dict(lr=2e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    x = torch.randn(32, 48, device=DEV, dtype=torch.bfloat16)
+    for t in range(1, 6):
+        model(x).float().pow(2).mean().backward()
+        grads = [p.grad.detach().clone().view(-1) for p in params]
+        opt.step()
+        opt.zero_grad()
+        tl = B.TensorList(ref_p, grads, ref_m, ref_v, fp8_exponents=[exps] * len(ref_p))
+        B.sr_adamw_step(tl, hyper, t, 9, FP8)
+        torch.cuda.synchronize()
+        for a, b, m, v in zip(params, ref_p, ref_m, ref_v):
+            assert torch.equal(a.detach().view(-1).view(torch.int16), b.view(torch.int16))
+            assert torch.equal(opt.state[a]["exp_avg"], m) and torch.equal(opt.state[a]["exp_avg_sq"], v)
+        if t == 2:
+            sd = opt.state_dict()
+            sd["state"] = [{k: v_.clone() for k, v_ in st.items()} for st in sd["state"]]
+            with pytest.raises(ValueError):
+                SRAdamW(params, strategy="fp8_moments", fp8_exponents=(12, 27)).load_state_dict(sd)
+            opt = SRAdamW(params, lr=2e-3, seed=0, strategy="fp8_moments", fp8_exponents=exps)
+            opt.load_state_dict(sd)
+    assert any(int(m.count_nonzero()) > 0 for m in ref_m)
+    with pytest.raises(ValueError):
+        SRAdamW(params, strategy="fp8_moments")
+    with pytest.raises(ValueError):
+        SRAdamW(params, strategy="sr", fp8_exponents=exps)
