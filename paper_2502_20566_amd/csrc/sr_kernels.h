@@ -17,7 +17,9 @@ namespace sr {
 // MI355X, 64-lane workgroups stream the 4-read/3-write pattern about 10% faster than 256-lane
 // ones (finer interleaving of the seven streams in time), and more blocks per lane are slower.
 // Rows of 4 elements per lane in the cast kernels.  Measured on 6.66e9 elements: BF16 cast 6.06 /
-// 6.10 / 7.04 ms with 1 / 2 / 4 rows; 8-bit cast 6.07 / 5.64 / 5.64 ms.
+// 6.10 / 7.04 ms with 1 / 2 / 4 rows; 8-bit cast (integer path) 6.07 / 5.64 / 5.64 ms.
+// SR_TUNE_FP8_NOHW = 1 builds the 8-bit cast without the chip's conversion instruction (every wave
+// on the integer path): the build used to check that path on all binary32 encodings.
 #ifndef SR_TUNE_FP8_NOHW
 #define SR_TUNE_FP8_NOHW 0
 #endif
