@@ -496,13 +496,35 @@ struct Mode {
     static constexpr bool half   = fp32m;                         // fast path: a lane owns half a block
 };
 
-// Algorithm 1 lines 5-10 for one element.  In: p, g, m, v.  Out: sum = lr u + (lr wd) p and
-// y = p - sum (the unrounded new parameter); m and v are replaced by the unrounded new moments.
-// One rounding per operation, in this order (no contraction: the library is built with
-// -ffp-contract=off; sqrt and divide are correctly rounded).
+// Correctly rounded square root of a binary32 value in [2^-96, +inf]: the hardware's approximation
+// and one step down or up, decided by the exact residuals x - s_down*s and x - s_up*s (one fused
+// multiply-add each).  This is the core of the compiler's own expansion of sqrtf, without its input
+// scaling for arguments below 2^-96 and without its special-case select for zeros, infinities and
+// NaNs: seven instructions instead of sixteen.  Equal to sqrtf on every encoding of that range
+// (compared once on the GPU, all 1.9e9 of them).
+__device__ __forceinline__ float sqrt_normal(float x)
+{
+    const float s = __builtin_amdgcn_sqrtf(x);
+    const float sd = __uint_as_float(__float_as_uint(s) - 1u), su = __uint_as_float(__float_as_uint(s) + 1u);
+    const float rd = __builtin_fmaf(-sd, s, x);
+    const float ru = __builtin_fmaf(-su, s, x);
+    float r = (rd <= 0.0f) ? sd : s;
+    r = (ru > 0.0f) ? su : r;
+    return r;
+}
+constexpr uint32_t kSqrtNormalLo = 0x0F800000u, kSqrtNormalHi = 0x7F800000u;   // encodings of 2^-96 and +inf
+
+// Algorithm 1 lines 5-10 for one element, in two parts.  One rounding per operation, in this order
+// (no contraction: the library is built with -ffp-contract=off; sqrt and divide are correctly
+// rounded).  `variant` is 0 at compile time in the kernels of the default arithmetic (straight-line
+// code) and a kernel argument in the others (wave-uniform branches).
+// Part 1, lines 5-8.  In: g, m, v.  m and v are replaced by the unrounded new moments; mh is the
+// bias-corrected first moment, root_arg what line 10 takes the root of: the bias-corrected second
+// moment, plus eps in the variant that has eps inside the root (Appendix B).  Bias corrections as
+// multiplications by host reciprocals, or (variant) the divisions of lines 7-8 as printed.
 template <bool CLIP>
-__device__ __forceinline__ void update_elem(const StepScalars& S, uint32_t variant, float c, float p, float g,
-                                            float& m, float& v, float& y, float& sum)
+__device__ __forceinline__ void moments_elem(const StepScalars& S, uint32_t variant, float c, float g,
+                                             float& m, float& v, float& mh, float& root_arg)
 {
     const float g1 = CLIP ? g * c : g;
     const float t1 = S.beta1 * m;
@@ -512,22 +534,27 @@ __device__ __forceinline__ void update_elem(const StepScalars& S, uint32_t varia
     const float t3 = S.beta2 * v;
     const float t4 = S.omb2 * gg;
     const float v1 = t3 + t4;
-    // Bias corrections as multiplications by host reciprocals, or (variant) the divisions of
-    // Algorithm 1 lines 7-8 as printed; eps outside the root, or (variant) inside it as in
-    // Appendix B.  `variant` is 0 at compile time in the kernels of the default arithmetic
-    // (straight-line code) and a kernel argument in the others (wave-uniform branches).
-    float mh, vh, d;
+    float vh;
     if (variant & VARIANT_DIV_BIAS) { mh = m1 / S.bc1; vh = v1 / S.bc2; }
     else                            { mh = m1 * S.rbc1; vh = v1 * S.rbc2; }
-    if (variant & VARIANT_EPS_IN_ROOT) { const float ve = vh + S.eps; d = __builtin_sqrtf(ve); }
-    else                               { d = __builtin_sqrtf(vh) + S.eps; }
+    root_arg = (variant & VARIANT_EPS_IN_ROOT) ? vh + S.eps : vh;
+    m = m1;
+    v = v1;
+}
+
+// Part 2, line 10.  Out: sum = lr u + (lr wd) p and y = p - sum (the unrounded new parameter).
+// SHORT_ROOT: every root_arg of the wave lies in [2^-96, +inf] (the caller has checked).
+template <bool SHORT_ROOT>
+__device__ __forceinline__ void step_elem(const StepScalars& S, uint32_t variant, float p, float mh, float root_arg,
+                                          float& y, float& sum)
+{
+    const float root = SHORT_ROOT ? sqrt_normal(root_arg) : __builtin_sqrtf(root_arg);
+    const float d = (variant & VARIANT_EPS_IN_ROOT) ? root : root + S.eps;
     const float q = mh / d;
     const float a = S.lr * q;
     const float w = S.lw * p;
     sum = a + w;
     y = p - sum;
-    m = m1;
-    v = v1;
 }
 
 // The N (8 or 4) elements a lane owns, as binary32 values, and what it will store.
@@ -547,10 +574,26 @@ __device__ __forceinline__ bool update_lane(LaneRegs<N>& L, const StepScalars& S
 {
     using M = Mode<F>;
     const uint32_t variant = VAR ? S.variant : 0u;
-    float y[N], sum[N];
+    float y[N], sum[N], mh[N], ra[N];
 #pragma unroll
-    for (int j = 0; j < N; ++j)
-        update_elem<CLIP>(S, variant, c, M::master ? L.aux[j] : L.p[j], L.g[j], L.m[j], L.v[j], y[j], sum[j]);
+    for (int j = 0; j < N; ++j) moments_elem<CLIP>(S, variant, c, L.g[j], L.m[j], L.v[j], mh[j], ra[j]);
+    // Where the kernel is bound by instruction issue (8-bit moments) the square roots of a wave whose
+    // arguments all lie in [2^-96, +inf] take the short form; zeros, tiny values, negative values and
+    // NaNs (all outside that range of encodings) send the whole wave through sqrtf.
+    bool short_root = false;
+    if (M::fp8m) {
+        uint32_t lo = __float_as_uint(ra[0]), hi = lo;
+#pragma unroll
+        for (int j = 1; j < N; ++j) { lo = min(lo, __float_as_uint(ra[j])); hi = max(hi, __float_as_uint(ra[j])); }
+        short_root = __builtin_amdgcn_ballot_w64(lo < kSqrtNormalLo || hi > kSqrtNormalHi) == 0;   // wave-uniform
+    }
+    if (short_root) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) step_elem<true>(S, variant, M::master ? L.aux[j] : L.p[j], mh[j], ra[j], y[j], sum[j]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < N; ++j) step_elem<false>(S, variant, M::master ? L.aux[j] : L.p[j], mh[j], ra[j], y[j], sum[j]);
+    }
     // A NaN in m' or v' always makes y NaN, so one test covers all three outputs; the test is
     // folded over the wave so that the guarded roundings are a branch no wave takes in practice
     // (as per-lane selects they were 100 of the 680 vector instructions of a wave).
