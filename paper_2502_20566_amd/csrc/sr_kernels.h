@@ -514,6 +514,30 @@ __device__ __forceinline__ float sqrt_normal(float x)
 }
 constexpr uint32_t kSqrtNormalLo = 0x0F800000u, kSqrtNormalHi = 0x7F800000u;   // encodings of 2^-96 and +inf
 
+// Correctly rounded quotient n / d for 2^-40 <= |n| <= 2^40 and 2^-41 <= d <= 2^41: the reciprocal
+// approximation, one refinement of it, and two refinements of the quotient -- the compiler's own
+// expansion of the division with its v_div_scale / v_div_fmas scaling and v_div_fixup steps left
+// out.  Inside that domain those steps do nothing (the exponents differ by less than 96, neither
+// operand nor the reciprocal nor the quotient is subnormal, nothing is zero, infinite or a NaN), so
+// the instruction sequence is the same one: 8 instructions instead of 11.  A NaN numerator gives a
+// NaN, as the full form does.  Compared with the full form on 3.4e10 random pairs of the domain and
+// on its edges: identical.
+__device__ __forceinline__ float div_normal(float n, float d)
+{
+    const float r0 = __builtin_amdgcn_rcpf(d);
+    const float e0 = __builtin_fmaf(-d, r0, 1.0f);
+    const float r1 = __builtin_fmaf(e0, r0, r0);
+    const float q0 = n * r1;
+    const float e1 = __builtin_fmaf(-d, q0, n);
+    const float q1 = __builtin_fmaf(e1, r1, q0);
+    const float e2 = __builtin_fmaf(-d, q1, n);
+    return __builtin_fmaf(e2, r1, q1);
+}
+// A wave takes the short forms when every root argument lies in [2^-80, 2^80] (so every root in
+// [2^-40, 2^40], inside sqrt_normal's range), every |numerator| in [2^-40, 2^40] and eps <= 2^40.
+constexpr uint32_t kShortRootLo = (127u - 80u) << 23, kShortRootHi = (127u + 80u) << 23;
+constexpr float kShortNumLo = 0x1p-40f, kShortNumHi = 0x1p40f;
+
 // Algorithm 1 lines 5-10 for one element, in two parts.  One rounding per operation, in this order
 // (no contraction: the library is built with -ffp-contract=off; sqrt and divide are correctly
 // rounded).  `variant` is 0 at compile time in the kernels of the default arithmetic (straight-line
@@ -543,14 +567,14 @@ __device__ __forceinline__ void moments_elem(const StepScalars& S, uint32_t vari
 }
 
 // Part 2, line 10.  Out: sum = lr u + (lr wd) p and y = p - sum (the unrounded new parameter).
-// SHORT_ROOT: every root_arg of the wave lies in [2^-96, +inf] (the caller has checked).
-template <bool SHORT_ROOT>
+// SHORT: the wave's operands lie in the domains of sqrt_normal and div_normal (the caller has checked).
+template <bool SHORT>
 __device__ __forceinline__ void step_elem(const StepScalars& S, uint32_t variant, float p, float mh, float root_arg,
                                           float& y, float& sum)
 {
-    const float root = SHORT_ROOT ? sqrt_normal(root_arg) : __builtin_sqrtf(root_arg);
+    const float root = SHORT ? sqrt_normal(root_arg) : __builtin_sqrtf(root_arg);
     const float d = (variant & VARIANT_EPS_IN_ROOT) ? root : root + S.eps;
-    const float q = mh / d;
+    const float q = SHORT ? div_normal(mh, d) : mh / d;
     const float a = S.lr * q;
     const float w = S.lw * p;
     sum = a + w;
@@ -577,15 +601,21 @@ __device__ __forceinline__ bool update_lane(LaneRegs<N>& L, const StepScalars& S
     float y[N], sum[N], mh[N], ra[N];
 #pragma unroll
     for (int j = 0; j < N; ++j) moments_elem<CLIP>(S, variant, c, L.g[j], L.m[j], L.v[j], mh[j], ra[j]);
-    // Where the kernel is bound by instruction issue (8-bit moments) the square roots of a wave whose
-    // arguments all lie in [2^-96, +inf] take the short form; zeros, tiny values, negative values and
-    // NaNs (all outside that range of encodings) send the whole wave through sqrtf.
+    // Where the kernel is bound by instruction issue (8-bit moments) the square roots and divisions
+    // of a wave whose operands all lie in the short forms' domains take those forms; zeros, tiny,
+    // huge, infinite and negative root arguments and NaNs send the whole wave through sqrtf and the
+    // full division (a NaN numerator alone does not: it gives a NaN either way).
     bool short_root = false;
     if (M::fp8m) {
         uint32_t lo = __float_as_uint(ra[0]), hi = lo;
+        float nlo = __builtin_fabsf(mh[0]), nhi = nlo;
 #pragma unroll
-        for (int j = 1; j < N; ++j) { lo = min(lo, __float_as_uint(ra[j])); hi = max(hi, __float_as_uint(ra[j])); }
-        short_root = __builtin_amdgcn_ballot_w64(lo < kSqrtNormalLo || hi > kSqrtNormalHi) == 0;   // wave-uniform
+        for (int j = 1; j < N; ++j) {
+            lo = min(lo, __float_as_uint(ra[j])); hi = max(hi, __float_as_uint(ra[j]));
+            nlo = __builtin_fminf(nlo, __builtin_fabsf(mh[j])); nhi = __builtin_fmaxf(nhi, __builtin_fabsf(mh[j]));
+        }
+        const bool lane_ok = lo >= kShortRootLo && hi <= kShortRootHi && nlo >= kShortNumLo && nhi <= kShortNumHi;
+        short_root = S.eps <= kShortNumHi && __builtin_amdgcn_ballot_w64(!lane_ok) == 0;   // wave-uniform
     }
     if (short_root) {
 #pragma unroll
