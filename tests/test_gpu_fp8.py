@@ -3,6 +3,8 @@ CPU oracle, bit for bit, through the C ABI.  The kernel works on encodings (the 
 instruction for waves that hold nothing near the top of the format's range, else a split of the
 significand and the carry of an add); the oracle on values (frexp/floor/ldexp and a search of the
 decoded grid): they share nothing but the published formats and the Philox layout."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -119,6 +121,23 @@ def test_fp8_cast_wave_with_a_value_near_the_top_of_the_range(gfmt, ofmt):
     want = ref.sr_cast_f32_fp8(bits.view(np.float32), ofmt, 12, 9, 4)
     bad = np.flatnonzero(got != want)
     assert bad.size == 0, (hex(int(bits[bad[0]])), got[bad[0]], want[bad[0]])
+
+
+@pytest.mark.skipif(os.environ.get("SR_TEST_EXHAUSTIVE") != "1",
+                    reason="three minutes of oracle time; set SR_TEST_EXHAUSTIVE=1 to run")
+@pytest.mark.parametrize("gfmt,ofmt", FMTS)
+def test_fp8_cast_all_binary32_encodings(gfmt, ofmt):
+    """Every one of the 2^32 binary32 encodings, in 32 pieces (waves of consecutive encodings share
+    an exponent, so all of them below the top binade take the conversion instruction and all above
+    it the integer path)."""
+    piece = 1 << 27
+    for c in range(32):
+        bits = torch.arange(c * piece, (c + 1) * piece, dtype=torch.int64, device=DEV).to(torch.int32)
+        x = bits.view(torch.float32)
+        got = gpu_cast(x, gfmt, 0xABCDEF, 5 + c, 2)
+        want = ref.sr_cast_f32_fp8(x.cpu().numpy(), ofmt, 0xABCDEF, 5 + c, 2)
+        bad = np.flatnonzero(got != want)
+        assert bad.size == 0, (c, hex(c * piece + int(bad[0])), got[bad[0]], want[bad[0]])
 
 
 @pytest.mark.parametrize("gfmt,ofmt", FMTS)
