@@ -103,8 +103,10 @@ extern "C" {
 typedef struct sr_tensor {
     void*       p;           /* BF16 [numel], in/out: parameters x_t                      */
     const void* g;           /* BF16 [numel], in    : reduced gradient (Alg.1 line 4)     */
-    void*       m;           /* BF16 or binary32 [numel], in/out: first moment            */
-    void*       v;           /* same type as m, in/out: second moment                     */
+    void*       m;           /* BF16 or binary32 [numel], in/out: first moment (E4M3 codes,
+                                one byte each, with SR_FLAG_FP8_MOMENTS)                  */
+    void*       v;           /* same type as m, in/out: second moment (E5M2 codes with
+                                SR_FLAG_FP8_MOMENTS)                                      */
     void*       aux;         /* NULL unless a flag names it: binary32 master parameters
                                 (SR_FLAG_MASTER_FP32) or BF16 Kahan compensation
                                 (SR_FLAG_KAHAN), in/out                                   */
