@@ -504,7 +504,11 @@ void ref_sr_adamw_tensor(uint16_t* p, const uint16_t* g, void* m, void* v, void*
  * in the top half of the 32-bit word: the rounding sees k = floor(2^16 frac) of the
  * dropped fraction (bias below 2^-16 of one grid spacing).  The parameter is
  * written back as in the BF16 strategies: SR with stream 0, or nearest with
- * REF_FLAG_RNE_PARAMS.  |m_exp|, |v_exp| <= 100 keeps the decode exact. */
+ * REF_FLAG_RNE_PARAMS.  |m_exp|, |v_exp| <= 100 keeps the decode exact.
+ * The write-back of v saturates like that of m: where Q_SR gives E5M2's infinity
+ * (a scaled value above 57344 that rounds up, or an infinite one) the largest
+ * finite code S.11110.11 is stored instead, because an infinite second moment
+ * would stay infinite (beta2 * inf) and stop its parameter for good.  NaN stays NaN. */
 void ref_sr_adamw_tensor_fp8m(uint16_t* p, const uint16_t* g, uint8_t* m8, uint8_t* v8,
                               uint64_t numel, uint32_t tensor_id, uint64_t elem_offset,
                               const ref_scalars_t* s, uint32_t step, uint64_t seed,
@@ -529,7 +533,9 @@ void ref_sr_adamw_tensor_fp8m(uint16_t* p, const uint16_t* g, uint8_t* m8, uint8
         float ms = m1 * m_scale;
         float vs = v1 * v_scale;
         m8[i] = ref_sr_round_fp8(ms, ref_r16(seed, step, tensor_id, gi, 1u) << 16, 0);
-        v8[i] = ref_sr_round_fp8(vs, ref_r16(seed, step, tensor_id, gi, 2u) << 16, 1);
+        uint8_t vc = ref_sr_round_fp8(vs, ref_r16(seed, step, tensor_id, gi, 2u) << 16, 1);
+        if ((vc & 0x7Fu) == 0x7Cu) vc = (uint8_t)((vc & 0x80u) | 0x7Bu);      /* infinity -> largest finite */
+        v8[i] = vc;
     }
 }
 

@@ -122,13 +122,23 @@ def test_range_rules_and_nan():
     m8, v8 = np.zeros(4, np.uint8), np.zeros(4, np.uint8)
     ref.sr_adamw_tensor_fp8m(p.copy(), g, m8, v8, 0, s, 1, 0, 13, 21)      # 0.1 * 2^13 = 819 > 448; 0.05 * 2^21 > 65536
     assert list(m8[:3]) == [0x7E, 0xFE, 0x7E]            # E4M3 saturates, sign kept
-    assert list(v8[:3]) == [0x7C, 0x7C, 0x7C]            # E5M2 goes to infinity
+    assert list(v8[:3]) == [0x7B, 0x7B, 0x7B]            # and so does E5M2 here: 57344, not infinity
     assert m8[3] & 0x7F == 0x7F and v8[3] & 0x7F == 0x7F  # NaN gradient: NaN codes
-    # infinity in v8 stays, NaN code in m8 stays a NaN
+    # an infinity that came in with v8 leaves as the largest finite value, a NaN code in m8 stays a NaN
     m8, v8 = np.array([0x7F, 0x08], np.uint8), np.array([0x10, 0x7C], np.uint8)
     pp = p[:2].copy()
     ref.sr_adamw_tensor_fp8m(pp, g[:2], m8, v8, 0, s, 1, 0, 0, 0)
-    assert m8[0] & 0x7F == 0x7F and v8[1] == 0x7C
+    assert m8[0] & 0x7F == 0x7F and v8[1] == 0x7B
+    # just below the top: 57344 stays, and a value between 57344 and 65536 goes to 57344 whatever the draw
+    # (g = 2^8 at step 1: v1 = (1 - beta2) 2^16 = 3276.8 (as binary32 products); times 2^4 = 52428.8, times 2^5 > 65536)
+    g2 = trunc_bits(np.full(64, 256.0))
+    for v_exp, allowed in ((4, {0x7A, 0x7B}), (5, {0x7B})):
+        codes = set()
+        for seed in range(40):
+            m8, v8 = np.zeros(64, np.uint8), np.zeros(64, np.uint8)
+            ref.sr_adamw_tensor_fp8m(trunc_bits(np.full(64, 0.5)), g2, m8, v8, 0, s, 1, seed, 0, v_exp)
+            codes |= set(v8.tolist())
+        assert codes == allowed
 
 
 def test_slices_with_element_offsets_reproduce_the_whole():
