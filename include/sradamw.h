@@ -96,8 +96,12 @@ extern "C" {
                                    sr_cast_f32_fp8's rule (the fraction is cut to 16
                                    bits).  10 bytes moved per element instead of 14.
                                    Combines with SR_FLAG_RNE_PARAMS, SR_FLAG_EPS_IN_ROOT
-                                   and SR_FLAG_DIV_BIAS only.  NaN codes stay NaN codes;
-                                   NaN signs and payloads are not specified.            */
+                                   and SR_FLAG_DIV_BIAS only.  Both write-backs saturate:
+                                   a scaled m' beyond 448 is stored as 448, a scaled v'
+                                   beyond 57344 (or one that Q_SR would round to E5M2's
+                                   infinity) as 57344, so the state never holds an
+                                   infinity.  NaN codes stay NaN codes; NaN signs and
+                                   payloads are not specified.                          */
 
 /* One tensor of the multi-tensor list. */
 typedef struct sr_tensor {

@@ -325,12 +325,13 @@ template <int FMT> struct Fp8 {
     static constexpr uint32_t efmax = FMT == 0 ? 127u + 8u : 127u + 15u;   // binade of the largest finite value
 };
 
-// One element on the integer path: every range and NaN rule applied.
-template <int FMT>
+// One element on the integer path: every range and NaN rule applied.  TOP: the code that larger
+// results collapse to (the format's own by default: E4M3's largest finite value, E5M2's infinity).
+template <int FMT, uint32_t TOP = Fp8<FMT>::top>
 __device__ __forceinline__ uint32_t fp8_code(uint32_t bits, uint32_t r32)
 {
     using P = Fp8<FMT>;
-    return fp8_sign(bits) | fp8_finish<P::top>(bits, sr_fp8_magnitude<P::mb, P::ef>(bits, r32));
+    return fp8_sign(bits) | fp8_finish<TOP>(bits, sr_fp8_magnitude<P::mb, P::ef>(bits, r32));
 }
 
 // Four elements into one word.  `ranged`: some value of the wave lies in the format's top binade
@@ -339,12 +340,12 @@ __device__ __forceinline__ uint32_t fp8_code(uint32_t bits, uint32_t r32)
 // below the top binade: it adds the word's top 23 - mb bits to the dropped fraction cut to as
 // many bits and keeps the carry, subnormal results included (checked against the by-value
 // oracle on every binary32 encoding).
-template <int FMT>
+template <int FMT, uint32_t TOP = Fp8<FMT>::top>
 __device__ __forceinline__ uint32_t fp8_encode4(const uint32_t (&b)[4], const uint32_t (&r)[4], bool ranged)
 {
     if (ranged)
-        return fp8_code<FMT>(b[0], r[0]) | (fp8_code<FMT>(b[1], r[1]) << 8) |
-               (fp8_code<FMT>(b[2], r[2]) << 16) | (fp8_code<FMT>(b[3], r[3]) << 24);
+        return fp8_code<FMT, TOP>(b[0], r[0]) | (fp8_code<FMT, TOP>(b[1], r[1]) << 8) |
+               (fp8_code<FMT, TOP>(b[2], r[2]) << 16) | (fp8_code<FMT, TOP>(b[3], r[3]) << 24);
     int w = 0;
     if (FMT == 0) {
         w = __builtin_amdgcn_cvt_sr_fp8_f32(__uint_as_float(b[0]), (int)r[0], w, 0);
@@ -396,7 +397,8 @@ __device__ __forceinline__ void fp8_decode8(v2u codes, float inv_scale, float (&
 // included -- by the rule of fp8_encode4 (checked against that rule on 4e6 values per scale).  The
 // product as a binary32 multiplication, which is what the definition says, can differ from the
 // exact one only where it underflows, and there both give a zero with the product's sign.
-// `ranged`: the multiplication and the integer path.
+// `ranged`: the multiplication and the integer path, saturating: both formats collapse to their
+// largest finite value (an optimizer state must not hold an infinity: it would stay one).
 template <int FMT>
 __device__ __forceinline__ uint32_t fp8_encode4_scaled(const float (&x)[4], const uint32_t (&r)[4], float scale,
                                                        float inv_scale, bool ranged)
@@ -404,7 +406,7 @@ __device__ __forceinline__ uint32_t fp8_encode4_scaled(const float (&x)[4], cons
     if (ranged) {
         const uint32_t b[4] = {__float_as_uint(x[0] * scale), __float_as_uint(x[1] * scale),
                                __float_as_uint(x[2] * scale), __float_as_uint(x[3] * scale)};
-        return fp8_encode4<FMT>(b, r, true);
+        return fp8_encode4<FMT, (FMT == 0 ? 0x7Eu : 0x7Bu)>(b, r, true);
     }
     int w = 0;
     if (FMT == 0) {

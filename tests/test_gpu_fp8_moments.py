@@ -109,7 +109,7 @@ def test_fp8_moments_many_steps_with_clip_and_offsets():
 
 
 def test_fp8_moments_top_of_range_and_nan_gradients():
-    """Scales chosen too large on purpose: m saturates at 448, v reaches infinity; NaN and infinite
+    """Scales chosen too large on purpose: m saturates at 448 and v at 57344; NaN and infinite
     gradients; every wave holds some of each, so the integer path and the conversion instruction
     both run (waves of the second tensor hold nothing large)."""
     st = State([512 * 3, 512 * 2], [(22, 44), (12, 30)], seed=8, codes="zero")
@@ -117,7 +117,8 @@ def test_fp8_moments_top_of_range_and_nan_gradients():
     for t in (1, 2, 3):
         st.step(t, 5, g_scale=2.0 ** 12, rng=rng)
         st.check(f"step {t}")
-    assert (st.host[0]["m"] & 0x7F == 0x7E).any() and (st.host[0]["v"] == 0x7C).any()
+    assert (st.host[0]["m"] & 0x7F == 0x7E).any() and (st.host[0]["v"] == 0x7B).any()
+    assert not (st.host[0]["v"] & 0x7F == 0x7C).any()             # no infinity is ever stored
     g = st.host[0]["g"].copy()
     g[5], g[700], g[1300] = 0x7FC0, 0x7F80, 0xFF80            # NaN, +inf, -inf
     st.host[0]["g"] = g
