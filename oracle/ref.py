@@ -8,7 +8,6 @@ BF16 data are numpy uint16 arrays holding the bit patterns; FP32 data are
 numpy float32 arrays.  All arrays must be C-contiguous.
 """
 import ctypes as C
-import os
 
 import numpy as np
 

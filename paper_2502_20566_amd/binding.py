@@ -6,7 +6,7 @@ library is missing or a call fails, an exception is raised.
 """
 import ctypes as C
 import os
-from typing import List, Optional, Sequence, Tuple
+from typing import Optional, Sequence, Tuple
 
 import torch  # imported before the library so that one HIP runtime serves both
 

@@ -12,7 +12,7 @@ scale), LayerNorm gains are 1, biases are 0, and gradients are zero-mean noise
 of a stated standard deviation with an optional fraction of large outliers.
 No dataset, checkpoint or benchmark item is involved.
 """
-from dataclasses import dataclass, field
+from dataclasses import dataclass
 from typing import List, Optional, Tuple
 
 import torch

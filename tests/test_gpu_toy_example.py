@@ -6,7 +6,6 @@ with nearest rounding never leaves x0 (every update is far below half a BF16 spa
 SR gets there but later on average: a walk that is behind when the learning rate has decayed
 waits on ever smaller updates, which gives the arrival times a heavy right tail.
 """
-import numpy as np
 import pytest
 import torch
 
