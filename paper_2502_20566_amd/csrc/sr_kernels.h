@@ -603,7 +603,7 @@ __device__ __forceinline__ bool update_lane(LaneRegs<N>& L, const StepScalars& S
     float y[N], sum[N], mh[N], ra[N];
 #pragma unroll
     for (int j = 0; j < N; ++j) moments_elem<CLIP>(S, variant, c, L.g[j], L.m[j], L.v[j], mh[j], ra[j]);
-    // Where the kernel is bound by instruction issue (8-bit moments) the square roots and divisions
+    // Where the arithmetic is not hidden behind the memory time (8-bit moments) the square roots and divisions
     // of a wave whose operands all lie in the short forms' domains take those forms; zeros, tiny,
     // huge, infinite and negative root arguments and NaNs send the whole wave through sqrtf and the
     // full division (a NaN numerator alone does not: it gives a NaN either way).
