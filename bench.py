@@ -351,10 +351,10 @@ def main():
     # ceiling of the access pattern on these very buffers: the step's 4-read/3-write traffic with
     # no arithmetic (BF16 strategies without an auxiliary tensor, flat or list alike)
     ceiling = None
-    if MODES[mode][3] == 14:
+    if MODES[mode][3] == 14 or fp8_exps is not None:
         def probe():
             for p_, g_, m_, v_ in zip(params, grads, ms, vs):
-                B.sr_stream_probe(p_, g_, m_, v_)
+                (B.sr_stream_probe_fp8m if fp8_exps is not None else B.sr_stream_probe)(p_, g_, m_, v_)
         probe()
         torch.cuda.synchronize()
         reps = max(3, min(args.steps, 10))
@@ -366,8 +366,9 @@ def main():
             pe1[i].record()
         torch.cuda.synchronize()
         probe_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(pe0, pe1)]))
-        ceiling = {"kind": "4-read/3-write copy of the same buffers, no arithmetic (sr_stream_probe)",
-                   "ms": probe_ms, "GBps": 14 * numel / (probe_ms * 1e-3) / 1e9}
+        ceiling = {"kind": "the step's reads and writes of the same buffers, no arithmetic (sr_stream_probe" +
+                           ("_fp8m: 6 B read, 4 B written per element)" if fp8_exps is not None else ": 8 B read, 6 B written per element)"),
+                   "ms": probe_ms, "GBps": MODES[mode][3] * numel / (probe_ms * 1e-3) / 1e9}
 
     # a plain device copy of the same footprint per buffer (1 read : 1 write), torch's copy kernel
     device_copy = None

@@ -277,6 +277,14 @@ uint64_t sr_workspace_bytes(uint32_t n_tensors, uint64_t total_numel);
  */
 int sr_stream_probe(void* d_p, const void* d_g, void* d_m, void* d_v, uint64_t numel, void* stream);
 
+/*
+ * The same measurement aid for the step with 8-bit moments (SR_FLAG_FP8_MOMENTS:
+ * 6 bytes read, 4 written per element): reads BF16 p, g and the one-byte code
+ * arrays d_m8, d_v8 and writes p, m8, v8 back UNCHANGED.  p, g 2-byte aligned;
+ * only whole 8-element blocks are touched.
+ */
+int sr_stream_probe_fp8m(void* d_p, const void* d_g, void* d_m8, void* d_v8, uint64_t numel, void* stream);
+
 /* Static description of an SR_ERR_* code. */
 const char* sr_strerror(int code);
 

@@ -30,7 +30,7 @@ SR_ACC_FIRST = 2
 SR_FP8_E4M3, SR_FP8_E5M2 = 0, 1
 
 EXPORTS = ("sr_cast_f32_bf16", "sr_cast_f32_fp8", "grad_global_norm", "grad_sum_of_squares", "sr_adamw_step", "sr_workspace_bytes",
-           "sr_grad_accumulate", "sr_accumulate_workspace_bytes", "sr_stream_probe",
+           "sr_grad_accumulate", "sr_accumulate_workspace_bytes", "sr_stream_probe", "sr_stream_probe_fp8m",
            "sr_strerror", "sr_last_hip_error", "sr_version", "sr_debug_set_launch_limit")
 
 
@@ -92,6 +92,8 @@ def lib():
         L.sr_accumulate_workspace_bytes.restype = C.c_uint64
         L.sr_stream_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
         L.sr_stream_probe.restype = C.c_int
+        L.sr_stream_probe_fp8m.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+        L.sr_stream_probe_fp8m.restype = C.c_int
         L.sr_workspace_bytes.argtypes = [C.c_uint32, C.c_uint64]
         L.sr_workspace_bytes.restype = C.c_uint64
         L.sr_strerror.argtypes = [C.c_int]
@@ -266,6 +268,22 @@ def sr_adamw_step(tl: TensorList, hyper: dict, step: int, seed: int, flags: int 
                              _stream_handle(stream))
     if rc != SR_OK:
         raise SrError(rc, "sr_adamw_step")
+
+
+def sr_stream_probe_fp8m(p: torch.Tensor, g: torch.Tensor, m8: torch.Tensor, v8: torch.Tensor, stream=None) -> None:
+    """6-read/4-write pass over BF16 p, g and one-byte m8, v8 that leaves the data unchanged (measurement aid)."""
+    for name, t in (("p", p), ("g", g)):
+        _check_dev(t, torch.bfloat16, name)
+    for name, t in (("m8", m8), ("v8", v8)):
+        if t.element_size() != 1:
+            raise ValueError(f"{name} must hold one byte per element")
+        _check_dev(t, t.dtype, name)
+    if not (p.numel() == g.numel() == m8.numel() == v8.numel()):
+        raise ValueError("p, g, m8, v8 differ in size")
+    rc = lib().sr_stream_probe_fp8m(p.data_ptr(), g.data_ptr(), m8.data_ptr(), v8.data_ptr(), p.numel(),
+                                    _stream_handle(stream))
+    if rc != SR_OK:
+        raise SrError(rc, "sr_stream_probe_fp8m")
 
 
 def sr_stream_probe(p: torch.Tensor, g: torch.Tensor, m: torch.Tensor, v: torch.Tensor, stream=None) -> None:

@@ -983,6 +983,26 @@ __global__ __launch_bounds__(kThreads) void stream_probe_kernel(uint16_t* __rest
     buf_store16<true>(rv, off, V ^ k);
 }
 
+// The same for the step with 8-bit moments: 16 bytes of p and g and 8 bytes of the m and v codes
+// read per lane, 16 bytes of p and 8 of each code array written back unchanged.
+__global__ __launch_bounds__(kThreads) void stream_probe_fp8m_kernel(uint16_t* __restrict__ p, const uint16_t* __restrict__ g,
+                                                                    uint8_t* __restrict__ m, uint8_t* __restrict__ v,
+                                                                    uint64_t nblk, uint64_t wg0, uint32_t mask)
+{
+    const uint64_t b0 = ((uint64_t)blockIdx.x + wg0) * kThreads, b = b0 + threadIdx.x;
+    if (b >= nblk) return;
+    const int64_t e0 = (int64_t)(b0 << 3);
+    const rsrc_t rp = chunk_rsrc<uint16_t>(p, e0, kThreads * 8u), rg = chunk_rsrc<uint16_t>(g, e0, kThreads * 8u);
+    const rsrc_t rm = chunk_rsrc<uint8_t>(m, e0, kThreads * 8u), rv = chunk_rsrc<uint8_t>(v, e0, kThreads * 8u);
+    const v4u P = buf_load16<true>(rp, threadIdx.x * 16u), G = buf_load16<true>(rg, threadIdx.x * 16u);
+    const v2u M = buf_load8<true>(rm, threadIdx.x * 8u), V = buf_load8<true>(rv, threadIdx.x * 8u);
+    const v4u k = G & mask;
+    v2u k2; k2.x = k.x; k2.y = k.y;
+    buf_store16<true>(rp, threadIdx.x * 16u, P ^ k);
+    buf_store8<true>(rm, threadIdx.x * 8u, M ^ k2);
+    buf_store8<true>(rv, threadIdx.x * 8u, V ^ k2);
+}
+
 // ----------------------------------------------------------------------- standalone SR cast
 
 // A lane owns half a block (4 elements) at a time: one 16-byte load and one 8-byte store per lane,

@@ -153,6 +153,24 @@ int sr_stream_probe(void* d_p, const void* d_g, void* d_m, void* d_v, uint64_t n
     return SR_OK;
 }
 
+int sr_stream_probe_fp8m(void* d_p, const void* d_g, void* d_m8, void* d_v8, uint64_t numel, void* stream)
+{
+    const uint64_t nblk = numel >> 3;                 // whole blocks only; a tail is left untouched
+    if (nblk == 0) return SR_OK;
+    if (!d_p || !d_g || !d_m8 || !d_v8) return SR_ERR_NULL;
+    if (!aligned(d_p, 2) || !aligned(d_g, 2)) return SR_ERR_ALIGN;
+    const uint64_t wgs = (nblk + kThreads - 1) / kThreads;
+    const uint32_t mg = max_grid(kThreads);
+    for (uint64_t w0 = 0; w0 < wgs; w0 += mg) {
+        const uint32_t grid = (uint32_t)(wgs - w0 < mg ? wgs - w0 : mg);
+        const hipError_t e = launch(stream_probe_fp8m_kernel, grid, kThreads, static_cast<hipStream_t>(stream),
+                                    static_cast<uint16_t*>(d_p), static_cast<const uint16_t*>(d_g),
+                                    static_cast<uint8_t*>(d_m8), static_cast<uint8_t*>(d_v8), nblk, w0, 0u);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return SR_OK;
+}
+
 const char* sr_strerror(int code)
 {
     switch (code) {

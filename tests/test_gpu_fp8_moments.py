@@ -204,3 +204,23 @@ def test_optimizer_object_with_8_bit_moments_and_resume():
         SRAdamW(params, strategy="fp8_moments")
     with pytest.raises(ValueError):
         SRAdamW(params, strategy="sr", fp8_exponents=exps)
+
+
+def test_stream_probe_of_the_8_bit_moment_pattern_leaves_the_data_unchanged():
+    n = 512 * 7 + 13                                             # whole blocks only: the tail is not touched either
+    p = (torch.randn(n, device=DEV) * 0.01).to(torch.bfloat16)
+    g = (torch.randn(n, device=DEV) * 0.01).to(torch.bfloat16)
+    m8 = torch.randint(0, 256, (n,), dtype=torch.uint8, device=DEV)
+    v8 = torch.randint(0, 128, (n,), dtype=torch.uint8, device=DEV)
+    before = [t.clone() for t in (p, g, m8, v8)]
+    B.sr_stream_probe_fp8m(p, g, m8, v8)
+    B.lib().sr_debug_set_launch_limit(3)                          # and cut into several launches
+    try:
+        B.sr_stream_probe_fp8m(p, g, m8, v8)
+    finally:
+        B.lib().sr_debug_set_launch_limit(0)
+    torch.cuda.synchronize()
+    for t, b in zip((p, g, m8, v8), before):
+        assert torch.equal(t.view(torch.uint8), b.view(torch.uint8))
+    e = torch.empty(0, dtype=torch.bfloat16, device=DEV)
+    B.sr_stream_probe_fp8m(e, e, torch.empty(0, dtype=torch.uint8, device=DEV), torch.empty(0, dtype=torch.uint8, device=DEV))
