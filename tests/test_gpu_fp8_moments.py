@@ -2,6 +2,8 @@
 a power-of-two scale per tensor) against the CPU oracle, through the C ABI: parameters and both code
 arrays bit for bit.  NaN codes are compared as NaN codes (sign and payload of a NaN that arithmetic
 produced are open), the parameter's NaNs as NaNs."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -55,7 +57,8 @@ class State:
         self.tl = B.TensorList([d["p"] for d in self.dev], [d["g"] for d in self.dev], [d["m"] for d in self.dev],
                                [d["v"] for d in self.dev], False, self.ids, self.offs, fp8_exponents=exps)
 
-    def step(self, t, seed, g_scale, flags=0, norm=None, max_norm=0.0, rng=None):
+    def step(self, t, seed, g_scale, flags=0, norm=None, max_norm=0.0, rng=None, hyper=None):
+        HYP = hyper or globals()["HYP"]
         rng = rng or np.random.default_rng(1000 + t)
         for h, d, (me, _) in zip(self.host, self.dev, self.exps):
             g = bf16_bits(rng.standard_normal(h["p"].size) * g_scale * 2.0 ** -me)
@@ -142,6 +145,38 @@ def test_fp8_moments_extreme_scales(exps, g_scale):
     for t in (1, 2, 3):
         st.step(t, 77, g_scale=g_scale, rng=rng)
         st.check(f"exponents {exps}, step {t}")
+
+
+def test_fp8_moments_randomized_cases():
+    """Thirty seeded random cases: list length, sizes, misalignment, element offsets, tensor ids, scale
+    exponents, parameter rounding and variant flags, clipping, hyper-parameters including the corners
+    (beta = 0, eps = 0, lr = 0, large lr, late steps), every code as incoming state."""
+    rng = np.random.default_rng(4242)
+    for case in range(int(os.environ.get("SR_TEST_CASES", "30"))):      # more cases on request
+        flags = 0
+        if rng.random() < 0.3:
+            flags |= B.SR_FLAG_RNE_PARAMS
+        if rng.random() < 0.3:
+            flags |= B.SR_FLAG_EPS_IN_ROOT
+        if rng.random() < 0.3:
+            flags |= B.SR_FLAG_DIV_BIAS
+        n_t = int(rng.integers(1, 70))
+        sizes = [int(rng.choice([1, 5, 8, 64, 257, 512, 1000, 4099, 9000])) for _ in range(n_t)]
+        exps = [(int(rng.integers(-20, 41)), int(rng.integers(-20, 61))) for _ in range(n_t)]
+        offs = [int(rng.choice([0, 0, 8, 3, 1 << 32, (1 << 40) + 5])) for _ in range(n_t)]
+        ids = [int(rng.integers(0, 1 << 32)) for _ in range(n_t)]
+        st = State(sizes, exps, seed=900 + case, offsets=offs, ids=ids, views=int(rng.integers(0, 4)))
+        hyper = dict(lr=float(rng.choice([0.0, 1e-5, 6e-4, 3e-3, 0.5])),
+                     beta1=float(rng.choice([0.0, 0.5, 0.9, 0.99])),
+                     beta2=float(rng.choice([0.0, 0.95, 0.999, 0.99999])),
+                     eps=float(rng.choice([0.0, 1e-12, 1e-8, 1e-3])),
+                     weight_decay=float(rng.choice([0.0, 0.1, 1.0])))
+        t = int(rng.choice([1, 2, 17, 1000, 123456, 2 ** 32 - 1]))
+        clip = None if rng.random() < 0.5 else float(rng.choice([1e-3, 0.05, 1.0, 100.0]))
+        norm = None if clip is None else float(rng.choice([1e-4, 0.3, 7.0]))
+        st.step(t, int(rng.integers(0, 1 << 62)), g_scale=float(rng.choice([0.25, 4.0, 64.0])), flags=flags,
+                norm=norm, max_norm=clip or 0.0, rng=rng, hyper=hyper)
+        st.check(f"case {case} flags {flags} hyper {hyper} t {t} clip {clip}")
 
 
 def test_fp8_moments_arguments():

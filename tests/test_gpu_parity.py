@@ -6,6 +6,8 @@ within relative 1e-6 (its binary64 sum runs in a different order on the two side
 NaNs produced by arithmetic are compared as NaNs (IEEE 754 leaves their sign and payload open);
 NaNs that are merely cast keep specified bits and are compared exactly.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -623,7 +625,7 @@ def test_adamw_randomized_cases():
     strategies = [0, B.SR_FLAG_RNE_MOMENTS, B.SR_FLAG_RNE_PARAMS | B.SR_FLAG_RNE_MOMENTS, B.SR_FLAG_RNE_PARAMS,
                   B.SR_FLAG_FP32_MOMENTS, B.SR_FLAG_FP32_MOMENTS | B.SR_FLAG_RNE_PARAMS,
                   B.SR_FLAG_KAHAN, B.SR_FLAG_MASTER_FP32 | B.SR_FLAG_FP32_MOMENTS]
-    for case in range(40):
+    for case in range(int(os.environ.get("SR_TEST_CASES", "40"))):     # more cases on request
         flags = strategies[case % len(strategies)]
         if rng.random() < 0.3:
             flags |= B.SR_FLAG_EPS_IN_ROOT
