@@ -64,3 +64,33 @@ def test_fp8_rounding_is_monotone_and_commutes_with_the_sign(fmt, lo_exp, hi_exp
         mags = np.array([ref.fp8_decode(ref.sr_round_fp8(x, int(r), fmt) & 0x7F, fmt) for r in draws])
         mags = np.where(np.isinf(mags), 1e30, mags)                # E5M2's infinity is the top of the order
         assert np.all(np.diff(mags) >= 0) and np.unique(mags).size <= 2
+
+
+@pytest.mark.parametrize("flags", [0, ref.FLAG_RNE_MOMENTS, ref.FLAG_RNE_PARAMS | ref.FLAG_RNE_MOMENTS,
+                                   ref.FLAG_EPS_IN_ROOT, ref.FLAG_DIV_BIAS])
+def test_adamw_step_commutes_with_a_sign_flip_of_p_g_and_m(flags):
+    """Algorithm 1 is odd in (x, g, m) for a fixed v: flipping their signs flips the new parameter and
+    first moment and leaves the second moment alone, unrounded and -- the roundings being sign-symmetric
+    for a given draw -- rounded as well.  A wrong sign on the weight-decay term, on the update direction
+    or inside a rounding breaks it."""
+    n = 4000
+    rng = np.random.default_rng(9)
+    bits = lambda x: (np.asarray(x, np.float32).view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    p, g, m = bits(rng.standard_normal(n) * 0.02), bits(rng.standard_normal(n) * 1e-3), bits(rng.standard_normal(n) * 1e-3)
+    v = bits(rng.random(n) * 1e-6)
+    hyper = dict(lr=3e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    flip = np.uint16(0x8000)
+    for t in (1, 50):
+        s = ref.adamw_scalars(step=t, norm=2.0, max_norm=1.0, **hyper)
+        y, m1, v1 = ref.adamw_unrounded(p, g, m, v, s, flags)
+        yn, m1n, v1n = ref.adamw_unrounded(p ^ flip, g ^ flip, m ^ flip, v, s, flags)
+        assert np.array_equal(yn.view(np.uint32), y.view(np.uint32) ^ np.uint32(1 << 31))
+        assert np.array_equal(m1n.view(np.uint32), m1.view(np.uint32) ^ np.uint32(1 << 31))
+        assert np.array_equal(v1n.view(np.uint32), v1.view(np.uint32))
+        a = dict(p=p.copy(), g=g, m=m.copy(), v=v.copy())
+        b = dict(p=p ^ flip, g=g ^ flip, m=m ^ flip, v=v.copy())
+        ref.sr_adamw_step([a], hyper, t, 77, flags, norm=2.0, max_norm=1.0)
+        ref.sr_adamw_step([b], hyper, t, 77, flags, norm=2.0, max_norm=1.0)
+        assert np.array_equal(b["p"], a["p"] ^ flip) and np.array_equal(b["m"], a["m"] ^ flip)
+        assert np.array_equal(b["v"], a["v"])
+        assert np.count_nonzero(a["p"] != p) > n // 10            # the step moved something
