@@ -56,14 +56,17 @@ def algorithmic_bytes_per_element(mode, clip) -> int:
     return MODES[mode][3] + (2 if clip is not None else 0)
 
 
-def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags, fp8_exps=None):
+def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags, fp8_exps=None, norm=None):
     """Time the CPU oracle (as it stands) on a bounded window of the same workload and check the
     GPU against it on that window.  `state` holds flat device tensors p, g, m, v, aux (first
-    tensor; aux may be None).  `flags`: the step's flag bits (same values on both sides)."""
+    tensor; aux may be None).  `flags`: the step's flag bits (same values on both sides).
+    `norm`: the gradient norm the device computed for this step when the config clips (the oracle
+    takes the same binary32 value, so the clip scale is the same on both sides), else None."""
     import numpy as np
     from oracle import ref
     p, g, m, v, aux = state
     threads = min(ref.max_threads(), os.cpu_count() or 1)
+    max_norm = cfg.clip if norm is not None else 0.0
 
     def window(lo, n):
         def cp(t):
@@ -83,7 +86,7 @@ def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags, fp8_exp
     # would mostly lose; Section 2.2), from the oracle's unrounded result on this window
     sub_ulp = None
     if aux is None:
-        sc = ref.adamw_scalars(step=step_no, **cfg.hyper)
+        sc = ref.adamw_scalars(step=step_no, norm=norm, max_norm=max_norm, **cfg.hyper)
         if fp8_exps is not None:
             y, _, _ = ref.adamw_unrounded_fp8m(w0["p"], w0["g"], w0["m"], w0["v"], sc, *fp8_exps)
         else:
@@ -91,18 +94,18 @@ def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags, fp8_exp
         p32 = ref.bf16_bits_to_f32(w0["p"])
         sub_ulp = float(np.mean(np.abs(y.astype(np.float64) - p32) < np.spacing(np.abs(p32)).astype(np.float64) * 65536.0))
     t0 = time.perf_counter()
-    ref.sr_adamw_step([w0], cfg.hyper, step_no, seed, flags, nthreads=1)
+    ref.sr_adamw_step([w0], cfg.hyper, step_no, seed, flags, norm=norm, max_norm=max_norm, nthreads=1)
     rate1 = n0 / (time.perf_counter() - t0)
     w0 = window(0, n0)
     t0 = time.perf_counter()
-    ref.sr_adamw_step([w0], cfg.hyper, step_no, seed, flags, nthreads=threads)
+    ref.sr_adamw_step([w0], cfg.hyper, step_no, seed, flags, norm=norm, max_norm=max_norm, nthreads=threads)
     rate0 = n0 / (time.perf_counter() - t0)
     n = int(min(p.numel(), max(n0, rate0 * seconds), 3 << 30))
     n -= n % 8
     lo = ((p.numel() - n) // 2) & ~7                      # a window from the middle of the buffer
     w = window(lo, n)
     t0 = time.perf_counter()
-    ref.sr_adamw_step([w], cfg.hyper, step_no, seed, flags, nthreads=threads)
+    ref.sr_adamw_step([w], cfg.hyper, step_no, seed, flags, norm=norm, max_norm=max_norm, nthreads=threads)
     dt = time.perf_counter() - t0
     return dict(value=n / dt, unit="params/s", cores=threads, kind="oracle", one_thread_value=rate1,
                 sub_ulp_update_fraction=sub_ulp,
@@ -291,23 +294,30 @@ def main():
     cpu = None
     check = None
     if not args.no_cpu_baseline:
+        nv = None
+        if cfg.clip is not None:
+            # the norm of this step's gradients as the device computes it: the oracle clips with
+            # the same binary32 value
+            B.grad_global_norm(tl, norm, ws)
+            torch.cuda.synchronize()
+            nv = float(norm.item())
         cpu, check = cpu_baseline(W, B, torch, cfg, (params[0], grads[0], ms[0], vs[0],
                                                      None if aux is None else aux[0]), t, cfg.seed,
-                                  args.cpu_seconds, flags, fp8_exps)
-        if cfg.clip is not None:
-            cpu["sample"] += " (oracle timed without the clip scale)"
+                                  args.cpu_seconds, flags, fp8_exps, nv)
 
     # the step the oracle reproduced, then the parity check of that window
     parity = "not checked"
-    if check is not None and cfg.clip is None:
+    if check is not None:
         one_step(t)
         torch.cuda.synchronize()
         lo, n, w = check
         got_p = W.bf16_to_u16_numpy(params[0][lo:lo + n])
         bad = int((got_p != w["p"]).sum())
         if fp32_moments or fp8_exps is not None:
-            bad += int((ms[0][lo:lo + n].cpu().numpy() != w["m"]).sum())
-            bad += int((vs[0][lo:lo + n].cpu().numpy() != w["v"]).sum())
+            bad += int((ms[0][lo:lo + n].cpu().numpy().view(np.uint32 if fp32_moments else np.uint8)
+                        != w["m"].view(np.uint32 if fp32_moments else np.uint8)).sum())
+            bad += int((vs[0][lo:lo + n].cpu().numpy().view(np.uint32 if fp32_moments else np.uint8)
+                        != w["v"].view(np.uint32 if fp32_moments else np.uint8)).sum())
         else:
             bad += int((W.bf16_to_u16_numpy(ms[0][lo:lo + n]) != w["m"]).sum())
             bad += int((W.bf16_to_u16_numpy(vs[0][lo:lo + n]) != w["v"]).sum())

@@ -1,8 +1,10 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration
-bench.py times.  Configs 2 and 3: every element of every tensor against the oracle.  Configs 4 and
-5: the GPU updates the whole parameter set; the oracle follows seeded windows of it through every
-step (the update is element-wise and the RNG is random-access, so a window with its element offset
-is self-contained), including windows that straddle element index 2^32.
+bench.py times.  Configs 2 and 3: every element of every tensor against the oracle after every one
+of their 10 steps.  Configs 4 and 5: the GPU updates the whole parameter set; the oracle follows
+seeded windows of it -- the first and last 2^20 elements of every tensor and 64 random windows of
+2^20 elements, for config 5 also windows that straddle element index 2^32 -- through every step from
+step 1, compared after every step (the update is element-wise and the RNG is random-access, so a
+window with its element offset is self-contained).
 """
 import numpy as np
 import pytest
@@ -30,33 +32,60 @@ def same_bf16(got, want):
 
 
 class Windows:
-    """Host copies of slices [lo, lo+n) of some tensors, advanced by the oracle."""
+    """Host copies of slices [lo, lo+n) of some tensors, advanced by the oracle.  The slices of one
+    array live back to back in one host array (one device gather and one download per array and
+    step); the oracle sees each slice as a tensor of its own with its element offset."""
 
     def __init__(self, params, ms, vs, picks, fp32):
         self.picks = picks                      # list of (tensor index, lo, n)
         self.fp32 = fp32
-        self.host = [dict(p=to_np(params[i][lo:lo + n]), m=to_np(ms[i][lo:lo + n]),
-                          v=to_np(vs[i][lo:lo + n]), tensor_id=i, elem_offset=lo)
-                     for i, lo, n in picks]
+        self.p, self.m, self.v = self.gather(params), self.gather(ms), self.gather(vs)
+        self.host, at = [], 0
+        for i, lo, n in picks:
+            self.host.append(dict(p=self.p[at:at + n], m=self.m[at:at + n], v=self.v[at:at + n],
+                                  tensor_id=i, elem_offset=lo))
+            at += n
+        self.numel = at
+
+    def gather(self, tensors):
+        return to_np(torch.cat([tensors[i][lo:lo + n] for i, lo, n in self.picks]))
 
     def step(self, grads, hyper, t, seed, norm, max_norm):
+        g, at = self.gather(grads), 0
         for h, (i, lo, n) in zip(self.host, self.picks):
-            h["g"] = to_np(grads[i][lo:lo + n])
+            h["g"] = g[at:at + n]
+            at += n
         flags = ref.FLAG_FP32_MOMENTS if self.fp32 else 0
         ref.sr_adamw_step(self.host, hyper, t, seed, flags, norm=norm, max_norm=max_norm)
 
     def mismatches(self, params, ms, vs):
-        bad = 0
-        for h, (i, lo, n) in zip(self.host, self.picks):
-            bad += same_bf16(to_np(params[i][lo:lo + n]), h["p"])
-            if self.fp32:
-                gm, gv = to_np(ms[i][lo:lo + n]), to_np(vs[i][lo:lo + n])
-                bad += int((gm.view(np.uint32) != h["m"].view(np.uint32)).sum())
-                bad += int((gv.view(np.uint32) != h["v"].view(np.uint32)).sum())
-            else:
-                bad += same_bf16(to_np(ms[i][lo:lo + n]), h["m"])
-                bad += same_bf16(to_np(vs[i][lo:lo + n]), h["v"])
+        bad = same_bf16(self.gather(params), self.p)
+        gm, gv = self.gather(ms), self.gather(vs)
+        if self.fp32:
+            bad += int((gm.view(np.uint32) != self.m.view(np.uint32)).sum())
+            bad += int((gv.view(np.uint32) != self.v.view(np.uint32)).sum())
+        else:
+            bad += same_bf16(gm, self.m) + same_bf16(gv, self.v)
         return bad
+
+
+def window_picks(sizes, rng, width, n_random):
+    """The windows followed through a full-size run: the first and the last `width` elements of
+    every tensor (the whole tensor when it is no longer than two widths) and n_random windows of
+    `width` elements at seeded random places, drawn over all elements of the tensors longer than
+    one width (so a tensor's share of them follows its size)."""
+    picks = []
+    for i, n in enumerate(sizes):
+        if n <= 2 * width:
+            picks.append((i, 0, n))
+        else:
+            picks += [(i, 0, width), (i, n - width, width)]
+    big = [(i, n) for i, n in enumerate(sizes) if n > width]
+    weights = np.array([n for _, n in big], dtype=np.float64)
+    for k in rng.choice(len(big), size=n_random, p=weights / weights.sum()):
+        i, n = big[int(k)]
+        picks.append((i, int(rng.integers(0, n - width + 1)), width))
+    return picks
 
 
 def setup(cfg):
@@ -111,22 +140,24 @@ def test_config2_full_buffers_ten_steps():
 
 
 def test_config3_full_buffers_clip():
-    full_compare(W.config(3), 3, True)
+    """All 10 steps of the configuration, every element of every tensor after every step; the
+    device's norm against the oracle's at every step."""
+    cfg = W.config(3)
+    assert cfg.steps == 10
+    full_compare(cfg, cfg.steps, True)
 
 
 def test_config4_full_size_windows_fp32_moments_clip():
+    """The whole 2.65e9-element list is updated on the GPU; the oracle follows the first and the
+    last 2^20 elements of every one of the 388 tensors (whole tensors up to 2^21 elements) and 64
+    random windows of 2^20 elements through all 5 steps, compared after every step."""
     cfg = W.config(4)
     params, grads, ms, vs, tl, norm, ws = setup(cfg)
-    rng = np.random.default_rng(4)
-    picks = []
-    for i in list(range(0, len(params), 29)) + [len(params) - 1]:
-        n = params[i].numel()
-        w = min(n, 1 << 15)
-        picks += [(i, 0, w), (i, n - w, w)]
-        if n > (1 << 20):
-            lo = int(rng.integers(0, n - (1 << 16)))
-            picks.append((i, lo, 1 << 16))
+    assert len(params) == 388 and cfg.steps == 5
+    picks = window_picks([p.numel() for p in params], np.random.default_rng(4), 1 << 20, 64)
+    assert {i for i, _, _ in picks} == set(range(len(params)))
     win = Windows(params, ms, vs, picks, True)
+    assert win.numel > 300 * (1 << 20)
     for t in range(1, cfg.steps + 1):
         W.fill_grads(grads, W.data_seed(4, t), cfg.grad_std)
         nv = gpu_step(cfg, tl, t, norm, ws)
@@ -141,23 +172,25 @@ def test_config4_full_size_windows_fp32_moments_clip():
 
 
 def test_config5_full_size_windows_through_warm_start():
+    """The 6.7B flat buffer through its 100 warm steps and the timed step 101: the oracle follows
+    the first and last 2^20 elements, windows that straddle element index 2^32 (where the counter's
+    low word wraps), a few ragged ones, and 64 random windows of 2^20 elements; every window is
+    compared after every step."""
     cfg = W.config(5)
     params, grads, ms, vs, tl, norm, ws = setup(cfg)
     n = params[0].numel()
     assert n == 6658465792
-    rng = np.random.default_rng(5)
-    w = 1 << 17
-    picks = [(0, 0, w), (0, n - w, w), (0, (1 << 32) - w // 2, w), (0, (1 << 32) + 3, w - 5),
-             (0, (1 << 32) - 1, 2), (0, 3 * (1 << 31) - 77, w), (0, n - 7, 7), (0, 12345, 999)]
-    picks += [(0, int(rng.integers(0, n - w)), w) for _ in range(16)]
+    w = 1 << 20
+    picks = window_picks([n], np.random.default_rng(5), w, 64)
+    picks += [(0, (1 << 32) - w // 2, w), (0, (1 << 32) + 3, w - 5), (0, (1 << 32) - 1, 2),
+              (0, 3 * (1 << 31) - 77, w), (0, n - 7, 7), (0, 12345, 999)]
     win = Windows(params, ms, vs, picks, False)
     steps = cfg.warm_steps + 1
     for t in range(1, steps + 1):
         W.fill_grads(grads, W.data_seed(5, t), cfg.grad_std)
         gpu_step(cfg, tl, t, norm, ws)
         win.step(grads, cfg.hyper, t, cfg.seed, None, 0.0)
-        if t in (1, 2, 50, steps):
-            assert win.mismatches(params, ms, vs) == 0, f"config 5 step {t}"
+        assert win.mismatches(params, ms, vs) == 0, f"config 5 step {t}"
     # after the warm start the second moment is alive and updates are far below a BF16 spacing
     v_end = ref.bf16_bits_to_f32(win.host[0]["v"])
     assert float((v_end > 0).mean()) > 0.99
