@@ -49,6 +49,11 @@ extern "C" {
                                   starting at any element of a larger buffer and keep the
                                   vector path                                             */
 #define SR_ERR_HIP       (-5)  /* a launch failed; see sr_last_hip_error()                */
+#define SR_ERR_SIZE      (-6)  /* the input needs more scratch than the static array of
+                                  grad_global_norm_static holds                           */
+
+/* bytes of the static device array behind grad_global_norm_static */
+#define SR_STATIC_SCRATCH_BYTES 1048576u
 
 /* flags of sr_adamw_step */
 #define SR_FLAG_FP32_MOMENTS 1u /* m, v are binary32 and stored unrounded; SR on p only
@@ -184,6 +189,25 @@ int sr_cast_f32_fp8(const float* d_src, void* d_dst, uint64_t n, uint32_t format
  */
 int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_norm_out,
                      void* d_workspace, uint64_t workspace_bytes, void* stream);
+
+/*
+ * grad_global_norm for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same kernels, same result bits; the partial sums go to a
+ * static device array inside the library (SR_STATIC_SCRATCH_BYTES per device
+ * that uses the library, held until the process ends) instead of a caller
+ * workspace, and the call allocates nothing.  The array holds one partial sum
+ * per 65536 gradient elements of each tensor (rounded up per tensor): lists
+ * that need more than SR_STATIC_SCRATCH_BYTES / 8 of them -- about 8.5e9
+ * elements -- are rejected with SR_ERR_SIZE and nothing is enqueued.  Nothing in
+ * the array has to start at zero (every partial sum that is read has been
+ * written by the same call).  All calls on one device share the array: calls
+ * that may run concurrently on one device (different streams) race; order
+ * them.  The first call on a device looks the array's address up in the
+ * runtime (no allocation): make that call outside a stream capture.
+ */
+int grad_global_norm_static(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_norm_out,
+                            void* stream);
 
 /*
  * The same two passes, leaving the binary64 sum of squares S itself in

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libsradamw.so")
 
 SR_OK = 0
-SR_ERR_NULL, SR_ERR_ARG, SR_ERR_WORKSPACE, SR_ERR_ALIGN, SR_ERR_HIP = -1, -2, -3, -4, -5
+SR_ERR_NULL, SR_ERR_ARG, SR_ERR_WORKSPACE, SR_ERR_ALIGN, SR_ERR_HIP, SR_ERR_SIZE = -1, -2, -3, -4, -5, -6
 SR_FLAG_FP32_MOMENTS = 1
 SR_FLAG_RNE_MOMENTS = 2
 SR_FLAG_RNE_PARAMS = 4
@@ -29,7 +29,7 @@ SR_ACC_FIRST = 2
 
 SR_FP8_E4M3, SR_FP8_E5M2 = 0, 1
 
-EXPORTS = ("sr_cast_f32_bf16", "sr_cast_f32_fp8", "grad_global_norm", "grad_sum_of_squares", "sr_adamw_step", "sr_workspace_bytes",
+EXPORTS = ("sr_cast_f32_bf16", "sr_cast_f32_fp8", "grad_global_norm", "grad_global_norm_static", "grad_sum_of_squares", "sr_adamw_step", "sr_workspace_bytes",
            "sr_grad_accumulate", "sr_accumulate_workspace_bytes", "sr_stream_probe", "sr_stream_probe_fp8m",
            "sr_strerror", "sr_last_hip_error", "sr_version", "sr_debug_set_launch_limit")
 
@@ -80,6 +80,8 @@ def lib():
         L.grad_global_norm.argtypes = [C.POINTER(SrTensor), C.c_uint32, C.c_void_p, C.c_void_p,
                                        C.c_uint64, C.c_void_p]
         L.grad_global_norm.restype = C.c_int
+        L.grad_global_norm_static.argtypes = [C.POINTER(SrTensor), C.c_uint32, C.c_void_p, C.c_void_p]
+        L.grad_global_norm_static.restype = C.c_int
         L.grad_sum_of_squares.argtypes = L.grad_global_norm.argtypes
         L.grad_sum_of_squares.restype = C.c_int
         L.sr_adamw_step.argtypes = [C.POINTER(SrTensor), C.c_uint32, C.POINTER(SrHyper), C.c_uint32,
@@ -234,6 +236,14 @@ def grad_global_norm(tl: TensorList, norm_out: torch.Tensor, workspace: torch.Te
                                 workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc != SR_OK:
         raise SrError(rc, "grad_global_norm")
+
+
+def grad_global_norm_static(tl: TensorList, norm_out: torch.Tensor, stream=None) -> None:
+    """grad_global_norm with the library's static scratch instead of a workspace (allocates nothing)."""
+    _check_dev(norm_out, torch.float32, "norm_out")
+    rc = lib().grad_global_norm_static(tl.array, tl.n, norm_out.data_ptr(), _stream_handle(stream))
+    if rc != SR_OK:
+        raise SrError(rc, "grad_global_norm_static")
 
 
 def grad_sum_of_squares(tl: TensorList, sumsq_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:

@@ -8,6 +8,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 namespace {
 
@@ -122,6 +123,37 @@ hipError_t launch_adamw_variant(uint32_t flags, bool clip, const AdamwBatch& b, 
     }
 }
 
+// Scratch of the entry point that allocates nothing (grad_global_norm_static): the partial sums
+// of the norm's first pass.  One copy per device that loads this library, held until the process
+// ends.  In host code the array's name is only a handle: its device address is looked up once per
+// device (with that device current) and only that address is passed to kernels.
+constexpr uint64_t kStaticPartials = SR_STATIC_SCRATCH_BYTES / sizeof(double);
+static __device__ __align__(256) unsigned char scratch[SR_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kMaxDevices] = {};
+
+// The current device's copy of `scratch`.  The first call on a device asks the runtime for the
+// symbol's address (no allocation; do it outside a stream capture); later calls read the table.
+int static_scratch(double** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return SR_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!p) return hip_fail(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = static_cast<double*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return SR_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -180,6 +212,7 @@ const char* sr_strerror(int code)
         case SR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case SR_ERR_ALIGN:     return "tensor pointer not aligned to its element size";
         case SR_ERR_HIP:       return "HIP launch failed (see sr_last_hip_error)";
+        case SR_ERR_SIZE:      return "the list needs more partial sums than the library's static scratch holds";
         default:               return "unknown error code";
     }
 }
@@ -230,8 +263,10 @@ int sr_cast_f32_fp8(const float* d_src, void* d_dst, uint64_t n, uint32_t format
     return SR_OK;
 }
 
+// Both norm entry points and the variant that brings its own scratch: `partials` is device memory
+// for `capacity` binary64 partial sums (the caller's workspace, or the library's static array).
 static int sum_of_squares(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_norm_out, double* d_sumsq_out,
-                          void* d_workspace, uint64_t workspace_bytes, void* stream)
+                          double* partials, uint64_t capacity, void* stream)
 {
     if (!d_norm_out && !d_sumsq_out) return SR_ERR_NULL;
     if (n_tensors && !tensors) return SR_ERR_NULL;
@@ -245,11 +280,10 @@ static int sum_of_squares(const sr_tensor_t* tensors, uint32_t n_tensors, float*
     }
     if (total_chunks > 0xFFFFFFFFull) return SR_ERR_ARG;
     if (total_chunks) {
-        if (!d_workspace || !aligned(d_workspace, 8)) return SR_ERR_WORKSPACE;
-        if (workspace_bytes < total_chunks * sizeof(double)) return SR_ERR_WORKSPACE;
+        if (!partials || !aligned(partials, 8)) return SR_ERR_WORKSPACE;
+        if (capacity < total_chunks) return SR_ERR_WORKSPACE;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    double* partials = static_cast<double*>(d_workspace);
 
     NormBatch batch;
     std::memset(&batch, 0, sizeof(batch));
@@ -290,13 +324,27 @@ static int sum_of_squares(const sr_tensor_t* tensors, uint32_t n_tensors, float*
 int grad_global_norm(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_norm_out,
                      void* d_workspace, uint64_t workspace_bytes, void* stream)
 {
-    return sum_of_squares(tensors, n_tensors, d_norm_out, nullptr, d_workspace, workspace_bytes, stream);
+    return sum_of_squares(tensors, n_tensors, d_norm_out, nullptr, static_cast<double*>(d_workspace),
+                          workspace_bytes / sizeof(double), stream);
 }
 
 int grad_sum_of_squares(const sr_tensor_t* tensors, uint32_t n_tensors, double* d_sumsq_out,
                         void* d_workspace, uint64_t workspace_bytes, void* stream)
 {
-    return sum_of_squares(tensors, n_tensors, nullptr, d_sumsq_out, d_workspace, workspace_bytes, stream);
+    return sum_of_squares(tensors, n_tensors, nullptr, d_sumsq_out, static_cast<double*>(d_workspace),
+                          workspace_bytes / sizeof(double), stream);
+}
+
+int grad_global_norm_static(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_norm_out, void* stream)
+{
+    uint64_t total_chunks = 0;
+    for (uint32_t i = 0; tensors && i < n_tensors; ++i)
+        total_chunks += (tensors[i].numel + kNormChunkElems - 1) / kNormChunkElems;
+    if (total_chunks > kStaticPartials) return SR_ERR_SIZE;
+    double* partials = nullptr;
+    const int rc = static_scratch(&partials);
+    if (rc != SR_OK) return rc;
+    return sum_of_squares(tensors, n_tensors, d_norm_out, nullptr, partials, kStaticPartials, stream);
 }
 
 uint64_t sr_accumulate_workspace_bytes(uint32_t n_tensors, uint64_t total_numel)

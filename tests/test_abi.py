@@ -86,8 +86,8 @@ def test_header_is_plain_c_and_struct_layouts_match_the_binding(tmp_path):
 
 def test_strerror_covers_all_codes():
     L = B.lib()
-    msgs = {c: L.sr_strerror(c).decode() for c in (0, -1, -2, -3, -4, -5, -99)}
-    assert len(set(msgs.values())) == 7 and msgs[0] == "ok"
+    msgs = {c: L.sr_strerror(c).decode() for c in (0, -1, -2, -3, -4, -5, -6, -99)}
+    assert len(set(msgs.values())) == 8 and msgs[0] == "ok"
 
 
 def test_workspace_bytes_bounds_the_partials():
