@@ -51,6 +51,34 @@ def fp8_scale_exponents(cfg):
     return int(math.floor(math.log2(448.0 / g))), int(math.floor(math.log2(57344.0 / (g * g))))
 
 
+def kernel_source_sha16() -> str:
+    """Hash of the kernel and launcher sources: ties a counter summary under profiles/ to the code
+    it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("sr_device.h", "sr_kernels.h", "sradamw.hip"):
+        h.update(open(os.path.join(ROOT, "paper_2502_20566_amd", "csrc", name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def profile_traffic(tag: str):
+    """(HBM bytes per step, where from) out of profiles/hbm_traffic_<tag>.txt -- a rocprofv3 counter
+    summary -- while it was made from the kernel sources this library is built from (the summary
+    records their hash); (None, why) otherwise."""
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{tag}.txt")
+    if not os.path.exists(tpath):
+        return None, None
+    fields = {}
+    for line in open(tpath):
+        if "=" in line and not line.startswith((" ", "#")):
+            k, v = line.split("=", 1)
+            fields[k.strip()] = v.strip()
+    rel = os.path.relpath(tpath, ROOT)
+    if fields.get("kernel_source_sha16") != kernel_source_sha16() or "hbm_bytes_per_step" not in fields:
+        return None, f"{rel} is stale (made from other kernel sources)"
+    return int(fields["hbm_bytes_per_step"]), rel
+
+
 def algorithmic_bytes_per_element(mode, clip) -> int:
     # the norm pass of a clipping config reads the gradients once more
     return MODES[mode][3] + (2 if clip is not None else 0)
@@ -194,6 +222,7 @@ def run_aux_op(args, torch, np, B, W, cfg):
         bad = int((W.bf16_to_u16_numpy(acc[lo:lo + n_cpu]) != want).sum())
     avg = float(np.mean(dev_ms))
     achieved = bpe * n / (avg * 1e-3) / 1e9
+    traffic, traffic_source = profile_traffic(f"config{cfg.index}_op_{args.op}")
     print(json.dumps({
         "metric": metric, "value": n * args.steps / wall, "unit": "elements/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
@@ -201,7 +230,8 @@ def run_aux_op(args, torch, np, B, W, cfg):
         "config": {"workload": f"{args.op} on one flat array of config {cfg.index}'s size", "numel": n,
                    "bytes_per_element": bpe},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "kernel": kernel,
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel": kernel,
                      "avg_launch_ms": avg, "median_launch_ms": float(np.median(dev_ms)),
                      "min_launch_ms": float(np.min(dev_ms))},
         "cpu_baseline": {"value": n_cpu / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
@@ -222,6 +252,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time its replays (same step number "
                          "on every replay; removes launch gaps of many-tensor lists)")
+    ap.add_argument("--step-events", choices=("auto", "on", "off"), default="auto",
+                    help="an event pair around every step (on), one pair around the timed region (off), "
+                         "or by step size (auto: per step from 10 GB per step upwards)")
     ap.add_argument("--warm-steps", type=int, default=None, help="seeded steps that warm the moments")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -343,20 +376,32 @@ def main():
         step_fn(t)
     torch.cuda.synchronize()
 
-    # timed region: exactly K steps, inputs resident, HIP events on the launch stream per step
-    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    # timed region: exactly K steps, inputs resident, HIP events on the launch stream.  Long steps
+    # (one big launch) get an event pair each, so that median and minimum are known; steps of a
+    # few hundred microseconds get ONE pair around the region, because an event record drains the
+    # queue and the refill would be charged to every step (measured: 0.345 against 0.28 ms per
+    # step on the 124M-element list).
+    per_step = args.step_events == "on" or (args.step_events == "auto" and MODES[mode][3] * numel >= 1e10)
+    n_ev = args.steps if per_step else 1
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for i in range(args.steps):
-        ev0[i].record()
-        step_fn(t + i)
-        ev1[i].record()
+    if per_step:
+        for i in range(args.steps):
+            ev0[i].record()
+            step_fn(t + i)
+            ev1[i].record()
+    else:
+        ev0[0].record()
+        for i in range(args.steps):
+            step_fn(t + i)
+        ev1[0].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     ms_per_step = wall * 1e3 / args.steps
     dev_ms = [a.elapsed_time(b) for a, b in zip(ev0, ev1)]
-    dev_avg_ms = float(np.mean(dev_ms))
+    dev_avg_ms = float(np.sum(dev_ms)) / args.steps
 
     # ceiling of the access pattern on these very buffers: the step's 4-read/3-write traffic with
     # no arithmetic (BF16 strategies without an auxiliary tensor, flat or list alike)
@@ -407,13 +452,10 @@ def main():
     bpe = algorithmic_bytes_per_element(mode, cfg.clip)
     value = numel * args.steps / wall
     achieved = bpe * numel / (dev_avg_ms * 1e-3) / 1e9
-    # HBM bytes per launch measured with rocprofv3 PMC counters (see the summary under profiles/)
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"adamw_kernel_config{cfg.index}_hbm_traffic.txt")
-    if mode == "sr" and os.path.exists(tpath):
-        for line in open(tpath):
-            if line.startswith("hbm_bytes_per_launch"):
-                traffic = int(line.split("=")[1])
+    # HBM bytes per step measured with rocprofv3 PMC counters: taken from the summary under
+    # profiles/ for this config and mode, and only while that summary was made from the kernel
+    # sources this library is built from (it records their hash); otherwise null
+    traffic, traffic_source = profile_traffic(f"config{cfg.index}_{mode}")
 
     out = {
         # the headline metric as the baseline names it; `value` is its first quantity (params/s),
@@ -431,16 +473,18 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}", "numel": numel, "tensors": len(params),
-                   "mode": mode, "moments": "fp32" if fp32_moments else "e4m3/e5m2" if fp8_exps else "bf16",
+                   "mode": mode, "storage": "bf16 parameters and gradients", "moments": "fp32" if fp32_moments else "e4m3/e5m2" if fp8_exps else "bf16",
                    "fp8_scale_exponents": fp8_exps, "clip": cfg.clip,
                    "warm_steps": warm, "bytes_per_element": bpe, "hip_graph": bool(args.graph)},
         "hbm_GBps": bpe * numel / (ms_per_step * 1e-3) / 1e9,
         "pct_of_hbm_peak": 100.0 * bpe * numel / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "adamw_kernel" if cfg.clip is None and len(params) <= 56 else
-                     "all launches of a step (norm passes + adamw_kernel per 56 tensors)", "avg_launch_ms": dev_avg_ms,
-                     "median_launch_ms": float(np.median(dev_ms)), "min_launch_ms": float(np.min(dev_ms)),
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel": "adamw_kernel" if cfg.clip is None and len(params) <= 320 else
+                     "all launches of a step (norm passes + adamw_kernel per 320 tensors)", "avg_launch_ms": dev_avg_ms,
+                     "median_launch_ms": float(np.median(dev_ms)) if per_step else None,
+                     "min_launch_ms": float(np.min(dev_ms)) if per_step else None,
+                     "events": "a pair per step" if per_step else "one pair around the timed region",
                      "copy_ceiling": ceiling, "device_copy": device_copy,
                      "frac_of_copy_ceiling": None if ceiling is None else
                      (MODES[mode][3] * numel / (dev_avg_ms * 1e-3) / 1e9) / ceiling["GBps"]},

@@ -18,7 +18,17 @@
  *     calling thread's current device must be the device of the stream and
  *     of the tensors.
  *   - Return value: SR_OK (0) or a negative SR_ERR_* code.  Arguments are
- *     validated on the host first; on an argument error nothing is enqueued.
+ *     validated on the host first; on an argument error (every code but
+ *     SR_ERR_HIP) nothing is enqueued.  SR_ERR_HIP means the runtime refused
+ *     a launch.  A call that needs several launches (a list of more tensors
+ *     than one launch takes, a job beyond one dispatch's size, the passes of
+ *     a norm) enqueues them in list order and stops at the first refusal: the
+ *     launches before it stay enqueued and will run, so a tensor list may then
+ *     be updated in part (whole tensors from the front of the list, possibly a
+ *     leading piece of one very large tensor), and a norm or sum output is not
+ *     written.  The library cannot take enqueued work back; a caller that
+ *     must recover keeps a copy of the state or treats the error as fatal for
+ *     the step (a refused launch means the stream or device is unusable).
  *   - Sizes: any tensor that fits in device memory is accepted.  A launch
  *     holds at most 2^32 - 1 work-items; larger jobs (more than about 3.4e10
  *     elements of a BF16-moment list, 1.7e10 of an FP32-moment list or of a
@@ -87,13 +97,22 @@ extern "C" {
                                    7-8 as printed, m'/(1-beta1^t) and v'/(1-beta2^t) with
                                    1-beta^t formed in binary64 and rounded once, instead of
                                    multiplications by the rounded reciprocals              */
+/* Guard for clipped steps (clipping itself is not in the paper). */
+#define SR_FLAG_SKIP_NONFINITE_NORM 256u /* with d_grad_norm: when the norm it holds is NaN
+                                   or infinite (an overflowed or poisoned gradient) the
+                                   step changes nothing -- p, m, v and aux keep their
+                                   bits.  Without this flag the clip formula is applied
+                                   as it stands: a NaN norm makes every p, m, v NaN, an
+                                   infinite norm scales the gradient to zero while decay
+                                   and moment decay still apply.  The caller still
+                                   advances or repeats `step` as it sees fit.            */
 /* A storage format of the moments (not one of the paper's strategies). */
 #define SR_FLAG_FP8_MOMENTS 128u /* extension (the paper's conclusion names FP8 as the next
                                    target of SR and gives no design): m and v are 8-bit
                                    codes, one byte per element, m in E4M3 and v in E5M2
                                    (see sr_cast_f32_fp8 for the formats), each with a
                                    power-of-two scale per tensor given in the tensor's
-                                   `reserved` field: m = decode(m8) 2^-m_exp,
+                                   m_exp and v_exp fields: m = decode(m8) 2^-m_exp,
                                    v = decode(v8) 2^-v_exp, the update as for every other
                                    strategy, m8 <- Q_SR(m' 2^m_exp), v8 <- Q_SR(v' 2^v_exp)
                                    with the element's 16-bit draws of streams 1 and 2 in
@@ -123,9 +142,11 @@ typedef struct sr_tensor {
     uint64_t    elem_offset; /* index of element 0 in the RNG counter; 0 for a whole
                                 tensor, the shard's start for a slice of a larger one     */
     uint32_t    tensor_id;   /* RNG counter word; keep it stable across steps and ranks   */
-    uint32_t    reserved;    /* must be 0; with SR_FLAG_FP8_MOMENTS: m_exp in bits 0-7 and
-                                v_exp in bits 8-15, two's complement, each in [-100, 100],
-                                bits 16-31 zero                                           */
+    int8_t      m_exp;       /* SR_FLAG_FP8_MOMENTS: m = decode(m8) 2^-m_exp, in
+                                [-100, 100]; must be 0 without that flag                  */
+    int8_t      v_exp;       /* SR_FLAG_FP8_MOMENTS: v = decode(v8) 2^-v_exp, in
+                                [-100, 100]; must be 0 without that flag                  */
+    uint16_t    reserved;    /* must be 0                                                 */
 } sr_tensor_t;
 
 /* Hyper-parameters of Algorithm 1: alpha_t, beta_1, beta_2, epsilon, lambda. */
@@ -238,7 +259,11 @@ int grad_sum_of_squares(const sr_tensor_t* tensors, uint32_t n_tensors, double* 
  *   flags        SR_FLAG_* bits
  *   d_grad_norm  NULL = no clipping; else device scalar holding the global
  *                gradient norm (as written by grad_global_norm on the same
- *                stream); gradients are scaled in registers, d g is not rewritten
+ *                stream); gradients are scaled in registers, d g is not
+ *                rewritten.  The scale is c = max_norm / (norm + 1e-6) in
+ *                binary32, replaced by 1 when c > 1: a NaN norm gives c = NaN
+ *                (every output NaN), an infinite norm c = 0 -- see
+ *                SR_FLAG_SKIP_NONFINITE_NORM for a step that skips itself instead
  *   max_norm     > 0, used only with d_grad_norm
  */
 int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper_t* hyper,
@@ -290,6 +315,22 @@ uint64_t sr_accumulate_workspace_bytes(uint32_t n_tensors, uint64_t total_numel)
  * tensors with total_numel elements in all (an upper bound, multiple of 256). */
 uint64_t sr_workspace_bytes(uint32_t n_tensors, uint64_t total_numel);
 
+/* Static description of an SR_ERR_* code. */
+const char* sr_strerror(int code);
+
+/* hipError_t value of the most recent SR_ERR_HIP on the calling thread (0 if none). */
+int sr_last_hip_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int sr_version(void);
+
+/* ======================================================================
+ * NOT PART OF THE PRODUCT API.  What follows serves measurement and tests
+ * only: two traffic probes that bench.py times beside the update, and one
+ * hook through which the tests reach code paths that otherwise need huge
+ * inputs or rare values.  A deployment can strip them.
+ * ====================================================================== */
+
 /*
  * Measurement aid, not part of the method: the memory traffic of the BF16 step
  * (8 bytes read, 6 written per element: the 14 bytes per element of an
@@ -309,22 +350,27 @@ int sr_stream_probe(void* d_p, const void* d_g, void* d_m, void* d_v, uint64_t n
  */
 int sr_stream_probe_fp8m(void* d_p, const void* d_g, void* d_m8, void* d_v8, uint64_t numel, void* stream);
 
-/* Static description of an SR_ERR_* code. */
-const char* sr_strerror(int code);
-
-/* hipError_t value of the most recent SR_ERR_HIP on the calling thread (0 if none). */
-int sr_last_hip_error(void);
-
 /*
- * For tests of the multi-launch paths: limit every later launch of this process
- * to max_workgroups workgroups (0 restores the hardware limit), so that small
- * inputs are cut into several launches.  Results must not change.  Not
- * synchronised with calls running on other threads.
+ * Process-wide switches for tests and measurements (not synchronised with
+ * calls running on other threads; set them while no call is in flight).
+ * Results of every entry point must not depend on them.
+ *   SR_DEBUG_LAUNCH_LIMIT    value = most workgroups one launch may hold
+ *                            (0 = the hardware limit): small inputs are cut
+ *                            into several launches, as huge ones are
+ *   SR_DEBUG_FP8_INTEGER     value != 0: every wave of sr_cast_f32_fp8 and of
+ *                            the 8-bit-moment write-back takes the integer
+ *                            path instead of the chip's conversion instruction
+ *                            (both compute the same function; this lets a
+ *                            test prove it on the same inputs)
+ *   SR_DEBUG_RESIDENT_WAVES  value = waves the streaming kernels allow to
+ *                            reside per compute unit (0 = the library's own
+ *                            setting per kernel, 32 = no cap)
+ * Unknown keys are ignored.
  */
-void sr_debug_set_launch_limit(uint32_t max_workgroups);
-
-/* Library version, major*10000 + minor*100 + patch. */
-int sr_version(void);
+#define SR_DEBUG_LAUNCH_LIMIT   0u
+#define SR_DEBUG_FP8_INTEGER    1u
+#define SR_DEBUG_RESIDENT_WAVES 2u
+void sr_debug_set(uint32_t key, uint32_t value);
 
 #ifdef __cplusplus
 }

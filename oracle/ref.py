@@ -21,6 +21,7 @@ FLAG_KAHAN = 16
 FLAG_EPS_IN_ROOT = 32
 FLAG_DIV_BIAS = 64
 FLAG_FP8_MOMENTS = 128
+FLAG_SKIP_NONFINITE_NORM = 256
 
 STREAM_PARAM, STREAM_M, STREAM_V, STREAM_CAST, STREAM_ACC = 0, 1, 2, 3, 4
 ACC_RNE = 1
@@ -282,6 +283,11 @@ def sr_adamw_step(tensors, hyper, step, seed, flags=0, norm=None, max_norm=0.0, 
     hyper = dict(lr, beta1, beta2, eps, weight_decay)."""
     s = adamw_scalars(hyper["lr"], hyper["beta1"], hyper["beta2"], hyper["eps"],
                       hyper["weight_decay"], step, norm, max_norm)
+    if flags & FLAG_SKIP_NONFINITE_NORM:
+        # guard of a clipped step: a NaN or infinite gradient norm leaves every tensor as it is
+        if norm is not None and not np.isfinite(np.float32(norm)):
+            return s
+        flags &= ~FLAG_SKIP_NONFINITE_NORM
     for idx, t in enumerate(tensors):
         if flags & FLAG_FP8_MOMENTS:
             sr_adamw_tensor_fp8m(t["p"], t["g"], t["m"], t["v"], t.get("tensor_id", idx), s, step, seed,

@@ -23,6 +23,9 @@ SR_FLAG_KAHAN = 16
 SR_FLAG_EPS_IN_ROOT = 32
 SR_FLAG_DIV_BIAS = 64
 SR_FLAG_FP8_MOMENTS = 128
+SR_FLAG_SKIP_NONFINITE_NORM = 256
+
+SR_DEBUG_LAUNCH_LIMIT, SR_DEBUG_FP8_INTEGER, SR_DEBUG_RESIDENT_WAVES = 0, 1, 2
 
 SR_ACC_RNE = 1
 SR_ACC_FIRST = 2
@@ -31,13 +34,13 @@ SR_FP8_E4M3, SR_FP8_E5M2 = 0, 1
 
 EXPORTS = ("sr_cast_f32_bf16", "sr_cast_f32_fp8", "grad_global_norm", "grad_global_norm_static", "grad_sum_of_squares", "sr_adamw_step", "sr_workspace_bytes",
            "sr_grad_accumulate", "sr_accumulate_workspace_bytes", "sr_stream_probe", "sr_stream_probe_fp8m",
-           "sr_strerror", "sr_last_hip_error", "sr_version", "sr_debug_set_launch_limit")
+           "sr_strerror", "sr_last_hip_error", "sr_version", "sr_debug_set")
 
 
 class SrTensor(C.Structure):
     _fields_ = [("p", C.c_void_p), ("g", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
                 ("aux", C.c_void_p), ("numel", C.c_uint64), ("elem_offset", C.c_uint64),
-                ("tensor_id", C.c_uint32), ("reserved", C.c_uint32)]
+                ("tensor_id", C.c_uint32), ("m_exp", C.c_int8), ("v_exp", C.c_int8), ("reserved", C.c_uint16)]
 
 
 class SrAccum(C.Structure):
@@ -102,8 +105,8 @@ def lib():
         L.sr_strerror.restype = C.c_char_p
         L.sr_last_hip_error.argtypes = []
         L.sr_last_hip_error.restype = C.c_int
-        L.sr_debug_set_launch_limit.argtypes = [C.c_uint32]
-        L.sr_debug_set_launch_limit.restype = None
+        L.sr_debug_set.argtypes = [C.c_uint32, C.c_uint32]
+        L.sr_debug_set.restype = None
         L.sr_version.argtypes = []
         L.sr_version.restype = C.c_int
         _lib = L
@@ -183,12 +186,12 @@ class TensorList:
             e.numel = p.numel()
             e.elem_offset = 0 if elem_offsets is None else int(elem_offsets[i])
             e.tensor_id = i if tensor_ids is None else int(tensor_ids[i])
-            e.reserved = 0
+            e.m_exp, e.v_exp, e.reserved = 0, 0, 0
             if fp8_exponents is not None:
                 m_exp, v_exp = (int(x) for x in fp8_exponents[i])
                 if not (-100 <= m_exp <= 100 and -100 <= v_exp <= 100):
                     raise ValueError("fp8 scale exponents must lie in [-100, 100]")
-                e.reserved = (m_exp & 0xFF) | ((v_exp & 0xFF) << 8)
+                e.m_exp, e.v_exp = m_exp, v_exp
             self.total_numel += p.numel()
 
     def workspace_bytes(self) -> int:

@@ -18,11 +18,6 @@ namespace sr {
 // ones (finer interleaving of the seven streams in time), and more blocks per lane are slower.
 // Rows of 4 elements per lane in the cast kernels.  Measured on 6.66e9 elements: BF16 cast 6.06 /
 // 6.10 / 7.04 ms with 1 / 2 / 4 rows; 8-bit cast (integer path) 6.07 / 5.64 / 5.64 ms.
-// SR_TUNE_FP8_NOHW = 1 builds the 8-bit cast without the chip's conversion instruction (every wave
-// on the integer path): the build used to check that path on all binary32 encodings.
-#ifndef SR_TUNE_FP8_NOHW
-#define SR_TUNE_FP8_NOHW 0
-#endif
 #ifndef SR_TUNE_CAST_ITERS
 #define SR_TUNE_CAST_ITERS 1
 #endif
@@ -32,13 +27,52 @@ namespace sr {
 #ifndef SR_TUNE_THREADS
 #define SR_TUNE_THREADS 64
 #endif
+// Tensors per update launch: the descriptors and the chunk table travel by value in the kernel
+// argument segment (22 KiB at 320).  Measured on MI355X with 56 / 160 / 320 per launch: the
+// 148-tensor list 0.282 / 0.273 / 0.273 ms, the 292-tensor list 0.786 / 0.772 / 0.770 ms, the
+// 388-tensor list equal within noise: every launch boundary drains and refills the chip.
+#ifndef SR_TUNE_MAXBATCH
+#define SR_TUNE_MAXBATCH 320
+#endif
+// Waves allowed to reside per CU, by kernel class (0 = as many as fit, 32): see occupancy_lds in
+// the host code.  Measured on MI355X, 6.66e9 elements, waves per CU 32 / 24 / 20 / 16 / 14 / 12:
+//   BF16 update (SR)   14.69 / 14.19 / 14.05 / 14.03 / 14.24 / 15.21 ms
+//   same, no arithmetic 14.54 / 14.66 / 14.31 / 14.11 / 13.96 / 13.93 ms
+//   Kahan (18 B/el)    19.90 / 19.52 / 18.96 / 18.70 / 18.37 / 18.20 ms
+//   binary32 moments (2.65e9 el) 9.09 / 9.06 / 9.00 / 8.99 / 8.96 / 9.18 ms
+//   8-bit moments      11.33 / 11.92 / 12.27 / 12.56 / 13.02 / 14.16 ms   (arithmetic not hidden: no cap)
+//   BF16 cast           6.16 /  6.93 /  7.40 /  7.90 /  8.89 / 10.53 ms   (half a block per lane: no cap)
+//   8-bit cast          4.94 /  4.90 /   -   /  5.50 /  5.98 /   -    ms   (28 waves: 4.84)
+//   accumulation        6.20 /  6.47 /  6.62 /  6.80 /  7.21 /  8.05 ms   (no cap)
+// A read-only stream does not care (7.32 ms for 8, 16 and 32 waves): it is the mix of reads and
+// writes that loses bandwidth when more requests than needed are in flight.
+#ifndef SR_TUNE_WAVES_BF16
+#define SR_TUNE_WAVES_BF16 20
+#endif
+#ifndef SR_TUNE_WAVES_KAHAN
+#define SR_TUNE_WAVES_KAHAN 12
+#endif
+#ifndef SR_TUNE_WAVES_FP32
+#define SR_TUNE_WAVES_FP32 16
+#endif
+#ifndef SR_TUNE_WAVES_FP8M
+#define SR_TUNE_WAVES_FP8M 0
+#endif
+#ifndef SR_TUNE_WAVES_CAST
+#define SR_TUNE_WAVES_CAST 0
+#endif
+#ifndef SR_TUNE_WAVES_CAST8
+#define SR_TUNE_WAVES_CAST8 28
+#endif
+#ifndef SR_TUNE_WAVES_ACC
+#define SR_TUNE_WAVES_ACC 0
+#endif
 constexpr int kThreads = SR_TUNE_THREADS;   // lanes per workgroup of the update and cast kernels
-constexpr int kMaxBatch = 56;          // tensors per update launch (argument segment <= 4 KiB;
-                                       // larger segments were measured and are not faster)
+constexpr int kMaxBatch = SR_TUNE_MAXBATCH; // tensors per update launch
 // Norm, first pass: measured on MI355X, 512-lane workgroups with 16 blocks per lane and
 // nontemporal loads read at 7.1 TB/s (the read-only ceiling); plain loads reach 6.1 TB/s.
 constexpr int kNormThreads = 512;      // lanes per workgroup of the norm's first pass
-constexpr int kNormMaxBatch = 160;     // tensors per norm launch
+constexpr int kNormMaxBatch = 400;     // tensors per norm launch
 constexpr int kNormIters = 16;         // blocks per lane in the norm's first pass
 constexpr int kNormChunkElems = kNormThreads * 8 * kNormIters;
 constexpr int kFinalThreads = 1024;
@@ -51,7 +85,7 @@ constexpr int kReduceThreads = 256;    // partial-sum folding: each workgroup ad
 constexpr int kReduceFan = 4096;
 constexpr uint32_t kReduceAbove = 16384;   // fold while more partials than this remain
 constexpr int kAccChunkElems = kAccThreads * 8 * kAccIters;
-constexpr int kAccMaxBatch = 88;       // tensors per accumulation launch
+constexpr int kAccMaxBatch = 320;      // tensors per accumulation launch
 
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 // Vector accesses are declared with the alignment of the ELEMENT type (2 bytes for BF16 arrays, 4 for
@@ -82,9 +116,10 @@ struct StepScalars {
     const float* d_norm;
     uint32_t seed_lo, seed_hi, step, n_tensors;
     uint32_t variant;                      // VARIANT_* bits: wave-uniform choices of the arithmetic
-    uint32_t pad_;
+    uint32_t skip_nonfinite;               // with clipping: leave everything unchanged when the norm is NaN or infinite
 };
-enum : uint32_t { VARIANT_EPS_IN_ROOT = 1u, VARIANT_DIV_BIAS = 2u };
+// VARIANT_FP8_INTEGER (test switch): every wave writes its 8-bit moments through the integer path.
+enum : uint32_t { VARIANT_EPS_IN_ROOT = 1u, VARIANT_DIV_BIAS = 2u, VARIANT_FP8_INTEGER = 4u };
 
 struct AdamwBatch {
     StepScalars s;
@@ -92,7 +127,7 @@ struct AdamwBatch {
     uint32_t pad_;
     TensorDesc t[kMaxBatch];
 };
-static_assert(sizeof(AdamwBatch) <= 4096, "kernel argument segment");
+static_assert(sizeof(AdamwBatch) <= 32768, "kernel argument segment");
 
 struct NormDesc { const uint16_t* g; uint64_t numel; };
 struct NormBatch {
@@ -102,7 +137,7 @@ struct NormBatch {
     uint32_t pad_;
     NormDesc t[kNormMaxBatch];
 };
-static_assert(sizeof(NormBatch) <= 4096, "kernel argument segment");
+static_assert(sizeof(NormBatch) <= 32768, "kernel argument segment");
 
 struct AccDesc {
     uint16_t* acc;
@@ -120,7 +155,7 @@ struct AccBatch {
     uint32_t pad2_;
     AccDesc t[kAccMaxBatch];
 };
-static_assert(sizeof(AccBatch) <= 4096, "kernel argument segment");
+static_assert(sizeof(AccBatch) <= 32768, "kernel argument segment");
 
 // ------------------------------------------------------------------ memory access helpers
 
@@ -802,7 +837,7 @@ __device__ __forceinline__ void inner_block(const TensorDesc& T, const StepScala
         buf_store16<NT>(rv, o32, bits4lo(L.v)); buf_store16<NT>(rv, o32 + 16u, bits4hi(L.v));
     } else if (M::fp8m) {
         v2u mo, vo;
-        fp8_moments_out(L.m, L.v, m_exp, v_exp, dm.w, dv.w, nan, mo, vo);
+        fp8_moments_out(L.m, L.v, m_exp, v_exp, dm.w, dv.w, nan || (VAR && (S.variant & VARIANT_FP8_INTEGER)), mo, vo);
         buf_store8<NT>(rm, lane * 8u, mo);
         buf_store8<NT>(rv, lane * 8u, vo);
     } else {
@@ -847,7 +882,7 @@ __device__ __forceinline__ void edge_block(const TensorDesc& T, const StepScalar
         store8_f32<false>(static_cast<float*>(T.v), l0, numel, false, L.v);
     } else if (M::fp8m) {
         v2u mo, vo;
-        fp8_moments_out(L.m, L.v, m_exp, v_exp, dm.w, dv.w, nan, mo, vo);
+        fp8_moments_out(L.m, L.v, m_exp, v_exp, dm.w, dv.w, nan || (VAR && (S.variant & VARIANT_FP8_INTEGER)), mo, vo);
         store8_u8(static_cast<uint8_t*>(T.m), l0, numel, mo);
         store8_u8(static_cast<uint8_t*>(T.v), l0, numel, vo);
     } else {
@@ -889,7 +924,10 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(const AdamwBatch B)
 
     float c = 1.0f;
     if (CLIP) {
-        c = S.max_norm / (*S.d_norm + 1e-6f);
+        const float norm = *S.d_norm;
+        // NaN and infinities are the encodings whose exponent field is all ones (wave-uniform test)
+        if (S.skip_nonfinite && (__float_as_uint(norm) & 0x7F800000u) == 0x7F800000u) return;
+        c = S.max_norm / (norm + 1e-6f);
         if (c > 1.0f) c = 1.0f;
     }
 
@@ -1069,7 +1107,7 @@ template <int FMT, bool NT>
 __global__ __launch_bounds__(kThreads) void cast_fp8_kernel(const float* __restrict__ src,
                                                             uint8_t* __restrict__ dst, uint64_t n,
                                                             uint64_t chunk0, uint32_t seed_lo, uint32_t seed_hi,
-                                                            uint32_t step, uint32_t tensor_id)
+                                                            uint32_t step, uint32_t tensor_id, uint32_t integer_path)
 {
     using P = Fp8<FMT>;
     const uint64_t cfirst = ((uint64_t)blockIdx.x + chunk0) * (uint64_t)kFp8ChunkElems;
@@ -1089,7 +1127,8 @@ __global__ __launch_bounds__(kThreads) void cast_fp8_kernel(const float* __restr
             const uint32_t b[4] = {x.x, x.y, x.z, x.w};
             // the range rules apply when some lane holds a value in the format's top binade or
             // above (or an infinity or a NaN): integer path for the whole wave
-            const bool ranged = SR_TUNE_FP8_NOHW ||
+            // (integer_path: a test switch that sends every wave down the integer path)
+            const bool ranged = integer_path != 0 ||
                                 __builtin_amdgcn_ballot_w64(max_magnitude4(b) >= (P::efmax << 23)) != 0;
             const uint32_t o = fp8_encode4<FMT>(b, r.w, ranged);
             __builtin_amdgcn_raw_buffer_store_b32(o, rd, (int)(row * 4u), 0, NT ? 2 : 0);

@@ -27,11 +27,17 @@ inline int hip_fail(hipError_t e)
 // kernel's signature, so every argument is converted before its address is passed.
 template <class T> struct same_type { using type = T; };
 template <class... P>
+inline hipError_t launch_lds(void (*kernel)(P...), uint32_t grid, uint32_t block, uint32_t lds_bytes,
+                             hipStream_t stream, typename same_type<P>::type... args)
+{
+    void* ptrs[] = {const_cast<void*>(static_cast<const void*>(&args))...};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), dim3(grid), dim3(block), ptrs, lds_bytes, stream);
+}
+template <class... P>
 inline hipError_t launch(void (*kernel)(P...), uint32_t grid, uint32_t block, hipStream_t stream,
                          typename same_type<P>::type... args)
 {
-    void* ptrs[] = {const_cast<void*>(static_cast<const void*>(&args))...};
-    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), dim3(grid), dim3(block), ptrs, 0, stream);
+    return launch_lds(kernel, grid, block, 0u, stream, args...);
 }
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -64,6 +70,30 @@ inline uint32_t max_grid(uint32_t threads)
     const uint32_t lim = g_launch_limit.load(std::memory_order_relaxed);
     return lim && lim < hw ? lim : hw;
 }
+// Test switch: every wave of the 8-bit conversions takes the integer path.
+std::atomic<uint32_t> g_fp8_integer{0};
+
+// Waves resident per CU.  A stream that mixes reads and writes runs FASTER on MI355X with fewer
+// waves in flight than the 32 single-wave workgroups a CU can hold: each kernel class below states
+// how many it lets reside, and the launch reserves that share of the CU's 160 KiB of LDS per
+// workgroup (LDS that no kernel touches) so that the hardware admits no more.  0 = no cap.  The
+// debug hook overrides the number for measurements.
+std::atomic<uint32_t> g_resident_waves{0};
+constexpr uint32_t kLdsPerCu = 160u * 1024u;
+inline uint32_t occupancy_lds(uint32_t class_default)
+{
+    const uint32_t forced = g_resident_waves.load(std::memory_order_relaxed);
+    const uint32_t waves = forced ? forced : class_default;
+    if (waves == 0 || waves >= 32) return 0;
+    return (kLdsPerCu / (waves < 3 ? 3 : waves)) & ~511u;     // a launch may ask for at most 64 KiB
+}
+constexpr uint32_t kWavesUpdateBf16 = SR_TUNE_WAVES_BF16;    // BF16 moments (14 bytes per element)
+constexpr uint32_t kWavesUpdateKahan = SR_TUNE_WAVES_KAHAN;  // BF16 moments + BF16 compensation (18)
+constexpr uint32_t kWavesUpdateFp32 = SR_TUNE_WAVES_FP32;    // binary32 moments / master parameters
+constexpr uint32_t kWavesUpdateFp8 = SR_TUNE_WAVES_FP8M;     // 8-bit moments
+constexpr uint32_t kWavesCast = SR_TUNE_WAVES_CAST;          // the standalone cast to BF16
+constexpr uint32_t kWavesCast8 = SR_TUNE_WAVES_CAST8;        // the standalone cast to an 8-bit format
+constexpr uint32_t kWavesAcc = SR_TUNE_WAVES_ACC;            // gradient accumulation
 
 // True when the counter indices elem_offset .. elem_offset + numel (rounded up to a block) leave 64 bits.
 inline bool range_wraps(uint64_t elem_offset, uint64_t numel)
@@ -93,8 +123,10 @@ hipError_t split_tensor(uint64_t numel, uint64_t elem_offset, uint64_t blocks_pe
 template <uint32_t F, bool VAR>
 hipError_t launch_adamw_v(bool clip, const AdamwBatch& batch, uint32_t n_chunks, hipStream_t stream)
 {
-    return clip ? launch(adamw_kernel<F, true, kNT, VAR>, n_chunks, kThreads, stream, batch)
-                : launch(adamw_kernel<F, false, kNT, VAR>, n_chunks, kThreads, stream, batch);
+    const uint32_t lds = occupancy_lds(Mode<F>::fp32m ? kWavesUpdateFp32 : Mode<F>::fp8m ? kWavesUpdateFp8
+                                       : Mode<F>::kahan ? kWavesUpdateKahan : kWavesUpdateBf16);
+    return clip ? launch_lds(adamw_kernel<F, true, kNT, VAR>, n_chunks, kThreads, lds, stream, batch)
+                : launch_lds(adamw_kernel<F, false, kNT, VAR>, n_chunks, kThreads, lds, stream, batch);
 }
 
 // The default arithmetic runs in kernels compiled without the variant branches.
@@ -162,9 +194,14 @@ int sr_version(void) { return 100; }
 
 int sr_last_hip_error(void) { return g_last_hip_error; }
 
-void sr_debug_set_launch_limit(uint32_t max_workgroups)
+void sr_debug_set(uint32_t key, uint32_t value)
 {
-    g_launch_limit.store(max_workgroups, std::memory_order_relaxed);
+    switch (key) {
+        case SR_DEBUG_LAUNCH_LIMIT:   g_launch_limit.store(value, std::memory_order_relaxed); break;
+        case SR_DEBUG_FP8_INTEGER:    g_fp8_integer.store(value, std::memory_order_relaxed); break;
+        case SR_DEBUG_RESIDENT_WAVES: g_resident_waves.store(value, std::memory_order_relaxed); break;
+        default: break;
+    }
 }
 
 int sr_stream_probe(void* d_p, const void* d_g, void* d_m, void* d_v, uint64_t numel, void* stream)
@@ -177,7 +214,7 @@ int sr_stream_probe(void* d_p, const void* d_g, void* d_m, void* d_v, uint64_t n
     const uint32_t mg = max_grid(kThreads);
     for (uint64_t w0 = 0; w0 < wgs; w0 += mg) {
         const uint32_t grid = (uint32_t)(wgs - w0 < mg ? wgs - w0 : mg);
-        const hipError_t e = launch(stream_probe_kernel, grid, kThreads, static_cast<hipStream_t>(stream),
+        const hipError_t e = launch_lds(stream_probe_kernel, grid, kThreads, occupancy_lds(kWavesUpdateBf16), static_cast<hipStream_t>(stream),
                                     static_cast<uint16_t*>(d_p), static_cast<const uint16_t*>(d_g),
                                     static_cast<uint16_t*>(d_m), static_cast<uint16_t*>(d_v), nblk, w0, 0u);
         if (e != hipSuccess) return hip_fail(e);
@@ -195,7 +232,7 @@ int sr_stream_probe_fp8m(void* d_p, const void* d_g, void* d_m8, void* d_v8, uin
     const uint32_t mg = max_grid(kThreads);
     for (uint64_t w0 = 0; w0 < wgs; w0 += mg) {
         const uint32_t grid = (uint32_t)(wgs - w0 < mg ? wgs - w0 : mg);
-        const hipError_t e = launch(stream_probe_fp8m_kernel, grid, kThreads, static_cast<hipStream_t>(stream),
+        const hipError_t e = launch_lds(stream_probe_fp8m_kernel, grid, kThreads, occupancy_lds(kWavesUpdateFp8), static_cast<hipStream_t>(stream),
                                     static_cast<uint16_t*>(d_p), static_cast<const uint16_t*>(d_g),
                                     static_cast<uint8_t*>(d_m8), static_cast<uint8_t*>(d_v8), nblk, w0, 0u);
         if (e != hipSuccess) return hip_fail(e);
@@ -208,7 +245,7 @@ const char* sr_strerror(int code)
     switch (code) {
         case SR_OK:            return "ok";
         case SR_ERR_NULL:      return "a required pointer is NULL";
-        case SR_ERR_ARG:       return "invalid argument (step, hyper-parameter, flag, reserved field or index range)";
+        case SR_ERR_ARG:       return "invalid argument (step, hyper-parameter, flag, scale exponent, reserved field or index range)";
         case SR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case SR_ERR_ALIGN:     return "tensor pointer not aligned to its element size";
         case SR_ERR_HIP:       return "HIP launch failed (see sr_last_hip_error)";
@@ -233,7 +270,7 @@ int sr_cast_f32_bf16(const float* d_src, void* d_dst, uint64_t n, uint64_t seed,
     const uint32_t mg = max_grid(kThreads);
     for (uint64_t c0 = 0; c0 < chunks; c0 += mg) {
         const uint32_t grid = (uint32_t)(chunks - c0 < mg ? chunks - c0 : mg);
-        const hipError_t e = launch(cast_kernel<kNT>, grid, kThreads, static_cast<hipStream_t>(stream), d_src,
+        const hipError_t e = launch_lds(cast_kernel<kNT>, grid, kThreads, occupancy_lds(kWavesCast), static_cast<hipStream_t>(stream), d_src,
                                     static_cast<uint16_t*>(d_dst), n, c0, (uint32_t)(seed & 0xFFFFFFFFu),
                                     (uint32_t)(seed >> 32), step, tensor_id);
         if (e != hipSuccess) return hip_fail(e);
@@ -255,9 +292,11 @@ int sr_cast_f32_fp8(const float* d_src, void* d_dst, uint64_t n, uint32_t format
     const uint32_t lo = (uint32_t)(seed & 0xFFFFFFFFu), hi = (uint32_t)(seed >> 32);
     for (uint64_t c0 = 0; c0 < chunks; c0 += mg) {
         const uint32_t grid = (uint32_t)(chunks - c0 < mg ? chunks - c0 : mg);
+        const uint32_t lds = occupancy_lds(kWavesCast8);
+        const uint32_t integer_path = g_fp8_integer.load(std::memory_order_relaxed) ? 1u : 0u;
         const hipError_t e = format == SR_FP8_E4M3
-            ? launch(cast_fp8_kernel<0, kNT>, grid, kThreads, s, d_src, static_cast<uint8_t*>(d_dst), n, c0, lo, hi, step, tensor_id)
-            : launch(cast_fp8_kernel<1, kNT>, grid, kThreads, s, d_src, static_cast<uint8_t*>(d_dst), n, c0, lo, hi, step, tensor_id);
+            ? launch_lds(cast_fp8_kernel<0, kNT>, grid, kThreads, lds, s, d_src, static_cast<uint8_t*>(d_dst), n, c0, lo, hi, step, tensor_id, integer_path)
+            : launch_lds(cast_fp8_kernel<1, kNT>, grid, kThreads, lds, s, d_src, static_cast<uint8_t*>(d_dst), n, c0, lo, hi, step, tensor_id, integer_path);
         if (e != hipSuccess) return hip_fail(e);
     }
     return SR_OK;
@@ -350,7 +389,8 @@ int grad_global_norm_static(const sr_tensor_t* tensors, uint32_t n_tensors, floa
 uint64_t sr_accumulate_workspace_bytes(uint32_t n_tensors, uint64_t total_numel)
 {
     // first-level partials plus the folded levels (each kReduceFan times smaller)
-    uint64_t chunks = total_numel / (uint64_t)kAccChunkElems + (uint64_t)n_tensors + 1;
+    // a tensor of numel elements whose counter blocks start mid-block spans up to numel/512 + 2 chunks
+    uint64_t chunks = total_numel / (uint64_t)kAccChunkElems + 2 * (uint64_t)n_tensors + 1;
     uint64_t total = chunks;
     while (chunks > kReduceAbove) { chunks = (chunks + kReduceFan - 1) / kReduceFan; total += chunks; }
     return (total * sizeof(double) + 255u) & ~(uint64_t)255u;
@@ -400,7 +440,7 @@ int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scal
         batch.n_tensors = nb;
         batch.partial_base = base;
         batch.chunk_start[nb] = chunks_in_batch;
-        const hipError_t e = launch(accumulate_kernel, chunks_in_batch, kAccThreads, s, batch, partials);
+        const hipError_t e = launch_lds(accumulate_kernel, chunks_in_batch, kAccThreads, occupancy_lds(kWavesAcc), s, batch, partials);
         base += chunks_in_batch;
         nb = 0; chunks_in_batch = 0;
         return e;
@@ -459,8 +499,12 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     if (n_tensors && !tensors) return SR_ERR_NULL;
     if (step == 0) return SR_ERR_ARG;
     if (flags & ~(SR_FLAG_FP32_MOMENTS | SR_FLAG_RNE_MOMENTS | SR_FLAG_RNE_PARAMS | SR_FLAG_MASTER_FP32 |
-                  SR_FLAG_KAHAN | SR_FLAG_EPS_IN_ROOT | SR_FLAG_DIV_BIAS | SR_FLAG_FP8_MOMENTS))
+                  SR_FLAG_KAHAN | SR_FLAG_EPS_IN_ROOT | SR_FLAG_DIV_BIAS | SR_FLAG_FP8_MOMENTS |
+                  SR_FLAG_SKIP_NONFINITE_NORM))
         return SR_ERR_ARG;
+    // a guard of the clipped step, not a strategy: it selects no kernel
+    const bool skip_nonfinite = (flags & SR_FLAG_SKIP_NONFINITE_NORM) != 0;
+    flags &= ~SR_FLAG_SKIP_NONFINITE_NORM;
     // variants of the arithmetic combine with any strategy and do not select a kernel
     uint32_t variant = 0;
     if (flags & SR_FLAG_EPS_IN_ROOT) variant |= VARIANT_EPS_IN_ROOT;
@@ -489,11 +533,10 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     // Validate the whole list before anything is enqueued.
     for (uint32_t i = 0; i < n_tensors; ++i) {
         const sr_tensor_t& t = tensors[i];
+        if (t.reserved != 0) return SR_ERR_ARG;
         if (fp8m) {
-            // the scale exponents of m (bits 0-7) and v (bits 8-15), two's complement
-            const int m_exp = (int8_t)(t.reserved & 0xFFu), v_exp = (int8_t)((t.reserved >> 8) & 0xFFu);
-            if ((t.reserved >> 16) != 0 || m_exp < -100 || m_exp > 100 || v_exp < -100 || v_exp > 100) return SR_ERR_ARG;
-        } else if (t.reserved != 0) {
+            if (t.m_exp < -100 || t.m_exp > 100 || t.v_exp < -100 || t.v_exp > 100) return SR_ERR_ARG;
+        } else if (t.m_exp != 0 || t.v_exp != 0) {
             return SR_ERR_ARG;
         }
         if (t.numel == 0) continue;
@@ -516,12 +559,13 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     S.rbc2 = (float)(1.0 / (1.0 - pow_uint((double)h.beta2, step)));
     S.bc1 = (float)(1.0 - pow_uint((double)h.beta1, step));
     S.bc2 = (float)(1.0 - pow_uint((double)h.beta2, step));
-    S.variant = variant;
+    S.variant = variant | (fp8m && g_fp8_integer.load(std::memory_order_relaxed) ? VARIANT_FP8_INTEGER : 0u);
     S.lr = h.lr;
     S.eps = h.eps;
     S.lw = (float)((double)h.lr * (double)h.weight_decay);
     S.max_norm = max_norm;
     S.d_norm = d_grad_norm;
+    S.skip_nonfinite = (skip_nonfinite && clip) ? 1u : 0u;
     S.seed_lo = (uint32_t)(seed & 0xFFFFFFFFu);
     S.seed_hi = (uint32_t)(seed >> 32);
     S.step = step;
@@ -559,7 +603,8 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
             d.numel = numel;
             d.elem_offset = goff;
             d.tensor_id = t.tensor_id;
-            d.flags = ((goff & 7u) == 0 ? DESC_VEC : 0u) | (fp8m ? (t.reserved & 0xFFFFu) << DESC_MEXP_SHIFT : 0u);
+            d.flags = ((goff & 7u) == 0 ? DESC_VEC : 0u) |
+                      (fp8m ? ((uint32_t)(uint8_t)t.m_exp << DESC_MEXP_SHIFT) | ((uint32_t)(uint8_t)t.v_exp << DESC_VEXP_SHIFT) : 0u);
             batch.chunk_start[nb] = chunks_in_batch;
             chunks_in_batch += nch;
             ++nb;

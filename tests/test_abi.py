@@ -29,7 +29,7 @@ def tensor(numel=64, **kw):
     t = B.SrTensor()
     t.p, t.g, t.m, t.v = buf(2 * numel), buf(2 * numel), buf(4 * numel), buf(4 * numel)
     t.aux = None
-    t.numel, t.elem_offset, t.tensor_id, t.reserved = numel, 0, 0, 0
+    t.numel, t.elem_offset, t.tensor_id, t.m_exp, t.v_exp, t.reserved = numel, 0, 0, 0, 0, 0
     for k, v in kw.items():
         setattr(t, k, v)
     return t
@@ -61,7 +61,7 @@ def test_header_is_plain_c_and_struct_layouts_match_the_binding(tmp_path):
     gcc = shutil.which("gcc")
     if gcc is None:
         pytest.skip("no host C compiler")
-    fields = {"sr_tensor_t": ["p", "g", "m", "v", "aux", "numel", "elem_offset", "tensor_id", "reserved"],
+    fields = {"sr_tensor_t": ["p", "g", "m", "v", "aux", "numel", "elem_offset", "tensor_id", "m_exp", "v_exp", "reserved"],
               "sr_accum_t": ["acc", "grad", "numel", "elem_offset", "tensor_id", "reserved"],
               "sr_hyper_t": ["lr", "beta1", "beta2", "eps", "weight_decay"]}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "sradamw.h"', 'int main(void) {']
@@ -107,12 +107,14 @@ def test_adamw_argument_errors():
     assert step([t], hyper=(float("nan"), 0.9, 0.95, 1e-8, 0.1)) == B.SR_ERR_ARG
     assert step([t], hyper=(1e-3, 0.9, 0.95, float("inf"), 0.1)) == B.SR_ERR_ARG
     assert step([t], hyper=(1e-3, 0.9, 0.95, 1e-8, float("nan"))) == B.SR_ERR_ARG
-    assert step([t], flags=256) == B.SR_ERR_ARG
+    assert step([t], flags=512) == B.SR_ERR_ARG
     for bad in (128 | 1, 128 | 2, 128 | 8 | 1, 128 | 16):        # 8-bit moments combine with few flags
         assert step([t], flags=bad) == B.SR_ERR_ARG
-    assert step([tensor(reserved=0x10000)], flags=128) == B.SR_ERR_ARG
-    assert step([tensor(reserved=101)], flags=128) == B.SR_ERR_ARG           # m_exp out of range
-    assert step([tensor(reserved=(256 - 101) << 8)], flags=128) == B.SR_ERR_ARG   # v_exp = -101
+    assert step([tensor(reserved=1)], flags=128) == B.SR_ERR_ARG
+    assert step([tensor(m_exp=101)], flags=128) == B.SR_ERR_ARG              # scale exponents lie in [-100, 100]
+    assert step([tensor(v_exp=-101)], flags=128) == B.SR_ERR_ARG
+    assert step([tensor(m_exp=1)]) == B.SR_ERR_ARG                           # and are zero without 8-bit moments
+    assert step([tensor(v_exp=-1)], flags=B.SR_FLAG_RNE_MOMENTS) == B.SR_ERR_ARG
     # comparison strategies: exact flag combinations and an aux tensor are required
     assert step([t], flags=B.SR_FLAG_MASTER_FP32) == B.SR_ERR_ARG
     assert step([t], flags=B.SR_FLAG_KAHAN | B.SR_FLAG_FP32_MOMENTS) == B.SR_ERR_ARG
@@ -230,3 +232,27 @@ def test_accumulate_argument_errors():
     assert call() == B.SR_ERR_ARG
     assert call(n=0) == B.SR_OK
     assert L.sr_accumulate_workspace_bytes(3, 10 ** 9) >= 8 * (10 ** 9 // 512 + 3)
+
+
+def test_accumulate_workspace_bound_covers_ragged_tensors_at_odd_offsets():
+    """Many tensors just under a chunk, each starting mid-block in the counter, span two chunks
+    each: the documented bound must cover the partial sums they need (one per chunk of 512
+    elements, counted from the counter block that holds the tensor's first element), and on a GPU
+    box a workspace of exactly that size must be accepted."""
+    L = B.lib()
+    n, numel, off = 177, 506, 7
+    blocks = ((off + numel - 1) >> 3) - (off >> 3) + 1
+    chunks = n * ((blocks + 63) // 64)
+    assert chunks == 2 * n
+    need = L.sr_accumulate_workspace_bytes(n, n * numel)
+    assert need >= 8 * chunks
+    if not HAVE_GPU:
+        return
+    arr = (B.SrAccum * n)()
+    for i in range(n):
+        arr[i].acc, arr[i].grad, arr[i].numel = buf(2 * 512), buf(2 * 512), numel
+        arr[i].elem_offset, arr[i].tensor_id, arr[i].reserved = off, i, 0
+    out, ws = buf(4), buf(need)
+    assert L.sr_grad_accumulate(arr, n, 1.0, 1, 0, 0, out, ws, need, None) == B.SR_OK
+    torch.cuda.synchronize()
+    assert L.sr_grad_accumulate(arr, n, 1.0, 1, 0, 0, out, ws, 8 * chunks - 8, None) == B.SR_ERR_WORKSPACE

@@ -123,21 +123,30 @@ def test_fp8_cast_wave_with_a_value_near_the_top_of_the_range(gfmt, ofmt):
     assert bad.size == 0, (hex(int(bits[bad[0]])), got[bad[0]], want[bad[0]])
 
 
-@pytest.mark.skipif(os.environ.get("SR_TEST_EXHAUSTIVE") != "1",
-                    reason="three minutes of oracle time; set SR_TEST_EXHAUSTIVE=1 to run")
+STRIDE = int(os.environ.get("SR_TEST_FP8_STRIDE", "5"))       # 1 = every encoding (three minutes of oracle time)
+
+
 @pytest.mark.parametrize("gfmt,ofmt", FMTS)
-def test_fp8_cast_all_binary32_encodings(gfmt, ofmt):
-    """Every one of the 2^32 binary32 encodings, in 32 pieces (waves of consecutive encodings share
-    an exponent, so all of them below the top binade take the conversion instruction and all above
-    it the integer path)."""
+def test_fp8_cast_sweep_of_all_encodings_through_both_paths(gfmt, ofmt):
+    """Every STRIDE-th of the 2^32 binary32 encodings (an odd stride meets every pattern of the low
+    bits), in 32 pieces, converted twice: by the library as it runs (waves of neighbouring
+    encodings share an exponent, so all below the format's top binade take the chip's conversion
+    instruction and all above it the integer path) and with the test switch that sends every wave
+    down the integer path.  The by-value oracle is computed once per piece and both must equal it:
+    the instruction and the integer path are two implementations of the rule the oracle defines."""
     piece = 1 << 27
-    for c in range(32):
-        bits = torch.arange(c * piece, (c + 1) * piece, dtype=torch.int64, device=DEV).to(torch.int32)
-        x = bits.view(torch.float32)
-        got = gpu_cast(x, gfmt, 0xABCDEF, 5 + c, 2)
-        want = ref.sr_cast_f32_fp8(x.cpu().numpy(), ofmt, 0xABCDEF, 5 + c, 2)
-        bad = np.flatnonzero(got != want)
-        assert bad.size == 0, (c, hex(c * piece + int(bad[0])), got[bad[0]], want[bad[0]])
+    try:
+        for c in range(32):
+            bits = torch.arange(c * piece, (c + 1) * piece, STRIDE, dtype=torch.int64, device=DEV).to(torch.int32)
+            x = bits.view(torch.float32)
+            want = ref.sr_cast_f32_fp8(x.cpu().numpy(), ofmt, 0xABCDEF, 5 + c, 2)
+            for integer_path in (0, 1):
+                B.lib().sr_debug_set(B.SR_DEBUG_FP8_INTEGER, integer_path)
+                got = gpu_cast(x, gfmt, 0xABCDEF, 5 + c, 2)
+                bad = np.flatnonzero(got != want)
+                assert bad.size == 0, (integer_path, c, hex(c * piece + STRIDE * int(bad[0])), got[bad[0]], want[bad[0]])
+    finally:
+        B.lib().sr_debug_set(B.SR_DEBUG_FP8_INTEGER, 0)
 
 
 @pytest.mark.parametrize("gfmt,ofmt", FMTS)

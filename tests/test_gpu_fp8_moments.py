@@ -111,6 +111,25 @@ def test_fp8_moments_many_steps_with_clip_and_offsets():
     assert used_m > 60 and used_v > 20                        # the state really lives on the 8-bit grids
 
 
+def test_fp8_moments_write_back_through_the_integer_path_only():
+    """The test switch that sends every wave's 8-bit write-back down the integer path (no conversion
+    instruction): the same scenarios must still equal the oracle, so the chip's scaled conversions
+    and the integer path are shown to compute one function on the same inputs."""
+    B.lib().sr_debug_set(B.SR_DEBUG_FP8_INTEGER, 1)
+    try:
+        st = State([512 * 5 + 3, 1021], [(12, 30), (-2, 9)], seed=31)
+        st.step(2, 0xC0FFEE, g_scale=4.0)
+        st.check("every code, integer path")
+        st = State([4096 + 5, 77, 8, 1], [(14, 33), (10, 26), (0, 0), (14, 33)], seed=5, offsets=[3, 8, 16, 7],
+                   ids=[7, 2, 9, 4], codes="zero", views=3)
+        for t in range(1, 11):
+            st.step(t, 17, g_scale=3.0, norm=2.5, max_norm=1.0, flags=B.SR_FLAG_RNE_PARAMS if t % 2 else 0)
+            st.check(f"integer path step {t}")
+        assert np.unique(st.host[0]["m"]).size > 60
+    finally:
+        B.lib().sr_debug_set(B.SR_DEBUG_FP8_INTEGER, 0)
+
+
 def test_fp8_moments_top_of_range_and_nan_gradients():
     """Scales chosen too large on purpose: m saturates at 448 and v at 57344; NaN and infinite
     gradients; every wave holds some of each, so the integer path and the conversion instruction
@@ -196,7 +215,7 @@ def test_fp8_moments_arguments():
             B.sr_adamw_step(tl, HYP, 1, 0, bad)
     with pytest.raises(ValueError):
         B.TensorList([p], [p.clone()], [m8], [m8.clone()], fp8_exponents=[(101, 0)])
-    tl.array[0].reserved = 0x10000
+    tl.array[0].reserved = 1
     with pytest.raises(B.SrError):
         B.sr_adamw_step(tl, HYP, 1, 0, FP8)
 
@@ -249,11 +268,11 @@ def test_stream_probe_of_the_8_bit_moment_pattern_leaves_the_data_unchanged():
     v8 = torch.randint(0, 128, (n,), dtype=torch.uint8, device=DEV)
     before = [t.clone() for t in (p, g, m8, v8)]
     B.sr_stream_probe_fp8m(p, g, m8, v8)
-    B.lib().sr_debug_set_launch_limit(3)                          # and cut into several launches
+    B.lib().sr_debug_set(B.SR_DEBUG_LAUNCH_LIMIT, 3)                          # and cut into several launches
     try:
         B.sr_stream_probe_fp8m(p, g, m8, v8)
     finally:
-        B.lib().sr_debug_set_launch_limit(0)
+        B.lib().sr_debug_set(B.SR_DEBUG_LAUNCH_LIMIT, 0)
     torch.cuda.synchronize()
     for t, b in zip((p, g, m8, v8), before):
         assert torch.equal(t.view(torch.uint8), b.view(torch.uint8))

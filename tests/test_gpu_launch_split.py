@@ -1,6 +1,6 @@
 """Jobs larger than one dispatch (2^32 - 1 work-items) are cut into several launches, tensors into
 pieces at counter-block boundaries.  The hardware limit needs tens of billions of elements to
-reach; sr_debug_set_launch_limit lowers it so that small inputs take the same host paths.  Every
+reach; sr_debug_set(SR_DEBUG_LAUNCH_LIMIT, n) lowers it so that small inputs take the same host paths.  Every
 entry point must give the bits it gives in one launch -- which the other tests pin to the oracle."""
 import numpy as np
 import pytest
@@ -18,8 +18,8 @@ DEV = "cuda"
 
 @pytest.fixture
 def limit():
-    yield lambda n: B.lib().sr_debug_set_launch_limit(n)
-    B.lib().sr_debug_set_launch_limit(0)
+    yield lambda n: B.lib().sr_debug_set(B.SR_DEBUG_LAUNCH_LIMIT, n)
+    B.lib().sr_debug_set(B.SR_DEBUG_LAUNCH_LIMIT, 0)
 
 
 @pytest.mark.parametrize("mode", ["sr", "fp32", "kahan", "master"])

@@ -225,10 +225,25 @@ def test_adamw_gpt_list_ten_steps_bit_exact():
 
 
 def test_adamw_more_tensors_than_one_launch_batch():
-    cfg = W.config(2)
-    shapes = W.gpt_shapes(24, 12, 40, 101, 16)          # 148 tensors -> three launches
-    assert len(shapes) == 148
-    run_config(cfg, shapes, 3)
+    """A launch takes 320 tensors (update, accumulation) or 400 (norm): a list of 868 tensors is
+    three launches of each, with clipping so that the norm's batches are cut too; then the same
+    list through the accumulation with the fused norm."""
+    cfg = W.config(3)
+    shapes = W.gpt_shapes(24, 72, 40, 101, 16)
+    assert len(shapes) == 868
+    pair = run_config(cfg, shapes, 2)
+    micro = [torch.empty_like(g) for g in pair.g]
+    W.fill_grads(micro, 61, cfg.grad_std)
+    al = B.AccumList(pair.g, micro)
+    ws = torch.empty(max(al.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
+    host = [to_np(g) for g in pair.g]
+    B.sr_grad_accumulate(al, 0.5, 7, 3, 0, pair.norm, ws)
+    torch.cuda.synchronize()
+    for i, h in enumerate(host):
+        ref.grad_accumulate(h, to_np(micro[i]), 0.5, 7, 3, tensor_id=i)
+        assert bool(np.all(to_np(pair.g[i]) == h)), f"accumulate tensor {i}"
+    want, got = ref.grad_global_norm(host), float(pair.norm.item())
+    assert got == want or abs(got - want) <= 1e-6 * want
 
 
 def test_adamw_clip_with_outliers_bit_exact():
@@ -236,6 +251,41 @@ def test_adamw_clip_with_outliers_bit_exact():
     shapes = W.gpt_shapes(64, 2, 256, 5003, 64)
     pair = run_config(cfg, shapes, 10)
     assert float(pair.norm.item()) > 10.0                  # clipping is strongly active
+
+
+@pytest.mark.parametrize("fp32", [False, True])
+def test_adamw_skips_the_step_on_a_nonfinite_norm(fp32):
+    """SR_FLAG_SKIP_NONFINITE_NORM: a NaN or infinite norm (here from a planted NaN / infinite
+    gradient, through grad_global_norm) leaves p, m, v untouched on both sides; with a finite
+    norm the flag changes nothing; without the flag the poisoned step is applied as the clip
+    formula says (NaN everywhere, or a zero gradient scale) and still equals the oracle."""
+    cfg = W.config(4 if fp32 else 3)
+    shapes = W.gpt_shapes(48, 1, 192, 1001, 32)
+    pair = make_pair(cfg, shapes)
+    SKIP = B.SR_FLAG_SKIP_NONFINITE_NORM
+    W.fill_grads(pair.g, W.data_seed(3, 1), cfg.grad_std)
+    pair.step(cfg.hyper, 1, 9, clip=1.0, flags=SKIP)                  # finite norm: an ordinary step
+    pair.compare("finite norm with the guard")
+    assert not bool(np.all(to_np(pair.m[0]).view(np.uint8) == 0))
+    for t, bad in ((2, float("nan")), (3, float("inf")), (4, float("-inf"))):
+        W.fill_grads(pair.g, W.data_seed(3, t), cfg.grad_std)
+        pair.g[2][5] = bad
+        before = [(to_np(p), to_np(m), to_np(v)) for p, m, v in zip(pair.p, pair.m, pair.v)]
+        pair.step(cfg.hyper, t, 9, clip=1.0, flags=SKIP, check_norm=False)
+        assert not np.isfinite(pair.norm.item())
+        for (p0, m0, v0), p, m, v in zip(before, pair.p, pair.m, pair.v):
+            for a, b in ((p0, p), (m0, m), (v0, v)):
+                assert bool(np.all(a.view(np.uint8) == to_np(b).view(np.uint8)))
+        pair.compare(f"skipped step {t}")
+    # without the guard: an infinite norm scales the gradient to zero, a NaN norm poisons the state
+    W.fill_grads(pair.g, W.data_seed(3, 5), cfg.grad_std)
+    pair.g[2][5] = float("inf")
+    pair.step(cfg.hyper, 5, 9, clip=1.0, check_norm=False)
+    pair.compare("unguarded infinite norm")
+    pair.g[2][5] = float("nan")
+    pair.step(cfg.hyper, 6, 9, clip=1.0, check_norm=False)
+    pair.compare("unguarded NaN norm")
+    assert bool(np.all(is_nan16(to_np(pair.p[0]))))
 
 
 def test_adamw_fp32_moments_clip_bit_exact():

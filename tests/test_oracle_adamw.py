@@ -76,6 +76,39 @@ def test_clip_coefficient():
     assert np.isnan(s.clip)
 
 
+def test_guard_against_a_nonfinite_norm():
+    """FLAG_SKIP_NONFINITE_NORM: a NaN or infinite norm leaves the state as it is (whatever the
+    other flags), a finite one gives exactly the unguarded step; without the guard a NaN norm
+    poisons every output and an infinite one is a step with a zero gradient."""
+    n = 1000
+    for flags in (0, ref.FLAG_FP32_MOMENTS, ref.FLAG_RNE_MOMENTS):
+        def state():
+            p, g = make_state(n, 5)
+            if flags & ref.FLAG_FP32_MOMENTS:
+                m, v = np.full(n, 1e-3, np.float32), np.full(n, 1e-6, np.float32)
+            else:
+                m, v = to_bf16_bits_trunc(np.full(n, 1e-3)), to_bf16_bits_trunc(np.full(n, 1e-6))
+            return dict(p=p, g=g, m=m, v=v)
+        for norm in (float("nan"), float("inf"), float("-inf")):
+            t, t0 = state(), state()
+            ref.sr_adamw_step([t], HYP, 3, 1, flags | ref.FLAG_SKIP_NONFINITE_NORM, norm=norm, max_norm=1.0)
+            assert all(np.array_equal(t[k].view(np.uint8), t0[k].view(np.uint8)) for k in "pmv")
+        a, b = state(), state()
+        ref.sr_adamw_step([a], HYP, 3, 1, flags | ref.FLAG_SKIP_NONFINITE_NORM, norm=2.5, max_norm=1.0)
+        ref.sr_adamw_step([b], HYP, 3, 1, flags, norm=2.5, max_norm=1.0)
+        assert all(np.array_equal(a[k].view(np.uint8), b[k].view(np.uint8)) for k in "pmv")
+        assert not np.array_equal(a["p"], state()["p"])
+        # unguarded: infinite norm = the same step with a zero gradient and no clipping
+        c, d = state(), state()
+        ref.sr_adamw_step([c], HYP, 3, 1, flags, norm=float("inf"), max_norm=1.0)
+        d["g"] = np.zeros(n, np.uint16)
+        ref.sr_adamw_step([d], HYP, 3, 1, flags)
+        assert all(np.array_equal(c[k].view(np.uint8), d[k].view(np.uint8)) for k in "pmv")
+        e = state()
+        ref.sr_adamw_step([e], HYP, 3, 1, flags, norm=float("nan"), max_norm=1.0)
+        assert np.all(np.isnan(val(e["p"])))
+
+
 # ----------------------------------------------------- step-1 closed form
 
 def test_step1_closed_form():
