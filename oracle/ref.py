@@ -22,6 +22,7 @@ FLAG_EPS_IN_ROOT = 32
 FLAG_DIV_BIAS = 64
 FLAG_FP8_MOMENTS = 128
 FLAG_SKIP_NONFINITE_NORM = 256
+FLAG_FP8_PARAMS = 512
 
 STREAM_PARAM, STREAM_M, STREAM_V, STREAM_CAST, STREAM_ACC = 0, 1, 2, 3, 4
 ACC_RNE = 1
@@ -85,6 +86,10 @@ def lib():
                                                C.POINTER(Scalars), C.c_uint32, C.c_uint64, C.c_uint32,
                                                C.c_int, C.c_int, C.c_int]
         L.ref_sr_adamw_tensor_fp8m.restype = None
+        L.ref_sr_adamw_tensor_fp8p.argtypes = [u8p, u16p, u16p, u16p, u8p, u8p, C.c_uint64, C.c_uint32, C.c_uint64,
+                                               C.POINTER(Scalars), C.c_uint32, C.c_uint64, C.c_uint32,
+                                               C.c_int, C.c_int, C.c_int, C.c_int]
+        L.ref_sr_adamw_tensor_fp8p.restype = None
         L.ref_adamw_unrounded_fp8m.argtypes = [u16p, u16p, u8p, u8p, C.c_uint64, C.POINTER(Scalars),
                                                C.c_uint32, C.c_int, C.c_int, f32p, f32p, f32p]
         L.ref_adamw_unrounded_fp8m.restype = None
@@ -269,6 +274,20 @@ def sr_adamw_tensor_fp8m(p, g, m8, v8, tensor_id, scalars: Scalars, step, seed, 
                                    C.byref(scalars), step, seed, flags, m_exp, v_exp, nthreads)
 
 
+def sr_adamw_tensor_fp8p(p8, g, m, v, tensor_id, scalars: Scalars, step, seed, p_exp, flags=0,
+                         m_exp=0, v_exp=0, elem_offset=0, nthreads=0):
+    """One tensor with the parameter held as E4M3 codes p8 (of p * 2^p_exp), in place over p8, m, v.
+    m, v are BF16 bit patterns (uint16), or 8-bit codes (uint8: E4M3 m, E5M2 v, with m_exp, v_exp)."""
+    assert p8.dtype == np.uint8 and p8.size == g.size == m.size == v.size
+    assert abs(p_exp) <= 100 and abs(m_exp) <= 100 and abs(v_exp) <= 100
+    if m.dtype == np.uint8:
+        lib().ref_sr_adamw_tensor_fp8p(_u8(p8), _u16(g), None, None, _u8(m), _u8(v), p8.size, tensor_id, elem_offset,
+                                       C.byref(scalars), step, seed, flags, p_exp, m_exp, v_exp, nthreads)
+    else:
+        lib().ref_sr_adamw_tensor_fp8p(_u8(p8), _u16(g), _u16(m), _u16(v), None, None, p8.size, tensor_id, elem_offset,
+                                       C.byref(scalars), step, seed, flags, p_exp, 0, 0, nthreads)
+
+
 def adamw_unrounded_fp8m(p, g, m8, v8, scalars: Scalars, m_exp, v_exp, flags=0):
     n = p.size
     y, m1, v1 = np.empty(n, np.float32), np.empty(n, np.float32), np.empty(n, np.float32)
@@ -289,7 +308,11 @@ def sr_adamw_step(tensors, hyper, step, seed, flags=0, norm=None, max_norm=0.0, 
             return s
         flags &= ~FLAG_SKIP_NONFINITE_NORM
     for idx, t in enumerate(tensors):
-        if flags & FLAG_FP8_MOMENTS:
+        if flags & FLAG_FP8_PARAMS:
+            sr_adamw_tensor_fp8p(t["p"], t["g"], t["m"], t["v"], t.get("tensor_id", idx), s, step, seed, t["p_exp"],
+                                 flags & ~(FLAG_FP8_PARAMS | FLAG_FP8_MOMENTS), t.get("m_exp", 0), t.get("v_exp", 0),
+                                 t.get("elem_offset", 0), nthreads)
+        elif flags & FLAG_FP8_MOMENTS:
             sr_adamw_tensor_fp8m(t["p"], t["g"], t["m"], t["v"], t.get("tensor_id", idx), s, step, seed,
                                  t["m_exp"], t["v_exp"], flags & ~FLAG_FP8_MOMENTS, t.get("elem_offset", 0), nthreads)
         else:

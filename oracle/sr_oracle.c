@@ -539,6 +539,57 @@ void ref_sr_adamw_tensor_fp8m(uint16_t* p, const uint16_t* g, uint8_t* m8, uint8
     }
 }
 
+/* Extension, one step further: the PARAMETER held in 8 bits too (the write-back the paper's
+ * conclusion points to; the paper gives no design).  p8 holds E4M3 codes, one byte per
+ * element, with a power-of-two scale per tensor:
+ *     p = decode(p8) * 2^-p_exp                                              (exact)
+ *     y, m1, v1 by adamw_element as for every other strategy
+ *     p8 <- Q_SR,E4M3(y * 2^p_exp)        (a binary32 multiplication, then Eq.(2) on the grid)
+ * Q_SR is ref_sr_round_fp8 with the element's full 32-bit word of output stream 0 (word
+ * i mod 4 of Philox block i div 4, the layout of the standalone 8-bit cast): the draw has the
+ * 20 bits binary32 keeps below E4M3's mantissa, so the probability is Eq.(2)'s exactly for every
+ * scaled value at or above 2^-6.  E4M3 has no infinity: scaled magnitudes from 448 upwards
+ * are stored as 448; NaN becomes the NaN code.  The moments are BF16 with SR (streams 1, 2,
+ * 16-bit draws, as in ref_sr_adamw_tensor) when m8 is NULL -- then m16, v16 are used -- or
+ * 8-bit codes exactly as in ref_sr_adamw_tensor_fp8m when m8, v8 are given. */
+void ref_sr_adamw_tensor_fp8p(uint8_t* p8, const uint16_t* g, uint16_t* m16, uint16_t* v16,
+                              uint8_t* m8, uint8_t* v8,
+                              uint64_t numel, uint32_t tensor_id, uint64_t elem_offset,
+                              const ref_scalars_t* s, uint32_t step, uint64_t seed,
+                              uint32_t flags, int p_exp, int m_exp, int v_exp, int nthreads)
+{
+    const int fp8m = m8 != NULL;
+    const float p_scale = (float)ldexp(1.0, p_exp);
+    const float m_scale = (float)ldexp(1.0, m_exp), v_scale = (float)ldexp(1.0, v_exp);
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+    #pragma omp parallel for schedule(static)
+    for (int64_t ii = 0; ii < (int64_t)numel; ++ii) {
+        uint64_t i = (uint64_t)ii;
+        uint64_t gi = elem_offset + i;
+        float pi = (float)ldexp(ref_fp8_decode(p8[i], 0), -p_exp);
+        float gr = bf16_bits_to_float(g[i]);
+        float mi = fp8m ? (float)ldexp(ref_fp8_decode(m8[i], 0), -m_exp) : bf16_bits_to_float(m16[i]);
+        float vi = fp8m ? (float)ldexp(ref_fp8_decode(v8[i], 1), -v_exp) : bf16_bits_to_float(v16[i]);
+        float y, m1, v1;
+        adamw_element(s, flags, pi, gr, mi, vi, &y, &m1, &v1, NULL);
+        float ys = y * p_scale;
+        p8[i] = ref_sr_round_fp8(ys, ref_r32(seed, step, tensor_id, gi, 0u), 0);
+        if (fp8m) {
+            float ms = m1 * m_scale;
+            float vs = v1 * v_scale;
+            m8[i] = ref_sr_round_fp8(ms, ref_r16(seed, step, tensor_id, gi, 1u) << 16, 0);
+            uint8_t vc = ref_sr_round_fp8(vs, ref_r16(seed, step, tensor_id, gi, 2u) << 16, 1);
+            if ((vc & 0x7Fu) == 0x7Cu) vc = (uint8_t)((vc & 0x80u) | 0x7Bu);
+            v8[i] = vc;
+        } else {
+            m16[i] = ref_sr_round(m1, ref_r16(seed, step, tensor_id, gi, 1u));
+            v16[i] = ref_sr_round(v1, ref_r16(seed, step, tensor_id, gi, 2u));
+        }
+    }
+}
+
 /* The unrounded results of the same step (for the checks of its arithmetic). */
 void ref_adamw_unrounded_fp8m(const uint16_t* p, const uint16_t* g, const uint8_t* m8, const uint8_t* v8,
                               uint64_t numel, const ref_scalars_t* s, uint32_t flags, int m_exp, int v_exp,
