@@ -32,6 +32,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published peak
 #   kahan         BF16 p,g,m,v,c read + p,m,v,c written                    10 + 8  = 18
 #   master        x32,g,m32,v32 read + x32,p16,m32,v32 written (O2 style)  14 + 14 = 28
 #   fp8_moments   2+2+1+1 read, 2+1+1 written (extension: E4M3 m, E5M2 v)   6 + 4  = 10
+#   fp8_params    1+2+2+2 read, 1+2+2 written (extension: E4M3 p)           7 + 5  = 12
+#   fp8_all       1+2+1+1 read, 1+1+1 written (extension: both)             5 + 3  = 8
 MODES = {
     "sr": ((), False, None, 14),
     "rne_moments": (("SR_FLAG_RNE_MOMENTS",), False, None, 14),
@@ -40,6 +42,9 @@ MODES = {
     "kahan": (("SR_FLAG_KAHAN",), False, "bf16", 18),
     "master": (("SR_FLAG_MASTER_FP32", "SR_FLAG_FP32_MOMENTS"), True, "f32", 28),
     "fp8_moments": (("SR_FLAG_FP8_MOMENTS",), False, None, 10),
+    # extension: the parameter as E4M3 codes too (1+2+2+2 read, 1+2+2 written; with 8-bit moments 1+2+1+1 and 1+1+1)
+    "fp8_params": (("SR_FLAG_FP8_PARAMS",), False, None, 12),
+    "fp8_all": (("SR_FLAG_FP8_PARAMS", "SR_FLAG_FP8_MOMENTS"), False, None, 8),
 }
 
 
@@ -140,7 +145,7 @@ def algorithmic_bytes_per_element(mode, clip) -> int:
     return MODES[mode][3] + (2 if clip is not None else 0)
 
 
-def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags, fp8_exps=None, norm=None):
+def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags, fp8_exps=None, norm=None, p_exp=None):
     """Time the CPU oracle (as it stands) on a bounded window of the same workload and check the
     GPU against it on that window.  `state` holds flat device tensors p, g, m, v, aux (first
     tensor; aux may be None).  `flags`: the step's flag bits (same values on both sides).
@@ -159,6 +164,8 @@ def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags, fp8_exp
         d = dict(p=cp(p), g=cp(g), m=cp(m), v=cp(v), tensor_id=0, elem_offset=lo)
         if fp8_exps is not None:
             d["m_exp"], d["v_exp"] = fp8_exps
+        if p_exp is not None:
+            d["p_exp"] = p_exp
         if aux is not None:
             d["aux"] = cp(aux)
         return d
@@ -169,7 +176,7 @@ def cpu_baseline(W, B, torch, cfg, state, step_no, seed, seconds, flags, fp8_exp
     # the workload's share of updates below one BF16 spacing of the parameter (what nearest rounding
     # would mostly lose; Section 2.2), from the oracle's unrounded result on this window
     sub_ulp = None
-    if aux is None:
+    if aux is None and p_exp is None:
         sc = ref.adamw_scalars(step=step_no, norm=norm, max_norm=max_norm, **cfg.hyper)
         if fp8_exps is not None:
             y, _, _ = ref.adamw_unrounded_fp8m(w0["p"], w0["g"], w0["m"], w0["v"], sc, *fp8_exps)
@@ -374,18 +381,36 @@ def main():
     else:
         params = W.make_params(cfg.shapes, dev, W.data_seed(cfg.index, 0), cfg.param_std)
         ms, vs = W.make_moments(cfg.shapes, dev, fp32_moments)
-        if mode == "fp8_moments":
+        if mode in ("fp8_moments", "fp8_all"):
             fp8_exps = fp8_scale_exponents(cfg)
             ms = [torch.zeros(m.numel(), dtype=torch.uint8, device=dev) for m in ms]
             vs = [torch.zeros(v.numel(), dtype=torch.uint8, device=dev) for v in vs]
         grads = [torch.empty_like(p) for p in params]
+    p_exp = None
+    if mode in ("fp8_params", "fp8_all"):
+        # the weights onto the E4M3 grid with the library's own stochastic cast: eight standard
+        # deviations (gains of 1 included) map to the top of the format
+        import math
+        p_exp = int(math.floor(math.log2(448.0 / max(8.0 * cfg.param_std, 1.0))))
+        p8s = []
+        for i, p_ in enumerate(params):
+            q = torch.empty(p_.numel(), dtype=torch.uint8, device=dev)
+            for at in range(0, p_.numel(), 1 << 28):
+                piece = p_[at:at + (1 << 28)].float() * float(2.0 ** p_exp)
+                B.sr_cast_f32_fp8(piece, q[at:at + (1 << 28)], B.SR_FP8_E4M3, cfg.seed, 0, i)
+            p8s.append(q)
+        torch.cuda.synchronize()
+        params = p8s
+        del p8s
+        torch.cuda.empty_cache()
     aux = None
     if aux_kind == "f32":
         aux = [p.float() for p in params]                 # binary32 master parameters
     elif aux_kind == "bf16":
         aux = [torch.zeros_like(p) for p in params]       # Kahan compensation starts at zero
     tl = B.TensorList(params, grads, ms, vs, fp32_moments, aux=aux,
-                      fp8_exponents=None if fp8_exps is None else [fp8_exps] * len(params))
+                      fp8_exponents=None if fp8_exps is None else [fp8_exps] * len(params),
+                      fp8_param_exponents=None if p_exp is None else [p_exp] * len(params))
     norm = torch.zeros(1, dtype=torch.float32, device=dev)
     ws = torch.empty(max(tl.workspace_bytes(), 256), dtype=torch.uint8, device=dev)
     numel = tl.total_numel
@@ -420,7 +445,7 @@ def main():
             nv = float(norm.item())
         cpu, check = cpu_baseline(W, B, torch, cfg, (params[0], grads[0], ms[0], vs[0],
                                                      None if aux is None else aux[0]), t, cfg.seed,
-                                  args.cpu_seconds, flags, fp8_exps, nv)
+                                  args.cpu_seconds, flags, fp8_exps, nv, p_exp)
 
     # the step the oracle reproduced, then the parity check of that window
     parity = "not checked"
@@ -428,7 +453,7 @@ def main():
         one_step(t)
         torch.cuda.synchronize()
         lo, n, w = check
-        got_p = W.bf16_to_u16_numpy(params[0][lo:lo + n])
+        got_p = params[0][lo:lo + n].cpu().numpy() if p_exp is not None else W.bf16_to_u16_numpy(params[0][lo:lo + n])
         bad = int((got_p != w["p"]).sum())
         if fp32_moments or fp8_exps is not None:
             bad += int((ms[0][lo:lo + n].cpu().numpy().view(np.uint32 if fp32_moments else np.uint8)
@@ -490,7 +515,7 @@ def main():
     # ceiling of the access pattern on these very buffers: the step's 4-read/3-write traffic with
     # no arithmetic (BF16 strategies without an auxiliary tensor, flat or list alike)
     ceiling = None
-    if MODES[mode][3] == 14 or fp8_exps is not None:
+    if MODES[mode][3] == 14 or mode == "fp8_moments":
         def probe():
             for p_, g_, m_, v_ in zip(params, grads, ms, vs):
                 (B.sr_stream_probe_fp8m if fp8_exps is not None else B.sr_stream_probe)(p_, g_, m_, v_)
@@ -553,7 +578,8 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}", "numel": numel, "tensors": len(params),
-                   "mode": mode, "storage": "bf16 parameters and gradients", "moments": "fp32" if fp32_moments else "e4m3/e5m2" if fp8_exps else "bf16",
+                   "mode": mode, "storage": "bf16 gradients; parameters " + ("e4m3 codes, scale exponent %d" % p_exp if p_exp is not None else "bf16"),
+                   "moments": "fp32" if fp32_moments else "e4m3/e5m2" if fp8_exps else "bf16",
                    "fp8_scale_exponents": fp8_exps, "clip": cfg.clip,
                    "warm_steps": warm, "bytes_per_element": bpe, "hip_graph": bool(args.graph),
                    "placement": placement, "resident_waves_override": args.resident_waves or None},

@@ -119,17 +119,35 @@ extern "C" {
                                    the top half of the 32-bit random word of
                                    sr_cast_f32_fp8's rule (the fraction is cut to 16
                                    bits).  10 bytes moved per element instead of 14.
-                                   Combines with SR_FLAG_RNE_PARAMS, SR_FLAG_EPS_IN_ROOT
-                                   and SR_FLAG_DIV_BIAS only.  Both write-backs saturate:
+                                   Combines with SR_FLAG_RNE_PARAMS, SR_FLAG_FP8_PARAMS,
+                                   SR_FLAG_EPS_IN_ROOT and SR_FLAG_DIV_BIAS only.  Both write-backs saturate:
                                    a scaled m' beyond 448 is stored as 448, a scaled v'
                                    beyond 57344 (or one that Q_SR would round to E5M2's
                                    infinity) as 57344, so the state never holds an
                                    infinity.  NaN codes stay NaN codes; NaN signs and
                                    payloads are not specified.                          */
 
+#define SR_FLAG_FP8_PARAMS 512u /* extension, the 8-bit write-back of the parameter that the
+                                   paper's conclusion points to (no design is given there):
+                                   p is held as E4M3 codes, one byte per element, with a
+                                   power-of-two scale per tensor, p = decode(p8) 2^-p_exp;
+                                   the update as for every other strategy;
+                                   p8 <- Q_SR(y 2^p_exp) by the rule of sr_cast_f32_fp8
+                                   (Eq.(2) on the E4M3 grid, the 20-bit draw from the top of
+                                   the element's own 32-bit word: word i&3 of Philox block
+                                   i>>2 of stream 0, i = elem_offset + index).  Scaled
+                                   magnitudes from 448 upwards are stored as 448; NaN becomes
+                                   the NaN code.  m, v: BF16 with SR (12 bytes moved per
+                                   element), or with SR_FLAG_FP8_MOMENTS 8-bit codes (8
+                                   bytes).  Combines with SR_FLAG_FP8_MOMENTS,
+                                   SR_FLAG_EPS_IN_ROOT, SR_FLAG_DIV_BIAS and
+                                   SR_FLAG_SKIP_NONFINITE_NORM only; elem_offset + numel
+                                   must not exceed 2^63.                                  */
+
 /* One tensor of the multi-tensor list. */
 typedef struct sr_tensor {
-    void*       p;           /* BF16 [numel], in/out: parameters x_t                      */
+    void*       p;           /* BF16 [numel], in/out: parameters x_t (E4M3 codes, one byte
+                                each, with SR_FLAG_FP8_PARAMS)                            */
     const void* g;           /* BF16 [numel], in    : reduced gradient (Alg.1 line 4)     */
     void*       m;           /* BF16 or binary32 [numel], in/out: first moment (E4M3 codes,
                                 one byte each, with SR_FLAG_FP8_MOMENTS)                  */
@@ -146,7 +164,9 @@ typedef struct sr_tensor {
                                 [-100, 100]; must be 0 without that flag                  */
     int8_t      v_exp;       /* SR_FLAG_FP8_MOMENTS: v = decode(v8) 2^-v_exp, in
                                 [-100, 100]; must be 0 without that flag                  */
-    uint16_t    reserved;    /* must be 0                                                 */
+    int8_t      p_exp;       /* SR_FLAG_FP8_PARAMS: p = decode(p8) 2^-p_exp, in
+                                [-100, 100]; must be 0 without that flag                  */
+    uint8_t     reserved;    /* must be 0                                                 */
 } sr_tensor_t;
 
 /* Hyper-parameters of Algorithm 1: alpha_t, beta_1, beta_2, epsilon, lambda. */

@@ -24,6 +24,7 @@ SR_FLAG_EPS_IN_ROOT = 32
 SR_FLAG_DIV_BIAS = 64
 SR_FLAG_FP8_MOMENTS = 128
 SR_FLAG_SKIP_NONFINITE_NORM = 256
+SR_FLAG_FP8_PARAMS = 512
 
 SR_DEBUG_LAUNCH_LIMIT, SR_DEBUG_FP8_INTEGER, SR_DEBUG_RESIDENT_WAVES = 0, 1, 2
 
@@ -40,7 +41,7 @@ EXPORTS = ("sr_cast_f32_bf16", "sr_cast_f32_fp8", "grad_global_norm", "grad_glob
 class SrTensor(C.Structure):
     _fields_ = [("p", C.c_void_p), ("g", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
                 ("aux", C.c_void_p), ("numel", C.c_uint64), ("elem_offset", C.c_uint64),
-                ("tensor_id", C.c_uint32), ("m_exp", C.c_int8), ("v_exp", C.c_int8), ("reserved", C.c_uint16)]
+                ("tensor_id", C.c_uint32), ("m_exp", C.c_int8), ("v_exp", C.c_int8), ("p_exp", C.c_int8), ("reserved", C.c_uint8)]
 
 
 class SrAccum(C.Structure):
@@ -140,11 +141,14 @@ class TensorList:
                  tensor_ids: Optional[Sequence[int]] = None,
                  elem_offsets: Optional[Sequence[int]] = None,
                  aux: Optional[Sequence[torch.Tensor]] = None,
-                 fp8_exponents: Optional[Sequence[Tuple[int, int]]] = None):
+                 fp8_exponents: Optional[Sequence[Tuple[int, int]]] = None,
+                 fp8_param_exponents: Optional[Sequence[int]] = None):
         """aux: per-tensor auxiliary arrays for the comparison strategies -- float32 master
         parameters (SR_FLAG_MASTER_FP32) or bfloat16 Kahan compensation (SR_FLAG_KAHAN).
         fp8_exponents: per-tensor (m_exp, v_exp) for SR_FLAG_FP8_MOMENTS; ms and vs are then one
-        byte per element (uint8 or a torch float8 dtype)."""
+        byte per element (uint8 or a torch float8 dtype).
+        fp8_param_exponents: per-tensor p_exp for SR_FLAG_FP8_PARAMS; params are then one byte per
+        element too."""
         n = len(params)
         if not (len(grads) == len(ms) == len(vs) == n):
             raise ValueError("params, grads, ms, vs must have the same length")
@@ -155,6 +159,9 @@ class TensorList:
             mdt = None                                        # any one-byte dtype
         self.fp32_moments = fp32_moments
         self.fp8_moments = fp8_exponents is not None
+        self.fp8_params = fp8_param_exponents is not None
+        if self.fp8_params and (fp32_moments or aux is not None or len(fp8_param_exponents) != n):
+            raise ValueError("fp8_param_exponents: one p_exp per tensor, not with fp32_moments or aux tensors")
         self.n = n
         self.array = (SrTensor * max(n, 1))()
         self.keep = (list(params), list(grads), list(ms), list(vs), None if aux is None else list(aux))
@@ -164,7 +171,9 @@ class TensorList:
         self.total_numel = 0
         for i in range(n):
             p, g, m, v = params[i], grads[i], ms[i], vs[i]
-            _check_dev(p, torch.bfloat16, f"params[{i}]")
+            if self.fp8_params and p.element_size() != 1:
+                raise ValueError(f"params[{i}] must hold one byte per element")
+            _check_dev(p, p.dtype if self.fp8_params else torch.bfloat16, f"params[{i}]")
             _check_dev(g, torch.bfloat16, f"grads[{i}]")
             for name, x in (("ms", m), ("vs", v)):
                 if mdt is None and x.element_size() != 1:
@@ -186,7 +195,11 @@ class TensorList:
             e.numel = p.numel()
             e.elem_offset = 0 if elem_offsets is None else int(elem_offsets[i])
             e.tensor_id = i if tensor_ids is None else int(tensor_ids[i])
-            e.m_exp, e.v_exp, e.reserved = 0, 0, 0
+            e.m_exp, e.v_exp, e.p_exp, e.reserved = 0, 0, 0, 0
+            if self.fp8_params:
+                if not -100 <= int(fp8_param_exponents[i]) <= 100:
+                    raise ValueError("fp8 scale exponents must lie in [-100, 100]")
+                e.p_exp = int(fp8_param_exponents[i])
             if fp8_exponents is not None:
                 m_exp, v_exp = (int(x) for x in fp8_exponents[i])
                 if not (-100 <= m_exp <= 100 and -100 <= v_exp <= 100):
@@ -268,6 +281,8 @@ def sr_adamw_step(tl: TensorList, hyper: dict, step: int, seed: int, flags: int 
         raise ValueError("SR_FLAG_FP32_MOMENTS does not match the moment dtype of the list")
     if bool(flags & SR_FLAG_FP8_MOMENTS) != tl.fp8_moments:
         raise ValueError("SR_FLAG_FP8_MOMENTS needs a list built with fp8_exponents (and only such a list)")
+    if bool(flags & SR_FLAG_FP8_PARAMS) != tl.fp8_params:
+        raise ValueError("SR_FLAG_FP8_PARAMS needs a list built with fp8_param_exponents (and only such a list)")
     if (flags & SR_FLAG_MASTER_FP32) and tl.n and tl.aux_dtype != torch.float32:
         raise ValueError("SR_FLAG_MASTER_FP32 needs float32 aux tensors in the list")
     if (flags & SR_FLAG_KAHAN) and tl.n and tl.aux_dtype != torch.bfloat16:

@@ -96,7 +96,8 @@ typedef v4u v4u_a4 __attribute__((aligned(4)));
 
 // DESC_VEC: elem_offset % 8 == 0, blocks of the RNG counter start at element 0.  With 8-bit moments
 // bits 8-15 and 16-23 hold the scale exponents of m and v (two's complement, |e| <= 100).
-enum : uint32_t { DESC_VEC = 1u, DESC_MEXP_SHIFT = 8u, DESC_VEXP_SHIFT = 16u };
+// With an 8-bit parameter bits 24-31 hold its scale exponent.
+enum : uint32_t { DESC_VEC = 1u, DESC_MEXP_SHIFT = 8u, DESC_VEXP_SHIFT = 16u, DESC_PEXP_SHIFT = 24u };
 
 struct TensorDesc {
     uint16_t* p;
@@ -517,6 +518,24 @@ __device__ __forceinline__ void fp8_moments_out(const float (&m)[8], const float
     vo.x = fp8_encode4_scaled<1>(vl, vrl, vs, vi, ranged); vo.y = fp8_encode4_scaled<1>(vh, vrh, vs, vi, ranged);
 }
 
+// The write-back of a lane's eight new parameters as E4M3 codes of y * 2^p_exp, each with the top
+// 20 bits of its own 32-bit random word (r0: elements 0-3, r1: elements 4-7); saturating at the
+// format's largest finite value.  `nan`: some value of the wave may be a NaN (wave-uniform).
+__device__ __forceinline__ v2u fp8_param_out(const float (&y)[8], int p_exp, const uint32_t (&r0)[4],
+                                             const uint32_t (&r1)[4], bool nan)
+{
+    float ymax = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ymax = __builtin_fmaxf(ymax, __builtin_fabsf(y[j]));
+    const bool ranged = nan || __builtin_amdgcn_ballot_w64(ymax >= pow2f(8 - p_exp)) != 0;   // wave-uniform
+    const float yl[4] = {y[0], y[1], y[2], y[3]}, yh[4] = {y[4], y[5], y[6], y[7]};
+    const float ps = pow2f(p_exp), pi = pow2f(-p_exp);
+    v2u o;
+    o.x = fp8_encode4_scaled<0>(yl, r0, ps, pi, ranged);
+    o.y = fp8_encode4_scaled<0>(yh, r1, ps, pi, ranged);
+    return o;
+}
+
 // ---------------------------------------------------------------------------- fused update
 
 // Variant of the step, from the ABI's flag bits (same values as SR_FLAG_* in sradamw.h).
@@ -526,6 +545,7 @@ struct Mode {
     static constexpr bool master = (F & 8u) != 0;                 // aux = binary32 master parameters
     static constexpr bool kahan  = (F & 16u) != 0;                // aux = BF16 Kahan compensation
     static constexpr bool fp8m   = (F & 128u) != 0;               // 8-bit moments: m E4M3, v E5M2, scaled
+    static constexpr bool fp8p   = (F & 512u) != 0;               // 8-bit parameter: E4M3 codes, scaled, SR
     static constexpr bool rnem   = !fp32m && !fp8m && (kahan || (F & 2u)); // BF16 moments rounded to nearest
     static constexpr bool rnep   = master || kahan || (F & 4u);   // BF16 parameter rounded to nearest
     static constexpr bool srm    = !fp32m && !fp8m && !rnem;      // BF16 moments stochastically rounded
@@ -671,7 +691,12 @@ __device__ __forceinline__ bool update_lane(LaneRegs<N>& L, const StepScalars& S
         for (int j = 0; j < N; ++j) lane_nan |= (y[j] != y[j]);
         nan = __builtin_amdgcn_ballot_w64(lane_nan) != 0;          // wave-uniform
     }
-    if (M::master) {
+    if (M::fp8p) {
+        // 8-bit parameter: the unrounded result goes back in L.aux (unused otherwise in this
+        // mode) for fp8_param_out, which needs a 32-bit random word per element
+#pragma unroll
+        for (int j = 0; j < N; ++j) L.aux[j] = y[j];
+    } else if (M::master) {
         // O2-style mixed precision: the master stays binary32, the model copy is RNE(master)
 #pragma unroll
         for (int j = 0; j < N; ++j) L.aux[j] = y[j];
@@ -773,11 +798,15 @@ __device__ __forceinline__ v2u words2(const uint32_t (&w)[2]) { v2u r; r.x = w[0
 // The random words of a lane's block for the three output streams (only those the mode uses).
 template <uint32_t F>
 __device__ __forceinline__ void block_draws(const TensorDesc& T, const StepScalars& S, uint64_t gblk,
-                                            u32x4& rp, u32x4& rm, u32x4& rv)
+                                            u32x4& rp, u32x4& rp2, u32x4& rm, u32x4& rv)
 {
     using M = Mode<F>;
-    rp = {}; rm = {}; rv = {};
-    if (!M::rnep) rp = block_bits(gblk, STREAM_P, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+    rp = {}; rp2 = {}; rm = {}; rv = {};
+    if (M::fp8p) {
+        // a 32-bit word per element: the parameter stream counts blocks of four elements here
+        rp = block_bits(2 * gblk, STREAM_P, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+        rp2 = block_bits(2 * gblk + 1, STREAM_P, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
+    } else if (!M::rnep) rp = block_bits(gblk, STREAM_P, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
     if (M::srm || M::fp8m) {
         rm = block_bits(gblk, STREAM_M, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
         rv = block_bits(gblk, STREAM_V, T.tensor_id, S.step, S.seed_lo, S.seed_hi);
@@ -794,7 +823,7 @@ __device__ __forceinline__ void inner_block(const TensorDesc& T, const StepScala
 {
     using M = Mode<F>;
     const uint32_t o16 = lane * 16u, o32 = lane * 32u;          // byte offsets in BF16 / binary32 arrays
-    const rsrc_t rp = chunk_rsrc<uint16_t>(T.p, lc0, span * 8u);
+    const rsrc_t rp = M::fp8p ? chunk_rsrc<uint8_t>(T.p, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.p, lc0, span * 8u);
     const rsrc_t rg = chunk_rsrc<uint16_t>(T.g, lc0, span * 8u);
     const rsrc_t rm = M::fp32m ? chunk_rsrc<float>(T.m, lc0, span * 8u)
                     : M::fp8m  ? chunk_rsrc<uint8_t>(T.m, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.m, lc0, span * 8u);
@@ -802,8 +831,9 @@ __device__ __forceinline__ void inner_block(const TensorDesc& T, const StepScala
                     : M::fp8m  ? chunk_rsrc<uint8_t>(T.v, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.v, lc0, span * 8u);
     const rsrc_t ra = M::master ? chunk_rsrc<float>(T.aux, lc0, span * 8u) : chunk_rsrc<uint16_t>(T.aux, lc0, span * 8u);
     v4u pq = {}, aq = {}, mq0 = {}, mq1 = {}, vq0 = {}, vq1 = {}, xq0 = {}, xq1 = {};
-    v2u m8 = {}, v8 = {};
-    if (!M::master) pq = buf_load16<NT>(rp, o16);
+    v2u m8 = {}, v8 = {}, p8 = {};
+    if (M::fp8p) p8 = buf_load8<NT>(rp, lane * 8u);
+    else if (!M::master) pq = buf_load16<NT>(rp, o16);
     const v4u gq = buf_load16<NT>(rg, o16);
     if (M::fp32m) {
         mq0 = buf_load16<NT>(rm, o32); mq1 = buf_load16<NT>(rm, o32 + 16u);
@@ -818,26 +848,30 @@ __device__ __forceinline__ void inner_block(const TensorDesc& T, const StepScala
     if (M::master) { xq0 = buf_load16<NT>(ra, o32); xq1 = buf_load16<NT>(ra, o32 + 16u); }
     if (M::kahan) aq = buf_load16<NT>(ra, o16);
 
-    u32x4 dp, dm, dv;
-    block_draws<F>(T, S, gblk, dp, dm, dv);
+    u32x4 dp, dp2, dm, dv;
+    block_draws<F>(T, S, gblk, dp, dp2, dm, dv);
 
     LaneRegs<8> L;
-    if (!M::master) unpack8(pq, L.p);
-    unpack8(gq, L.g);
     const int m_exp = (int)(int8_t)(T.flags >> DESC_MEXP_SHIFT), v_exp = (int)(int8_t)(T.flags >> DESC_VEXP_SHIFT);
+    const int p_exp = (int)(int8_t)(T.flags >> DESC_PEXP_SHIFT);
+    if (M::fp8p) fp8_decode8<0>(p8, pow2f(-p_exp), L.p);
+    else if (!M::master) unpack8(pq, L.p);
+    unpack8(gq, L.g);
     if (M::fp32m)     { floats8(mq0, mq1, L.m); floats8(vq0, vq1, L.v); }
     else if (M::fp8m) { fp8_decode8<0>(m8, pow2f(-m_exp), L.m); fp8_decode8<1>(v8, pow2f(-v_exp), L.v); }
     else              { unpack8(mq0, L.m); unpack8(vq0, L.v); }
     if (M::master) floats8(xq0, xq1, L.aux);
     if (M::kahan) unpack8(aq, L.aux);
     const bool nan = update_lane<F, CLIP, VAR, 8>(L, S, c, dp.w, dm.w, dv.w);
-    buf_store16<NT>(rp, o16, words4(L.po));
+    const bool integer_path = nan || (VAR && (S.variant & VARIANT_FP8_INTEGER));
+    if (M::fp8p) buf_store8<NT>(rp, lane * 8u, fp8_param_out(L.aux, p_exp, dp.w, dp2.w, integer_path));
+    else buf_store16<NT>(rp, o16, words4(L.po));
     if (M::fp32m) {
         buf_store16<NT>(rm, o32, bits4lo(L.m)); buf_store16<NT>(rm, o32 + 16u, bits4hi(L.m));
         buf_store16<NT>(rv, o32, bits4lo(L.v)); buf_store16<NT>(rv, o32 + 16u, bits4hi(L.v));
     } else if (M::fp8m) {
         v2u mo, vo;
-        fp8_moments_out(L.m, L.v, m_exp, v_exp, dm.w, dv.w, nan || (VAR && (S.variant & VARIANT_FP8_INTEGER)), mo, vo);
+        fp8_moments_out(L.m, L.v, m_exp, v_exp, dm.w, dv.w, integer_path, mo, vo);
         buf_store8<NT>(rm, lane * 8u, mo);
         buf_store8<NT>(rv, lane * 8u, vo);
     } else {
@@ -858,9 +892,11 @@ __device__ __forceinline__ void edge_block(const TensorDesc& T, const StepScalar
     using M = Mode<F>;
     const uint64_t numel = T.numel;
     LaneRegs<8> L;
-    if (!M::master) unpack8(load8_bf16<false>(T.p, l0, numel, false), L.p);
-    unpack8(load8_bf16<false>(T.g, l0, numel, false), L.g);
     const int m_exp = (int)(int8_t)(T.flags >> DESC_MEXP_SHIFT), v_exp = (int)(int8_t)(T.flags >> DESC_VEXP_SHIFT);
+    const int p_exp = (int)(int8_t)(T.flags >> DESC_PEXP_SHIFT);
+    if (M::fp8p) fp8_decode8<0>(load8_u8(reinterpret_cast<const uint8_t*>(T.p), l0, numel), pow2f(-p_exp), L.p);
+    else if (!M::master) unpack8(load8_bf16<false>(T.p, l0, numel, false), L.p);
+    unpack8(load8_bf16<false>(T.g, l0, numel, false), L.g);
     if (M::fp32m) {
         load8_f32<false>(static_cast<const float*>(T.m), l0, numel, false, L.m);
         load8_f32<false>(static_cast<const float*>(T.v), l0, numel, false, L.v);
@@ -873,16 +909,18 @@ __device__ __forceinline__ void edge_block(const TensorDesc& T, const StepScalar
     }
     if (M::master) load8_f32<false>(static_cast<const float*>(T.aux), l0, numel, false, L.aux);
     if (M::kahan) unpack8(load8_bf16<false>(static_cast<const uint16_t*>(T.aux), l0, numel, false), L.aux);
-    u32x4 dp, dm, dv;
-    block_draws<F>(T, S, gblk, dp, dm, dv);
+    u32x4 dp, dp2, dm, dv;
+    block_draws<F>(T, S, gblk, dp, dp2, dm, dv);
     const bool nan = update_lane<F, CLIP, VAR, 8>(L, S, c, dp.w, dm.w, dv.w);
-    store8_bf16<false>(T.p, l0, numel, false, words4(L.po));
+    const bool integer_path = nan || (VAR && (S.variant & VARIANT_FP8_INTEGER));
+    if (M::fp8p) store8_u8(reinterpret_cast<uint8_t*>(T.p), l0, numel, fp8_param_out(L.aux, p_exp, dp.w, dp2.w, integer_path));
+    else store8_bf16<false>(T.p, l0, numel, false, words4(L.po));
     if (M::fp32m) {
         store8_f32<false>(static_cast<float*>(T.m), l0, numel, false, L.m);
         store8_f32<false>(static_cast<float*>(T.v), l0, numel, false, L.v);
     } else if (M::fp8m) {
         v2u mo, vo;
-        fp8_moments_out(L.m, L.v, m_exp, v_exp, dm.w, dv.w, nan || (VAR && (S.variant & VARIANT_FP8_INTEGER)), mo, vo);
+        fp8_moments_out(L.m, L.v, m_exp, v_exp, dm.w, dv.w, integer_path, mo, vo);
         store8_u8(static_cast<uint8_t*>(T.m), l0, numel, mo);
         store8_u8(static_cast<uint8_t*>(T.v), l0, numel, vo);
     } else {

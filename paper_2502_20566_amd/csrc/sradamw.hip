@@ -123,7 +123,7 @@ hipError_t split_tensor(uint64_t numel, uint64_t elem_offset, uint64_t blocks_pe
 template <uint32_t F, bool VAR>
 hipError_t launch_adamw_v(bool clip, const AdamwBatch& batch, uint32_t n_chunks, hipStream_t stream)
 {
-    const uint32_t lds = occupancy_lds(Mode<F>::fp32m ? kWavesUpdateFp32 : Mode<F>::fp8m ? kWavesUpdateFp8
+    const uint32_t lds = occupancy_lds(Mode<F>::fp32m ? kWavesUpdateFp32 : (Mode<F>::fp8m || Mode<F>::fp8p) ? kWavesUpdateFp8
                                        : Mode<F>::kahan ? kWavesUpdateKahan : kWavesUpdateBf16);
     return clip ? launch_lds(adamw_kernel<F, true, kNT, VAR>, n_chunks, kThreads, lds, stream, batch)
                 : launch_lds(adamw_kernel<F, false, kNT, VAR>, n_chunks, kThreads, lds, stream, batch);
@@ -151,6 +151,8 @@ hipError_t launch_adamw_variant(uint32_t flags, bool clip, const AdamwBatch& b, 
         case SR_FLAG_KAHAN:                                   return launch_adamw<SR_FLAG_KAHAN>(clip, b, n, s);
         case SR_FLAG_FP8_MOMENTS:                             return launch_adamw<SR_FLAG_FP8_MOMENTS>(clip, b, n, s);
         case SR_FLAG_FP8_MOMENTS | SR_FLAG_RNE_PARAMS:        return launch_adamw<SR_FLAG_FP8_MOMENTS | SR_FLAG_RNE_PARAMS>(clip, b, n, s);
+        case SR_FLAG_FP8_PARAMS:                              return launch_adamw<SR_FLAG_FP8_PARAMS>(clip, b, n, s);
+        case SR_FLAG_FP8_PARAMS | SR_FLAG_FP8_MOMENTS:        return launch_adamw<SR_FLAG_FP8_PARAMS | SR_FLAG_FP8_MOMENTS>(clip, b, n, s);
         default:                                              return hipErrorInvalidValue;   // unreachable after validation
     }
 }
@@ -500,7 +502,7 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     if (step == 0) return SR_ERR_ARG;
     if (flags & ~(SR_FLAG_FP32_MOMENTS | SR_FLAG_RNE_MOMENTS | SR_FLAG_RNE_PARAMS | SR_FLAG_MASTER_FP32 |
                   SR_FLAG_KAHAN | SR_FLAG_EPS_IN_ROOT | SR_FLAG_DIV_BIAS | SR_FLAG_FP8_MOMENTS |
-                  SR_FLAG_SKIP_NONFINITE_NORM))
+                  SR_FLAG_SKIP_NONFINITE_NORM | SR_FLAG_FP8_PARAMS))
         return SR_ERR_ARG;
     // a guard of the clipped step, not a strategy: it selects no kernel
     const bool skip_nonfinite = (flags & SR_FLAG_SKIP_NONFINITE_NORM) != 0;
@@ -512,7 +514,8 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     flags &= ~(SR_FLAG_EPS_IN_ROOT | SR_FLAG_DIV_BIAS);
     if ((flags & SR_FLAG_MASTER_FP32) && flags != (SR_FLAG_MASTER_FP32 | SR_FLAG_FP32_MOMENTS)) return SR_ERR_ARG;
     if ((flags & SR_FLAG_KAHAN) && flags != SR_FLAG_KAHAN) return SR_ERR_ARG;
-    if ((flags & SR_FLAG_FP8_MOMENTS) && (flags & ~(SR_FLAG_FP8_MOMENTS | SR_FLAG_RNE_PARAMS))) return SR_ERR_ARG;
+    if ((flags & SR_FLAG_FP8_PARAMS) && (flags & ~(SR_FLAG_FP8_PARAMS | SR_FLAG_FP8_MOMENTS))) return SR_ERR_ARG;
+    if ((flags & SR_FLAG_FP8_MOMENTS) && (flags & ~(SR_FLAG_FP8_MOMENTS | SR_FLAG_RNE_PARAMS | SR_FLAG_FP8_PARAMS))) return SR_ERR_ARG;
     const sr_hyper_t h = *hyper;
     if (!std::isfinite(h.lr) || !std::isfinite(h.eps) || !std::isfinite(h.weight_decay) ||
         !std::isfinite(h.beta1) || !std::isfinite(h.beta2)) return SR_ERR_ARG;
@@ -528,7 +531,8 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     const bool master = (flags & SR_FLAG_MASTER_FP32) != 0;
     const bool kahan = (flags & SR_FLAG_KAHAN) != 0;
     const bool fp8m = (flags & SR_FLAG_FP8_MOMENTS) != 0;
-    const uintptr_t moment_align = fp32m ? 4 : fp8m ? 1 : 2;
+    const bool fp8p = (flags & SR_FLAG_FP8_PARAMS) != 0;
+    const uintptr_t moment_align = fp32m ? 4 : fp8m ? 1 : 2, param_align = fp8p ? 1 : 2;
 
     // Validate the whole list before anything is enqueued.
     for (uint32_t i = 0; i < n_tensors; ++i) {
@@ -539,13 +543,17 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
         } else if (t.m_exp != 0 || t.v_exp != 0) {
             return SR_ERR_ARG;
         }
+        if (fp8p ? (t.p_exp < -100 || t.p_exp > 100) : t.p_exp != 0) return SR_ERR_ARG;
         if (t.numel == 0) continue;
         if (!t.p || !t.g || !t.m || !t.v) return SR_ERR_NULL;
         if ((master || kahan) && !t.aux) return SR_ERR_NULL;
-        if (!aligned(t.p, 2) || !aligned(t.g, 2) || !aligned(t.m, moment_align) || !aligned(t.v, moment_align))
+        if (!aligned(t.p, param_align) || !aligned(t.g, 2) || !aligned(t.m, moment_align) || !aligned(t.v, moment_align))
             return SR_ERR_ALIGN;
         if ((master && !aligned(t.aux, 4)) || (kahan && !aligned(t.aux, 2))) return SR_ERR_ALIGN;
         if (range_wraps(t.elem_offset, t.numel)) return SR_ERR_ARG;
+        // an 8-bit parameter draws a 32-bit word per element: its stream counts blocks of four
+        // elements, whose index must leave the counter's three stream bits free
+        if (fp8p && t.elem_offset + t.numel > (1ull << 63)) return SR_ERR_ARG;
     }
 
     AdamwBatch batch;
@@ -582,7 +590,7 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
     };
     const uint32_t mg = max_grid(kThreads);
     const uint64_t per_chunk = fp32m ? kBlocksPerChunkFp32 : kBlocksPerChunkBf16;
-    const uint64_t moment_size = fp32m ? 4 : fp8m ? 1 : 2, aux_size = master ? 4 : 2;
+    const uint64_t moment_size = fp32m ? 4 : fp8m ? 1 : 2, aux_size = master ? 4 : 2, param_size = fp8p ? 1 : 2;
     for (uint32_t i = 0; i < n_tensors; ++i) {
         const sr_tensor_t& t = tensors[i];
         if (t.numel == 0) continue;
@@ -595,7 +603,7 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
                 if (e != hipSuccess) return e;
             }
             TensorDesc& d = batch.t[nb];
-            d.p = static_cast<uint16_t*>(t.p) + local;
+            d.p = reinterpret_cast<uint16_t*>(static_cast<char*>(t.p) + local * param_size);
             d.g = static_cast<const uint16_t*>(t.g) + local;
             d.m = static_cast<char*>(t.m) + local * moment_size;
             d.v = static_cast<char*>(t.v) + local * moment_size;
@@ -604,7 +612,8 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
             d.elem_offset = goff;
             d.tensor_id = t.tensor_id;
             d.flags = ((goff & 7u) == 0 ? DESC_VEC : 0u) |
-                      (fp8m ? ((uint32_t)(uint8_t)t.m_exp << DESC_MEXP_SHIFT) | ((uint32_t)(uint8_t)t.v_exp << DESC_VEXP_SHIFT) : 0u);
+                      (fp8m ? ((uint32_t)(uint8_t)t.m_exp << DESC_MEXP_SHIFT) | ((uint32_t)(uint8_t)t.v_exp << DESC_VEXP_SHIFT) : 0u) |
+                      (fp8p ? (uint32_t)(uint8_t)t.p_exp << DESC_PEXP_SHIFT : 0u);
             batch.chunk_start[nb] = chunks_in_batch;
             chunks_in_batch += nch;
             ++nb;

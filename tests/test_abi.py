@@ -29,7 +29,7 @@ def tensor(numel=64, **kw):
     t = B.SrTensor()
     t.p, t.g, t.m, t.v = buf(2 * numel), buf(2 * numel), buf(4 * numel), buf(4 * numel)
     t.aux = None
-    t.numel, t.elem_offset, t.tensor_id, t.m_exp, t.v_exp, t.reserved = numel, 0, 0, 0, 0, 0
+    t.numel, t.elem_offset, t.tensor_id, t.m_exp, t.v_exp, t.p_exp, t.reserved = numel, 0, 0, 0, 0, 0, 0
     for k, v in kw.items():
         setattr(t, k, v)
     return t
@@ -61,7 +61,7 @@ def test_header_is_plain_c_and_struct_layouts_match_the_binding(tmp_path):
     gcc = shutil.which("gcc")
     if gcc is None:
         pytest.skip("no host C compiler")
-    fields = {"sr_tensor_t": ["p", "g", "m", "v", "aux", "numel", "elem_offset", "tensor_id", "m_exp", "v_exp", "reserved"],
+    fields = {"sr_tensor_t": ["p", "g", "m", "v", "aux", "numel", "elem_offset", "tensor_id", "m_exp", "v_exp", "p_exp", "reserved"],
               "sr_accum_t": ["acc", "grad", "numel", "elem_offset", "tensor_id", "reserved"],
               "sr_hyper_t": ["lr", "beta1", "beta2", "eps", "weight_decay"]}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "sradamw.h"', 'int main(void) {']
@@ -107,7 +107,14 @@ def test_adamw_argument_errors():
     assert step([t], hyper=(float("nan"), 0.9, 0.95, 1e-8, 0.1)) == B.SR_ERR_ARG
     assert step([t], hyper=(1e-3, 0.9, 0.95, float("inf"), 0.1)) == B.SR_ERR_ARG
     assert step([t], hyper=(1e-3, 0.9, 0.95, 1e-8, float("nan"))) == B.SR_ERR_ARG
-    assert step([t], flags=512) == B.SR_ERR_ARG
+    assert step([t], flags=1024) == B.SR_ERR_ARG
+    # the 8-bit parameter combines with 8-bit moments and the arithmetic variants only
+    for bad in (512 | 1, 512 | 2, 512 | 4, 512 | 16, 512 | 8 | 1):
+        assert step([t], flags=bad) == B.SR_ERR_ARG
+    assert step([tensor(p_exp=101)], flags=512) == B.SR_ERR_ARG
+    assert step([tensor(p_exp=-101)], flags=512 | 128) == B.SR_ERR_ARG
+    assert step([tensor(p_exp=3)]) == B.SR_ERR_ARG                           # zero without the flag
+    assert step([tensor(elem_offset=2 ** 63)], flags=512) == B.SR_ERR_ARG    # the 32-bit-word stream's index range
     for bad in (128 | 1, 128 | 2, 128 | 8 | 1, 128 | 16):        # 8-bit moments combine with few flags
         assert step([t], flags=bad) == B.SR_ERR_ARG
     assert step([tensor(reserved=1)], flags=128) == B.SR_ERR_ARG

@@ -1,0 +1,189 @@
+"""GPU parity of the update with the parameter held in 8 bits (SR_FLAG_FP8_PARAMS: E4M3 codes with a
+power-of-two scale per tensor; moments BF16, or 8-bit with SR_FLAG_FP8_MOMENTS) against the CPU
+oracle, through the C ABI: parameter codes and moments bit for bit.  NaN codes are compared as NaN
+codes (sign and payload of a NaN that arithmetic produced are open)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2502_20566_amd import binding as B
+from paper_2502_20566_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+HYP = dict(lr=3e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+FP8P, FP8M = B.SR_FLAG_FP8_PARAMS, B.SR_FLAG_FP8_MOMENTS
+
+
+def bf16_bits(x):
+    return (np.asarray(x, np.float32).view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+def is_nan16(a):
+    return ((a & 0x7F80) == 0x7F80) & ((a & 0x007F) != 0)
+
+
+class State:
+    """A list of tensors on the device (views at odd byte offsets when views > 0) and on the host."""
+
+    def __init__(self, sizes, p_exps, seed, fp8m=None, offsets=None, ids=None, codes="any", views=0):
+        rng = np.random.default_rng(seed)
+        n_t = len(sizes)
+        self.fp8m = fp8m                                   # None, or per-tensor (m_exp, v_exp)
+        self.ids = ids or list(range(n_t))
+        self.offs = offsets or [0] * n_t
+        self.p_exps = p_exps
+        self.host, self.dev = [], []
+        for k, n in enumerate(sizes):
+            if codes == "any":                              # every code, the NaN codes included
+                p8 = rng.integers(0, 256, n).astype(np.uint8)
+            else:                                           # weights ~ N(0, 0.02) on the grid (truncated)
+                w = np.clip(rng.standard_normal(n) * 0.02 * 2.0 ** p_exps[k], -440.0, 440.0)
+                p8 = torch.from_numpy(w.astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy().copy()
+            h = dict(p=p8, p_exp=p_exps[k])
+            if fp8m is None:
+                h["m"] = bf16_bits(rng.standard_normal(n) * 1e-3) if codes == "any" else np.zeros(n, np.uint16)
+                h["v"] = bf16_bits(rng.random(n) * 1e-6) if codes == "any" else np.zeros(n, np.uint16)
+            else:
+                h["m"] = rng.integers(0, 256, n).astype(np.uint8) if codes == "any" else np.zeros(n, np.uint8)
+                h["v"] = rng.integers(0, 128, n).astype(np.uint8) if codes == "any" else np.zeros(n, np.uint8)
+                h["m_exp"], h["v_exp"] = fp8m[k]
+            self.host.append(h)
+            pad = views
+
+            def put(a):
+                whole = torch.from_numpy(np.concatenate([np.zeros(pad, a.dtype), a, np.zeros(8, a.dtype)]))
+                if a.dtype == np.uint16:
+                    whole = whole.view(torch.int16).view(torch.bfloat16)
+                whole = whole.to(DEV)
+                return whole[pad:pad + n]
+            self.dev.append(dict(p=put(h["p"]), m=put(h["m"]), v=put(h["v"]),
+                                 g=torch.empty(n + pad + 8, dtype=torch.bfloat16, device=DEV)[pad:pad + n]))
+        self.tl = B.TensorList([d["p"] for d in self.dev], [d["g"] for d in self.dev], [d["m"] for d in self.dev],
+                               [d["v"] for d in self.dev], False, self.ids, self.offs,
+                               fp8_exponents=fp8m, fp8_param_exponents=p_exps)
+        self.flags = FP8P | (FP8M if fp8m is not None else 0)
+
+    def step(self, t, seed, g_std, flags=0, norm=None, max_norm=0.0, rng=None, hyper=HYP, special=None):
+        rng = rng or np.random.default_rng(1000 + t)
+        for h, d in zip(self.host, self.dev):
+            g = bf16_bits(rng.standard_normal(h["p"].size) * g_std)
+            if special is not None:
+                special(g)
+            h["g"] = g
+            d["g"].copy_(W.u16_numpy_to_bf16(g, DEV))
+        if norm is None:
+            B.sr_adamw_step(self.tl, hyper, t, seed, flags | self.flags)
+        else:
+            nt = torch.tensor([norm], dtype=torch.float32, device=DEV)
+            B.sr_adamw_step(self.tl, hyper, t, seed, flags | self.flags, nt, max_norm)
+        torch.cuda.synchronize()
+        hs = [dict(h, tensor_id=i, elem_offset=o) for h, i, o in zip(self.host, self.ids, self.offs)]
+        oflags = flags | ref.FLAG_FP8_PARAMS | (ref.FLAG_FP8_MOMENTS if self.fp8m is not None else 0)
+        ref.sr_adamw_step(hs, hyper, t, seed, oflags, norm, max_norm)
+
+    def check(self, what):
+        for k, (h, d) in enumerate(zip(self.host, self.dev)):
+            got = d["p"].cpu().numpy()
+            gn, wn = (got & 0x7F) == 0x7F, (h["p"] & 0x7F) == 0x7F
+            assert np.array_equal(gn, wn), f"{what}: tensor {k}: parameter NaN codes differ"
+            bad = np.flatnonzero((got != h["p"]) & ~gn)
+            assert bad.size == 0, f"{what}: tensor {k}: {bad.size} parameter codes differ, first {bad[:4]} got {got[bad[:4]]} want {h['p'][bad[:4]]}"
+            for name, fmt in (("m", 0), ("v", 1)):
+                if self.fp8m is None:
+                    g16, w16 = W.bf16_to_u16_numpy(d[name]), h[name]
+                    gnn, wnn = is_nan16(g16), is_nan16(w16)
+                    assert np.array_equal(gnn, wnn), f"{what}: tensor {k}: {name} NaN positions differ"
+                    assert np.array_equal(np.where(gnn, 0, g16), np.where(wnn, 0, w16)), f"{what}: tensor {k}: {name} differs"
+                else:
+                    g8, w8 = d[name].cpu().numpy(), h[name]
+                    nan = lambda c: (c & 0x7F) == 0x7F if fmt == 0 else (c & 0x7F) > 0x7C
+                    assert np.array_equal(nan(g8), nan(w8)), f"{what}: tensor {k}: {name} NaN codes differ"
+                    assert np.array_equal(np.where(nan(g8), 0, g8), np.where(nan(w8), 0, w8)), f"{what}: tensor {k}: {name} codes differ"
+
+
+@pytest.mark.parametrize("fp8m", [None, [(12, 30), (-2, 9)]])
+@pytest.mark.parametrize("flags", [0, B.SR_FLAG_EPS_IN_ROOT, B.SR_FLAG_DIV_BIAS])
+def test_fp8_params_every_code_as_input(fp8m, flags):
+    """Random codes as the incoming parameters (all 256, NaN codes included), several chunks and
+    ragged tails, two tensors with different scales."""
+    st = State([512 * 5 + 3, 1021], [13, -1], seed=3 + flags, fp8m=fp8m)
+    st.step(2, 0xC0FFEE, g_std=1e-3, flags=flags)
+    st.check(f"flags {flags}")
+
+
+@pytest.mark.parametrize("fp8m", [None, [(14, 33), (10, 26), (0, 0), (14, 33)]])
+def test_fp8_params_running_optimizer_with_clip_offsets_and_views(fp8m):
+    """Ten steps from quantized N(0, 0.02) weights and zero moments, clipping on, element offsets
+    that are not multiples of 8 (edge blocks at both ends), byte-misaligned views, tensor ids out of
+    order; then the same through the integer path only (the test switch)."""
+    for integer_path in (0, 1):
+        B.lib().sr_debug_set(B.SR_DEBUG_FP8_INTEGER, integer_path)
+        try:
+            st = State([4096 + 5, 77, 8, 1], [11, 11, 9, 12], seed=5, fp8m=fp8m, offsets=[3, 8, 16, 7],
+                       ids=[7, 2, 9, 4], codes="weights", views=3)
+            for t in range(1, 11):
+                st.step(t, 17, g_std=1e-3, norm=2.5, max_norm=1.0)
+                st.check(f"integer path {integer_path}, step {t}")
+            assert np.unique(st.host[0]["p"]).size > 60            # the weights live on the 8-bit grid
+        finally:
+            B.lib().sr_debug_set(B.SR_DEBUG_FP8_INTEGER, 0)
+
+
+def test_fp8_params_gpt_shaped_list_and_flat_buffer():
+    """The shapes of the list configurations (scaled down: 52 tensors) and one flat tensor of
+    2^22 + 5 elements, ten and four steps."""
+    shapes = W.gpt_shapes(48, 4, 192, 1001, 32)
+    sizes = [W.numel_of(s) for _, s, _ in shapes]
+    st = State(sizes, [11] * len(sizes), seed=6, codes="weights")
+    for t in range(1, 11):
+        st.step(t, 0, g_std=1e-4, hyper=dict(HYP, lr=6e-4))
+        st.check(f"list step {t}")
+    st = State([(1 << 22) + 5], [11], seed=7, fp8m=[(13, 36)], codes="weights")
+    for t in range(1, 5):
+        st.step(t, 3, g_std=1e-4, hyper=dict(HYP, lr=1.2e-4))
+        st.check(f"flat step {t}")
+
+
+def test_fp8_params_saturation_and_special_gradients():
+    """A learning rate that throws parameters past the top of the format (stored as +-448), NaN
+    and infinite gradients (NaN codes), every wave holding some of each so that the integer path
+    and the conversion instruction both run (the second tensor's waves hold nothing large)."""
+    st = State([512 * 3, 512 * 2], [13, 11], seed=8, codes="weights")
+
+    def spikes(g):
+        if g.size == 512 * 3:
+            g[5], g[700], g[1300] = 0x7FC0, 0x7F80, 0xFF80
+    rng = np.random.default_rng(4)
+    st.step(1, 5, g_std=1e-3, rng=rng, hyper=dict(HYP, lr=0.5))
+    st.check("large step")
+    assert ((st.host[0]["p"] & 0x7F) == 0x7E).sum() > 100
+    st.step(2, 5, g_std=1e-3, rng=rng, special=spikes)
+    st.check("special gradients")
+    assert st.host[0]["p"][5] & 0x7F == 0x7F
+
+
+def test_fp8_params_cut_into_many_launches():
+    B.lib().sr_debug_set(B.SR_DEBUG_LAUNCH_LIMIT, 3)
+    try:
+        st = State([4096 + 5, 77, 1030], [11, 11, 9], seed=9, offsets=[3, 8, 5], codes="weights", views=1)
+        for t in (1, 2):
+            st.step(t, 1, g_std=1e-3)
+            st.check(f"three workgroups per launch, step {t}")
+    finally:
+        B.lib().sr_debug_set(B.SR_DEBUG_LAUNCH_LIMIT, 0)
+
+
+def test_fp8_params_arguments():
+    st = State([64], [11], seed=1)
+    for bad in (FP8P | B.SR_FLAG_RNE_PARAMS, FP8P | B.SR_FLAG_RNE_MOMENTS, FP8P | B.SR_FLAG_KAHAN):
+        with pytest.raises((B.SrError, ValueError)):
+            B.sr_adamw_step(st.tl, HYP, 1, 0, bad)
+    with pytest.raises(ValueError):                              # the binding checks the list against the flag
+        B.sr_adamw_step(st.tl, HYP, 1, 0, 0)
+    with pytest.raises(ValueError):
+        B.TensorList([st.dev[0]["p"]], [st.dev[0]["g"]], [st.dev[0]["m"]], [st.dev[0]["v"]], fp8_param_exponents=[101])
+    st.tl.array[0].reserved = 1
+    with pytest.raises(B.SrError):
+        B.sr_adamw_step(st.tl, HYP, 1, 0, FP8P)

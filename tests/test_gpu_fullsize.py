@@ -235,6 +235,83 @@ def test_config5_full_size_windows_8_bit_moments():
     assert float((v_end > 0).mean()) > 0.99
 
 
+def _quantize_params(params, p_exp, seed):
+    """The BF16 weights onto the E4M3 grid of scale 2^p_exp with the library's stochastic cast."""
+    out = []
+    for i, p in enumerate(params):
+        q = torch.empty(p.numel(), dtype=torch.uint8, device=DEV)
+        for at in range(0, p.numel(), 1 << 28):
+            B.sr_cast_f32_fp8(p[at:at + (1 << 28)].float() * float(2.0 ** p_exp), q[at:at + (1 << 28)], B.SR_FP8_E4M3, seed, 0, i)
+        out.append(q)
+    torch.cuda.synchronize()
+    return out
+
+
+def _same_codes(got, want, nan):
+    return int(((got != want) & ~(nan(got) & nan(want))).sum())
+
+
+def test_config2_list_with_8_bit_parameters():
+    """The 148-tensor list at full size with the parameters held as E4M3 codes (extension) and BF16
+    moments: every element of every tensor against the oracle for three steps."""
+    cfg = W.config(2)
+    p_exp = 8
+    params = _quantize_params(W.make_params(cfg.shapes, DEV, W.data_seed(2, 0), cfg.param_std), p_exp, 3)
+    ms, vs = W.make_moments(cfg.shapes, DEV, False)
+    grads = [torch.empty(p.numel(), dtype=torch.bfloat16, device=DEV) for p in params]
+    tl = B.TensorList(params, grads, ms, vs, fp8_param_exponents=[p_exp] * len(params))
+    host = [dict(p=p.cpu().numpy(), m=to_np(m), v=to_np(v), p_exp=p_exp) for p, m, v in zip(params, ms, vs)]
+    nan4 = lambda c: (c & 0x7F) == 0x7F
+    for t in range(1, 4):
+        W.fill_grads(grads, W.data_seed(2, t), cfg.grad_std)
+        for h, g in zip(host, grads):
+            h["g"] = to_np(g)
+        B.sr_adamw_step(tl, cfg.hyper, t, cfg.seed, B.SR_FLAG_FP8_PARAMS)
+        torch.cuda.synchronize()
+        ref.sr_adamw_step(host, cfg.hyper, t, cfg.seed, ref.FLAG_FP8_PARAMS)
+        bad = 0
+        for i, h in enumerate(host):
+            bad += _same_codes(params[i].cpu().numpy(), h["p"], nan4) + same_bf16(to_np(ms[i]), h["m"]) + same_bf16(to_np(vs[i]), h["v"])
+        assert bad == 0, f"config 2, 8-bit parameters, step {t}: {bad} mismatches"
+    # under SR the codes keep moving although every update is well below one E4M3 spacing
+    start = _quantize_params(W.make_params(cfg.shapes[:1], DEV, W.data_seed(2, 0), cfg.param_std), p_exp, 3)[0]
+    assert 1e-4 < float((params[0] != start).float().mean()) < 0.9
+
+
+def test_config5_flat_buffer_all_state_in_8_bits():
+    """The 6.7B flat buffer with parameters and both moments in 8 bits (extension), six steps from
+    zero moments: the oracle follows the first and last 2^18 elements, a window across element
+    index 2^32 and 16 random windows, codes bit for bit (NaN codes as NaN codes)."""
+    import bench
+    cfg = W.config(5)
+    exps = bench.fp8_scale_exponents(cfg)
+    p_exp = 8
+    params = _quantize_params(W.make_params(cfg.shapes, DEV, W.data_seed(5, 0), cfg.param_std), p_exp, 5)
+    n = params[0].numel()
+    ms = [torch.zeros(n, dtype=torch.uint8, device=DEV)]
+    vs = [torch.zeros(n, dtype=torch.uint8, device=DEV)]
+    grads = [torch.empty(n, dtype=torch.bfloat16, device=DEV)]
+    tl = B.TensorList(params, grads, ms, vs, fp8_exponents=[exps], fp8_param_exponents=[p_exp])
+    w = 1 << 18
+    picks = [(lo, k) for _, lo, k in window_picks([n], np.random.default_rng(59), w, 16)]
+    picks += [((1 << 32) - w // 2, w), ((1 << 32) + 3, w - 5), (n - 7, 7)]
+    host = [dict(p=params[0][lo:lo + k].cpu().numpy(), m=to_np(ms[0][lo:lo + k]), v=to_np(vs[0][lo:lo + k]),
+                 p_exp=p_exp, m_exp=exps[0], v_exp=exps[1], tensor_id=0, elem_offset=lo) for lo, k in picks]
+    nan4, nan5 = (lambda c: (c & 0x7F) == 0x7F), (lambda c: (c & 0x7F) > 0x7C)
+    for t in range(1, 7):
+        W.fill_grads(grads, W.data_seed(5, t), cfg.grad_std)
+        B.sr_adamw_step(tl, cfg.hyper, t, cfg.seed, B.SR_FLAG_FP8_PARAMS | B.SR_FLAG_FP8_MOMENTS)
+        torch.cuda.synchronize()
+        for h, (lo, k) in zip(host, picks):
+            h["g"] = to_np(grads[0][lo:lo + k])
+        ref.sr_adamw_step(host, cfg.hyper, t, cfg.seed, ref.FLAG_FP8_PARAMS | ref.FLAG_FP8_MOMENTS)
+        bad = 0
+        for h, (lo, k) in zip(host, picks):
+            bad += _same_codes(params[0][lo:lo + k].cpu().numpy(), h["p"], nan4)
+            bad += _same_codes(to_np(ms[0][lo:lo + k]), h["m"], nan4) + _same_codes(to_np(vs[0][lo:lo + k]), h["v"], nan5)
+        assert bad == 0, f"config 5, all state in 8 bits, step {t}: {bad} mismatches"
+
+
 def test_cast_every_binary32_encoding():
     """All 2^32 binary32 encodings (every exponent, subnormal, infinity and NaN payload), each with
     the draw its index gets: the GPU cast equals the by-value oracle bit for bit."""
