@@ -307,8 +307,10 @@ def run_aux_op(args, torch, np, B, W, cfg):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default 20; 200 for configurations whose step moves under 10 GB, where "
+                         "the first steps after the synchronisation run below full clocks and would dominate)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default 3; 20 for those)")
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--mode", choices=sorted(MODES), default=None,
                     help="step variant (default: the config's own: sr, or fp32_moments for config 4)")
@@ -353,6 +355,11 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     cfg = W.config(args.config)
+    short_steps = args.op == "step" and 22 * cfg.numel < 1e10
+    if args.steps is None:
+        args.steps = 200 if short_steps else 20
+    if args.warmup is None:
+        args.warmup = 20 if short_steps else 3
     if args.op != "step":
         run_aux_op(args, torch, np, B, W, cfg)
         return
