@@ -55,7 +55,8 @@ extern "C" {
                                   range overflow                                          */
 #define SR_ERR_WORKSPACE (-3)  /* workspace NULL, misaligned (8 bytes) or too small       */
 #define SR_ERR_ALIGN     (-4)  /* a BF16 pointer not 2-byte / an FP32 pointer not 4-byte
-                                  aligned.  Nothing more is required: tensors may be views
+                                  aligned (arrays of 8-bit codes may start at any byte).
+                                  Nothing more is required: tensors may be views
                                   starting at any element of a larger buffer and keep the
                                   vector path                                             */
 #define SR_ERR_HIP       (-5)  /* a launch failed; see sr_last_hip_error()                */
@@ -120,8 +121,9 @@ extern "C" {
                                    sr_cast_f32_fp8's rule (the fraction is cut to 16
                                    bits).  10 bytes moved per element instead of 14.
                                    Combines with SR_FLAG_RNE_PARAMS, SR_FLAG_FP8_PARAMS,
-                                   SR_FLAG_EPS_IN_ROOT and SR_FLAG_DIV_BIAS only.  Both write-backs saturate:
-                                   a scaled m' beyond 448 is stored as 448, a scaled v'
+                                   SR_FLAG_EPS_IN_ROOT, SR_FLAG_DIV_BIAS and
+                                   SR_FLAG_SKIP_NONFINITE_NORM only.  Both write-backs
+                                   saturate: a scaled m' beyond 448 is stored as 448, a scaled v'
                                    beyond 57344 (or one that Q_SR would round to E5M2's
                                    infinity) as 57344, so the state never holds an
                                    infinity.  NaN codes stay NaN codes; NaN signs and
