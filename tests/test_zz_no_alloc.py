@@ -53,3 +53,48 @@ def test_static_scratch_empty_list_and_limit():
     torch.cuda.synchronize()
     assert rc == B.SR_ERR_SIZE and out.item() == 7.0
     assert b"static scratch" in B.lib().sr_strerror(rc)
+
+
+def test_static_scratch_norm_under_graph_capture():
+    """What the entry point is for: after one call outside a capture (which looks the scratch
+    address up), norm + clipped step are captured with no workspace in sight and replayed three
+    times, with eager work and synchronisations between the replays; the result equals three eager
+    calls through the workspace entry point."""
+    from oracle import ref  # noqa: F401  (same import order as the other GPU tests)
+    import numpy as np
+    cfg = W.config(3)
+    shapes = W.gpt_shapes(48, 2, 192, 1001, 32)
+
+    def fresh():
+        p = W.make_params(shapes, DEV, 61, cfg.param_std)
+        m, v = W.make_moments(shapes, DEV, False)
+        g = W.make_grads(shapes, DEV, 62, cfg.grad_std, cfg.outlier_frac, cfg.outlier_std)
+        return p, m, v, B.TensorList(p, g, m, v), torch.zeros(1, dtype=torch.float32, device=DEV)
+
+    p, m, v, tl, norm = fresh()
+    ws = torch.empty(max(tl.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
+    for _ in range(3):
+        B.grad_global_norm(tl, norm, ws)
+        B.sr_adamw_step(tl, cfg.hyper, 5, 8, 0, norm, cfg.clip)
+    torch.cuda.synchronize()
+    eager = [W.bf16_to_u16_numpy(x) for x in p + m + v]
+
+    p2, m2, v2, tl2, norm2 = fresh()
+    B.grad_global_norm_static(tl2, norm2)                    # first call on the device: outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.grad_global_norm_static(tl2, norm2)
+            B.sr_adamw_step(tl2, cfg.hyper, 5, 8, 0, norm2, cfg.clip)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    other = torch.zeros(1024, device=DEV)
+    for _ in range(3):
+        graph.replay()
+        other += 1.0
+        torch.cuda.synchronize()
+    for a, b in zip(eager, [W.bf16_to_u16_numpy(x) for x in p2 + m2 + v2]):
+        assert bool(np.all(a == b))
