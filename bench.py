@@ -56,7 +56,7 @@ def fp8_scale_exponents(cfg):
     return int(math.floor(math.log2(448.0 / g))), int(math.floor(math.log2(57344.0 / (g * g))))
 
 
-def place_flat_buffers(torch, np, B, n, dev, n_candidates, n_layouts):
+def place_flat_buffers(torch, np, B, n, dev, n_candidates, n_layouts, slowest=False):
     """Where p, g, m, v lie in physical memory moves the 4-read/3-write stream by several percent on
     MI355X (14.1 to 15.4 ms for the same kernel on the 6.7B buffers; the ranking of layouts is stable
     within a process and follows no rule in the virtual addresses).  So the four flat arrays are
@@ -89,11 +89,12 @@ def place_flat_buffers(torch, np, B, n, dev, n_candidates, n_layouts):
     layouts += rng.sample(every, min(n_layouts - 1, len(every)))
     times = [probe_ms(l) for l in layouts]
     # the best few once more, with more repetitions, so that one lucky timing does not decide
-    order = sorted(range(len(layouts)), key=lambda i: times[i])
+    order = sorted(range(len(layouts)), key=lambda i: times[i], reverse=slowest)
     finals = {i: probe_ms(layouts[i], 4) for i in order[:4]}
-    best = min(finals, key=finals.get)
+    best = (max if slowest else min)(finals, key=finals.get)
     chosen = tuple(bufs[i] for i in layouts[best])
-    report = {"policy": "fastest of the probed layouts (sr_stream_probe on spare allocations of the same size)",
+    report = {"policy": ("SLOWEST (a measurement of what placement costs)" if slowest else "fastest") +
+                        " of the probed layouts (sr_stream_probe on spare allocations of the same size)",
               "candidates": n_candidates, "layouts_tried": len(layouts),
               "probe_ms": {"chosen": finals[best], "as_allocated": times[0], "median": float(np.median(times)),
                            "worst": max(times), "best_first_pass": min(times)}}
@@ -325,10 +326,11 @@ def main():
     ap.add_argument("--resident-waves", type=int, default=0,
                     help="measurement only: override the number of waves the library lets reside per "
                          "compute unit in its streaming kernels (0 = the library's own setting, 32 = no cap)")
-    ap.add_argument("--placement", choices=("probe", "plain"), default="probe",
+    ap.add_argument("--placement", choices=("probe", "plain", "slowest"), default="probe",
                     help="flat BF16 configurations: choose the four arrays among spare allocations by "
                          "timing the no-arithmetic probe on a sample of layouts (probe), or take them as "
-                         "the allocator returns them (plain)")
+                         "the allocator returns them (plain); slowest keeps the worst probed layout, to "
+                         "measure what placement costs")
     ap.add_argument("--placement-candidates", type=int, default=8)
     ap.add_argument("--placement-layouts", type=int, default=40)
     ap.add_argument("--warm-steps", type=int, default=None, help="seeded steps that warm the moments")
@@ -373,9 +375,9 @@ def main():
     placement = {"policy": "as the allocator returns them"}
     fp8_exps = None
     placed = None
-    if args.placement == "probe" and len(cfg.shapes) == 1 and MODES[mode][3] == 14 and cfg.numel >= (1 << 28):
+    if args.placement in ("probe", "slowest") and len(cfg.shapes) == 1 and MODES[mode][3] == 14 and cfg.numel >= (1 << 28):
         placed, placement = place_flat_buffers(torch, np, B, cfg.numel, dev, args.placement_candidates,
-                                               args.placement_layouts)
+                                               args.placement_layouts, slowest=args.placement == "slowest")
     if placed is not None:
         p_, g_, m_, v_ = placed
         tmp = W.make_params(cfg.shapes, dev, W.data_seed(cfg.index, 0), cfg.param_std)
