@@ -347,10 +347,13 @@ int sr_last_hip_error(void);
 int sr_version(void);
 
 /* ======================================================================
- * NOT PART OF THE PRODUCT API.  What follows serves measurement and tests
- * only: two traffic probes that bench.py times beside the update, and one
- * hook through which the tests reach code paths that otherwise need huge
- * inputs or rare values.  A deployment can strip them.
+ * NOT PART OF THE METHOD.  What follows serves measurement and tests: two
+ * traffic probes -- bench.py times them beside the update, and a caller can
+ * time them on candidate buffers to choose where its arrays lie (on MI355X
+ * the placement of p, g, m, v in physical memory moves the step by several
+ * percent) -- and one hook through which the tests reach code paths that
+ * otherwise need huge inputs or rare values.  Nothing in the update path
+ * depends on them.
  * ====================================================================== */
 
 /*
