@@ -103,6 +103,11 @@ class SRAdamW(torch.optim.Optimizer):
                 need = max(everything.workspace_bytes(), 256)
                 if self._ws is None or self._ws.numel() < need:
                     self._ws = torch.empty(need, dtype=torch.uint8, device=self.norm.device)
+            # the lists hold the gradients' addresses, not the tensors: a gradient buffer that the
+            # framework frees after the step (zero_grad(set_to_none=True)) must not be kept alive here
+            for tl in per_group + ([everything] if everything is not None else []):
+                tl.keep = (tl.keep[0], None, tl.keep[2] if tl is not everything else None,
+                           tl.keep[3] if tl is not everything else None, tl.keep[4])
             self._lists = (per_group, everything)
             self._grad_ptrs = ptrs
         return self._lists
