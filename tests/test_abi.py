@@ -263,3 +263,14 @@ def test_accumulate_workspace_bound_covers_ragged_tensors_at_odd_offsets():
     assert L.sr_grad_accumulate(arr, n, 1.0, 1, 0, 0, out, ws, need, None) == B.SR_OK
     torch.cuda.synchronize()
     assert L.sr_grad_accumulate(arr, n, 1.0, 1, 0, 0, out, ws, 8 * chunks - 8, None) == B.SR_ERR_WORKSPACE
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No CPU fallback anywhere: when the built library is not there, the binding raises and says
+    how to build it; nothing else is tried."""
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libsradamw.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.lib()
+    src = open(os.path.join(ROOT, "paper_2502_20566_amd", "binding.py")).read()
+    assert "oracle" not in src                              # the product path never reaches for the checker
