@@ -326,51 +326,89 @@ def main():
         flags |= getattr(B, name)
 
     placement = {"policy": "as the allocator returns them"}
-    fp8_exps = None
+    import math
+    fp8m, fp8p = mode in ("fp8_moments", "fp8_all"), mode in ("fp8_params", "fp8_all")
+    fp8_exps = fp8_scale_exponents(cfg) if fp8m else None
+    # the weights go onto the E4M3 grid with the library's own stochastic cast: eight standard
+    # deviations (gains of 1 included) map to the top of the format
+    p_exp = int(math.floor(math.log2(448.0 / max(8.0 * cfg.param_std, 1.0)))) if fp8p else None
+
+    def quantise(src, dst, tensor_id):
+        for at in range(0, src.numel(), 1 << 28):
+            piece = src[at:at + (1 << 28)].float() * float(2.0 ** p_exp)
+            B.sr_cast_f32_fp8(piece, dst[at:at + (1 << 28)], B.SR_FP8_E4M3, cfg.seed, 0, tensor_id)
+        torch.cuda.synchronize()
+
+    def tensor_list(a):
+        return B.TensorList([a["p"]], [a["g"]], [a["m"]], [a["v"]], fp32_moments,
+                            aux=[a["aux"]] if "aux" in a else None,
+                            fp8_exponents=None if fp8_exps is None else [fp8_exps],
+                            fp8_param_exponents=None if p_exp is None else [p_exp])
+
     placed = None
-    if args.placement in ("probe", "slowest") and len(cfg.shapes) == 1 and MODES[mode][3] == 14 and cfg.numel >= (1 << 28):
-        from paper_2502_20566_amd.placement import place_flat_buffers
-        placed, placement = place_flat_buffers(cfg.numel, dev, args.placement_candidates, args.placement_layouts,
-                                               slowest=args.placement == "slowest")
+    if args.placement in ("probe", "slowest") and len(cfg.shapes) == 1 and cfg.numel >= (1 << 28):
+        from paper_2502_20566_amd import placement as P
+        slowest = args.placement == "slowest"
+        if MODES[mode][3] == 14:
+            four, placement = P.place_flat_buffers(cfg.numel, dev, args.placement_candidates, args.placement_layouts, slowest=slowest)
+            placed = None if four is None else dict(zip("pgmv", four))
+        else:
+            # arrays of several sizes: the step itself, on zero-filled candidates, is the probe
+            moment = torch.float32 if fp32_moments else torch.uint8 if fp8m else torch.bfloat16
+            roles = {"p": (torch.uint8 if fp8p else torch.bfloat16, cfg.numel), "g": (torch.bfloat16, cfg.numel),
+                     "m": (moment, cfg.numel), "v": (moment, cfg.numel)}
+            if aux_kind is not None:
+                roles["aux"] = (torch.float32 if aux_kind == "f32" else torch.bfloat16, cfg.numel)
+
+            def time_layout(a, reps=2):
+                tl_ = tensor_list(a)
+                B.sr_adamw_step(tl_, cfg.hyper, 1, cfg.seed, flags)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    B.sr_adamw_step(tl_, cfg.hyper, 1, cfg.seed, flags)
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / reps
+
+            placed, placement = P.place_state_buffers(roles, dev, time_layout, n_layouts=min(args.placement_layouts, 24), slowest=slowest)
     if placed is not None:
-        p_, g_, m_, v_ = placed
-        tmp = W.make_params(cfg.shapes, dev, W.data_seed(cfg.index, 0), cfg.param_std)
-        p_.copy_(tmp[0])
+        tmp = W.make_params(cfg.shapes, dev, W.data_seed(cfg.index, 0), cfg.param_std)[0]
+        if fp8p:
+            quantise(tmp, placed["p"], 0)
+        else:
+            placed["p"].copy_(tmp)
+        if aux_kind == "f32":
+            placed["aux"].copy_(tmp)                      # binary32 master parameters
+        elif aux_kind == "bf16":
+            placed["aux"].zero_()                         # Kahan compensation starts at zero
         del tmp
         torch.cuda.empty_cache()
-        m_.zero_()
-        v_.zero_()
-        params, grads, ms, vs = [p_], [g_], [m_], [v_]
+        placed["m"].zero_()
+        placed["v"].zero_()
+        params, grads, ms, vs = [placed["p"]], [placed["g"]], [placed["m"]], [placed["v"]]
+        aux = [placed["aux"]] if "aux" in placed else None
     else:
         params = W.make_params(cfg.shapes, dev, W.data_seed(cfg.index, 0), cfg.param_std)
         ms, vs = W.make_moments(cfg.shapes, dev, fp32_moments)
-        if mode in ("fp8_moments", "fp8_all"):
-            fp8_exps = fp8_scale_exponents(cfg)
+        if fp8m:
             ms = [torch.zeros(m.numel(), dtype=torch.uint8, device=dev) for m in ms]
             vs = [torch.zeros(v.numel(), dtype=torch.uint8, device=dev) for v in vs]
         grads = [torch.empty_like(p) for p in params]
-    p_exp = None
-    if mode in ("fp8_params", "fp8_all"):
-        # the weights onto the E4M3 grid with the library's own stochastic cast: eight standard
-        # deviations (gains of 1 included) map to the top of the format
-        import math
-        p_exp = int(math.floor(math.log2(448.0 / max(8.0 * cfg.param_std, 1.0))))
-        p8s = []
-        for i, p_ in enumerate(params):
-            q = torch.empty(p_.numel(), dtype=torch.uint8, device=dev)
-            for at in range(0, p_.numel(), 1 << 28):
-                piece = p_[at:at + (1 << 28)].float() * float(2.0 ** p_exp)
-                B.sr_cast_f32_fp8(piece, q[at:at + (1 << 28)], B.SR_FP8_E4M3, cfg.seed, 0, i)
-            p8s.append(q)
-        torch.cuda.synchronize()
-        params = p8s
-        del p8s
-        torch.cuda.empty_cache()
-    aux = None
-    if aux_kind == "f32":
-        aux = [p.float() for p in params]                 # binary32 master parameters
-    elif aux_kind == "bf16":
-        aux = [torch.zeros_like(p) for p in params]       # Kahan compensation starts at zero
+        aux = None
+        if aux_kind == "f32":
+            aux = [p.float() for p in params]             # binary32 master parameters
+        elif aux_kind == "bf16":
+            aux = [torch.zeros_like(p) for p in params]   # Kahan compensation starts at zero
+        if fp8p:
+            p8s = []
+            for i, p_ in enumerate(params):
+                q = torch.empty(p_.numel(), dtype=torch.uint8, device=dev)
+                quantise(p_, q, i)
+                p8s.append(q)
+            params = p8s
+            del p8s
+            torch.cuda.empty_cache()
     tl = B.TensorList(params, grads, ms, vs, fp32_moments, aux=aux,
                       fp8_exponents=None if fp8_exps is None else [fp8_exps] * len(params),
                       fp8_param_exponents=None if p_exp is None else [p_exp] * len(params))
