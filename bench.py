@@ -186,14 +186,36 @@ def run_aux_op(args, torch, np, B, W, cfg):
     threads = min(ref.max_threads(), os.cpu_count() or 1)
     n_cpu = min(n, 1 << 26) & ~7 or n
     lo = ((n - n_cpu) // 2) & ~7
+    def placed_arrays(roles, run):
+        """The op's arrays chosen among spare allocations (as for the step), or None."""
+        if args.placement == "plain" or n < (1 << 28):
+            return None, {"policy": "as the allocator returns them"}
+        from paper_2502_20566_amd.placement import place_state_buffers
+
+        def time_layout(a, reps=3):
+            run(a)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                run(a)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        return place_state_buffers(roles, dev, time_layout, n_layouts=12, slowest=args.placement == "slowest")
+
     if args.op.startswith("cast"):
-        src = torch.empty(n, dtype=torch.float32, device=dev)
+        out_dtype = torch.bfloat16 if args.op == "cast" else torch.uint8
+        fmt = B.SR_FP8_E5M2 if args.op == "cast_e5m2" else B.SR_FP8_E4M3
+        run = ((lambda a: B.sr_cast_f32_bf16(a["src"], a["dst"], seed, 7, tid)) if args.op == "cast" else
+               (lambda a: B.sr_cast_f32_fp8(a["src"], a["dst"], fmt, seed, 7, tid)))
+        placed, placement = placed_arrays({"src": (torch.float32, n), "dst": (out_dtype, n)}, run)
+        src = placed["src"] if placed else torch.empty(n, dtype=torch.float32, device=dev)
         for k, at in enumerate(range(0, n, 1 << 28)):            # generated in pieces of 2^28 elements
             piece = src[at:at + (1 << 28)]
             piece.copy_(W.make_cast_input(piece.numel(), dev, W.data_seed(cfg.index, 900 + k)))
         host = src[lo:lo + n_cpu].cpu().numpy()
         if args.op == "cast":
-            dst = torch.empty(n, dtype=torch.bfloat16, device=dev)
+            dst = placed["dst"] if placed else torch.empty(n, dtype=torch.bfloat16, device=dev)
             fn = lambda: B.sr_cast_f32_bf16(src, dst, seed, 7, tid)
             bpe, kernel, metric = 6, "cast_kernel", "sr_cast_elements_per_sec"
             wall, dev_ms = time_launches(torch, np, fn, args.warmup, args.steps)
@@ -202,9 +224,8 @@ def run_aux_op(args, torch, np, B, W, cfg):
             dt = time.perf_counter() - t0
             bad = int((W.bf16_to_u16_numpy(dst[lo:lo + n_cpu]) != want).sum())
         else:                                                    # 8-bit formats: 4 B read + 1 B written
-            fmt = B.SR_FP8_E4M3 if args.op == "cast_e4m3" else B.SR_FP8_E5M2
             ofmt = ref.E4M3 if args.op == "cast_e4m3" else ref.E5M2
-            dst = torch.empty(n, dtype=torch.uint8, device=dev)
+            dst = placed["dst"] if placed else torch.empty(n, dtype=torch.uint8, device=dev)
             fn = lambda: B.sr_cast_f32_fp8(src, dst, fmt, seed, 7, tid)
             bpe, kernel, metric = 5, "cast_fp8_kernel", "sr_cast_fp8_elements_per_sec"
             wall, dev_ms = time_launches(torch, np, fn, args.warmup, args.steps)
@@ -216,11 +237,20 @@ def run_aux_op(args, torch, np, B, W, cfg):
             bad = int((dst[lo:lo + n_cpu].cpu().numpy() != want).sum())
     else:
         with_norm = args.op == "accumulate_norm"
-        acc = W.make_grads(flat, dev, W.data_seed(cfg.index, 901), cfg.grad_std)[0]
-        g = W.make_grads(flat, dev, W.data_seed(cfg.index, 902), cfg.grad_std)[0]
-        al = B.AccumList([acc], [g], tensor_ids=[tid])
         norm = torch.zeros(1, dtype=torch.float32, device=dev) if with_norm else None
-        ws = torch.empty(max(al.workspace_bytes(), 256), dtype=torch.uint8, device=dev) if with_norm else None
+        ws = (torch.empty(max(B.lib().sr_accumulate_workspace_bytes(1, n), 256), dtype=torch.uint8, device=dev)
+              if with_norm else None)
+        placed, placement = placed_arrays({"acc": (torch.bfloat16, n), "g": (torch.bfloat16, n)},
+                                          lambda a: B.sr_grad_accumulate(B.AccumList([a["acc"]], [a["g"]], tensor_ids=[tid]),
+                                                                         0.25, 1, seed, 0, norm, ws))
+        if placed:
+            acc, g = placed["acc"], placed["g"]
+            W.fill_grads([acc], W.data_seed(cfg.index, 901), cfg.grad_std)
+            W.fill_grads([g], W.data_seed(cfg.index, 902), cfg.grad_std)
+        else:
+            acc = W.make_grads(flat, dev, W.data_seed(cfg.index, 901), cfg.grad_std)[0]
+            g = W.make_grads(flat, dev, W.data_seed(cfg.index, 902), cfg.grad_std)[0]
+        al = B.AccumList([acc], [g], tensor_ids=[tid])
         k = [0]
 
         def fn():
@@ -247,7 +277,7 @@ def run_aux_op(args, torch, np, B, W, cfg):
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.op} on one flat array of config {cfg.index}'s size", "numel": n,
-                   "bytes_per_element": bpe},
+                   "bytes_per_element": bpe, "placement": placement},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": kernel,
