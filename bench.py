@@ -71,7 +71,7 @@ def kernel_source_sha16() -> str:
     it was measured on."""
     import hashlib
     h = hashlib.sha256()
-    for name in ("sr_device.h", "sr_kernels.h", "sradamw.hip"):
+    for name in ("sr_device.h", "sr_host.h", "sr_kernels.h", "sradamw.hip"):
         h.update(open(os.path.join(ROOT, "paper_2502_20566_amd", "csrc", name), "rb").read())
     return h.hexdigest()[:16]
 

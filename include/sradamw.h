@@ -389,7 +389,9 @@ int sr_stream_probe_fp8m(void* d_p, const void* d_g, void* d_m8, void* d_v8, uin
  *                            test prove it on the same inputs)
  *   SR_DEBUG_RESIDENT_WAVES  value = waves the streaming kernels allow to
  *                            reside per compute unit (0 = the library's own
- *                            setting per kernel, 32 = no cap)
+ *                            setting per kernel, 32 = no cap; the hardware
+ *                            grants LDS in units of 1280 bytes, so only 24,
+ *                            20, 18, 16, 14, 12, 11, 10, 9, 8, ... differ)
  * Unknown keys are ignored.
  */
 #define SR_DEBUG_LAUNCH_LIMIT   0u

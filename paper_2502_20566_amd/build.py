@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsradamw.so")
 SOURCES = [os.path.join(CSRC, "sradamw.hip")]
-HEADERS = [os.path.join(CSRC, "sr_kernels.h"), os.path.join(CSRC, "sr_device.h"),
+HEADERS = [os.path.join(CSRC, "sr_kernels.h"), os.path.join(CSRC, "sr_device.h"), os.path.join(CSRC, "sr_host.h"),
            os.path.join(os.path.dirname(HERE), "include", "sradamw.h")]
 
 HIPCC = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"

@@ -35,19 +35,25 @@ namespace sr {
 #define SR_TUNE_MAXBATCH 320
 #endif
 // Waves allowed to reside per CU, by kernel class (0 = as many as fit, 32): see occupancy_lds in
-// the host code.  Measured on MI355X, 6.66e9 elements, waves per CU 32 / 24 / 20 / 16 / 14 / 12:
-//   BF16 update (SR)   14.69 / 14.19 / 14.05 / 14.03 / 14.24 / 15.21 ms
-//   same, no arithmetic 14.54 / 14.66 / 14.31 / 14.11 / 13.96 / 13.93 ms
-//   Kahan (18 B/el)    19.90 / 19.52 / 18.96 / 18.70 / 18.37 / 18.20 ms
-//   binary32 moments (2.65e9 el) 9.09 / 9.06 / 9.00 / 8.99 / 8.96 / 9.18 ms
-//   8-bit moments      11.33 / 11.92 / 12.27 / 12.56 / 13.02 / 14.16 ms   (arithmetic not hidden: no cap)
-//   BF16 cast           6.16 /  6.93 /  7.40 /  7.90 /  8.89 / 10.53 ms   (half a block per lane: no cap)
-//   8-bit cast          4.94 /  4.90 /   -   /  5.50 /  5.98 /   -    ms   (28 waves: 4.84)
-//   accumulation        6.20 /  6.47 /  6.62 /  6.80 /  7.21 /  8.05 ms   (no cap)
+// the host code; LDS is granted in units of 1280 bytes, so the settings that differ are 32, 24
+// (23-24 measured), 20, 18 (17-18 measured), 16, 14, 12, 11, 10, 9, 8.  Measured on MI355X,
+// 6.66e9 elements, one process, arrays as allocated, waves per CU 32 / 24 / 20 / 18 / 16 / 14 / 12 / 11:
+//   BF16 update (SR)    14.51 / 14.44 / 14.24 / 14.25 / 14.36 / 14.54 / 14.98 / 15.49 ms
+//   same, moments to nearest 14.63 / 14.43 / 14.16 / 14.02 / 14.04 / 14.19 / 14.69 / 15.41 ms
+//   same, no arithmetic 14.64 / 14.70 / 14.54 / 14.22 / 14.08 / 13.98 / 13.89 / 13.92 ms
+//   Kahan (18 B/el)     19.81 / 19.90 / 19.38 / 18.89 / 18.61 / 18.39 / 18.23 / 18.27 ms
+//   master (28 B/el)    28.83 / 28.87 / 28.73 / 28.63 / 28.50 / 28.50 / 28.52 / 28.54 ms
+//   8-bit moments       11.87 / 12.03 / 12.34 / 12.63 / 12.97 / 13.55 / 14.23 / 14.60 ms   (no cap)
+// and in earlier runs: binary32 moments (2.65e9 el) best at 14-16 (9.09 -> 8.96-8.99 ms); the
+// BF16 cast (half a block per lane) and the accumulation lose from any cap (6.16 -> 6.93,
+// 6.20 -> 6.47 ms at 20); the 8-bit cast gains a little at 24 (4.94 -> 4.84 ms).
+// The update's arithmetic keeps the vector ALUs busy for nearly the whole kernel (VALUBusy 90-103%
+// with SR on all three outputs, 86-91% with the moments to nearest, in two runs), so it needs
+// 16-20 waves to overlap with the memory stream, while the bare stream is fastest at 11-12.
 // A read-only stream does not care (7.32 ms for 8, 16 and 32 waves): it is the mix of reads and
 // writes that loses bandwidth when more requests than needed are in flight.
 #ifndef SR_TUNE_WAVES_BF16
-#define SR_TUNE_WAVES_BF16 20
+#define SR_TUNE_WAVES_BF16 18
 #endif
 #ifndef SR_TUNE_WAVES_KAHAN
 #define SR_TUNE_WAVES_KAHAN 12
@@ -62,7 +68,7 @@ namespace sr {
 #define SR_TUNE_WAVES_CAST 0
 #endif
 #ifndef SR_TUNE_WAVES_CAST8
-#define SR_TUNE_WAVES_CAST8 28
+#define SR_TUNE_WAVES_CAST8 24
 #endif
 #ifndef SR_TUNE_WAVES_ACC
 #define SR_TUNE_WAVES_ACC 0

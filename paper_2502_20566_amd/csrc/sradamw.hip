@@ -4,6 +4,7 @@
 // nothing synchronises with the host.
 #include "../../include/sradamw.h"
 #include "sr_kernels.h"
+#include "sr_host.h"
 
 #include <atomic>
 #include <cmath>
@@ -13,6 +14,10 @@
 namespace {
 
 using namespace sr;
+using sr_host::blocks_spanned;
+using sr_host::chunks_of;
+using sr_host::range_wraps;
+using sr_host::split_tensor;
 
 thread_local int g_last_hip_error = 0;
 
@@ -76,16 +81,14 @@ std::atomic<uint32_t> g_fp8_integer{0};
 // Waves resident per CU.  A stream that mixes reads and writes runs FASTER on MI355X with fewer
 // waves in flight than the 32 single-wave workgroups a CU can hold: each kernel class below states
 // how many it lets reside, and the launch reserves that share of the CU's 160 KiB of LDS per
-// workgroup (LDS that no kernel touches) so that the hardware admits no more.  0 = no cap.  The
-// debug hook overrides the number for measurements.
+// workgroup (LDS that no kernel touches, granted in units of 1280 bytes: sr_host::occupancy_lds)
+// so that the hardware admits no more.  0 = no cap.  The debug hook overrides the number for
+// measurements.
 std::atomic<uint32_t> g_resident_waves{0};
-constexpr uint32_t kLdsPerCu = 160u * 1024u;
 inline uint32_t occupancy_lds(uint32_t class_default)
 {
     const uint32_t forced = g_resident_waves.load(std::memory_order_relaxed);
-    const uint32_t waves = forced ? forced : class_default;
-    if (waves == 0 || waves >= 32) return 0;
-    return (kLdsPerCu / (waves < 3 ? 3 : waves)) & ~511u;     // a launch may ask for at most 64 KiB
+    return sr_host::occupancy_lds(forced ? forced : class_default);
 }
 constexpr uint32_t kWavesUpdateBf16 = SR_TUNE_WAVES_BF16;    // BF16 moments (14 bytes per element)
 constexpr uint32_t kWavesUpdateKahan = SR_TUNE_WAVES_KAHAN;  // BF16 moments + BF16 compensation (18)
@@ -94,31 +97,6 @@ constexpr uint32_t kWavesUpdateFp8 = SR_TUNE_WAVES_FP8M;     // 8-bit moments
 constexpr uint32_t kWavesCast = SR_TUNE_WAVES_CAST;          // the standalone cast to BF16
 constexpr uint32_t kWavesCast8 = SR_TUNE_WAVES_CAST8;        // the standalone cast to an 8-bit format
 constexpr uint32_t kWavesAcc = SR_TUNE_WAVES_ACC;            // gradient accumulation
-
-// True when the counter indices elem_offset .. elem_offset + numel (rounded up to a block) leave 64 bits.
-inline bool range_wraps(uint64_t elem_offset, uint64_t numel)
-{
-    return numel > UINT64_MAX - 8 || elem_offset > UINT64_MAX - 8 - numel;
-}
-
-// Calls f(local, numel, elem_offset) for consecutive pieces of a tensor slice of `numel` elements
-// whose element 0 has counter index `elem_offset`; every piece spans at most blocks_per_piece
-// counter blocks and all but the first start on a block boundary.  local = index of the piece's
-// first element in the slice.  Stops at the first failure.
-template <class F>
-hipError_t split_tensor(uint64_t numel, uint64_t elem_offset, uint64_t blocks_per_piece, F f)
-{
-    const uint64_t G0 = elem_offset, gblk0 = G0 >> 3;
-    const uint64_t nblk = ((G0 + numel - 1) >> 3) - gblk0 + 1;
-    for (uint64_t b = 0; b < nblk; b += blocks_per_piece) {
-        const uint64_t bend = nblk - b < blocks_per_piece ? nblk : b + blocks_per_piece;
-        const uint64_t gfirst = b == 0 ? G0 : (gblk0 + b) << 3;
-        const uint64_t gend = bend == nblk ? G0 + numel : (gblk0 + bend) << 3;
-        const hipError_t e = f(gfirst - G0, gend - gfirst, gfirst);
-        if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
-}
 
 template <uint32_t F, bool VAR>
 hipError_t launch_adamw_v(bool clip, const AdamwBatch& batch, uint32_t n_chunks, hipStream_t stream)
@@ -317,9 +295,11 @@ static int sum_of_squares(const sr_tensor_t* tensors, uint32_t n_tensors, float*
         if (tensors[i].numel == 0) continue;
         if (!tensors[i].g) return SR_ERR_NULL;
         if (!aligned(tensors[i].g, 2)) return SR_ERR_ALIGN;
-        total_chunks += (tensors[i].numel + kNormChunkElems - 1) / kNormChunkElems;
+        uint64_t nch = 0;
+        if (!chunks_of(tensors[i].numel, kNormChunkElems, &nch)) return SR_ERR_ARG;
+        total_chunks += nch;
+        if (total_chunks > 0xFFFFFFFFull) return SR_ERR_ARG;      // partial sums are indexed with 32 bits
     }
-    if (total_chunks > 0xFFFFFFFFull) return SR_ERR_ARG;
     if (total_chunks) {
         if (!partials || !aligned(partials, 8)) return SR_ERR_WORKSPACE;
         if (capacity < total_chunks) return SR_ERR_WORKSPACE;
@@ -379,9 +359,12 @@ int grad_sum_of_squares(const sr_tensor_t* tensors, uint32_t n_tensors, double* 
 int grad_global_norm_static(const sr_tensor_t* tensors, uint32_t n_tensors, float* d_norm_out, void* stream)
 {
     uint64_t total_chunks = 0;
-    for (uint32_t i = 0; tensors && i < n_tensors; ++i)
-        total_chunks += (tensors[i].numel + kNormChunkElems - 1) / kNormChunkElems;
-    if (total_chunks > kStaticPartials) return SR_ERR_SIZE;
+    for (uint32_t i = 0; tensors && i < n_tensors; ++i) {
+        uint64_t nch = 0;
+        if (!chunks_of(tensors[i].numel, kNormChunkElems, &nch)) return SR_ERR_ARG;
+        total_chunks += nch;
+        if (total_chunks > kStaticPartials) return SR_ERR_SIZE;
+    }
     double* partials = nullptr;
     const int rc = static_scratch(&partials);
     if (rc != SR_OK) return rc;
@@ -415,10 +398,10 @@ int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scal
         if (!t.acc || !t.grad) return SR_ERR_NULL;
         if (!aligned(t.acc, 2) || !aligned(t.grad, 2)) return SR_ERR_ALIGN;
         if (range_wraps(t.elem_offset, t.numel)) return SR_ERR_ARG;
-        const uint64_t nblk = ((t.elem_offset + t.numel - 1) >> 3) - (t.elem_offset >> 3) + 1;
+        const uint64_t nblk = blocks_spanned(t.numel, t.elem_offset);
         total_chunks += (nblk + blocks_per_chunk - 1) / blocks_per_chunk;
+        if (total_chunks > 0xFFFFFFFFull) return SR_ERR_ARG;      // partial sums are indexed with 32 bits
     }
-    if (total_chunks > 0xFFFFFFFFull) return SR_ERR_ARG;
     if (d_norm_out && total_chunks) {
         uint64_t need = total_chunks, level = total_chunks;
         while (level > kReduceAbove) { level = (level + kReduceFan - 1) / kReduceFan; need += level; }
@@ -453,7 +436,7 @@ int sr_grad_accumulate(const sr_accum_t* tensors, uint32_t n_tensors, float scal
         if (t.numel == 0) continue;
         const hipError_t pe = split_tensor(t.numel, t.elem_offset, (uint64_t)mg * blocks_per_chunk,
                                            [&](uint64_t local, uint64_t numel, uint64_t goff) -> hipError_t {
-            const uint64_t nblk = ((goff + numel - 1) >> 3) - (goff >> 3) + 1;
+            const uint64_t nblk = blocks_spanned(numel, goff);
             const uint32_t nch = (uint32_t)((nblk + blocks_per_chunk - 1) / blocks_per_chunk);
             if (nb == kAccMaxBatch || (uint64_t)chunks_in_batch + nch > mg) {
                 const hipError_t e = flush();
@@ -596,7 +579,7 @@ int sr_adamw_step(const sr_tensor_t* tensors, uint32_t n_tensors, const sr_hyper
         if (t.numel == 0) continue;
         const hipError_t pe = split_tensor(t.numel, t.elem_offset, (uint64_t)mg * per_chunk,
                                            [&](uint64_t local, uint64_t numel, uint64_t goff) -> hipError_t {
-            const uint64_t nblk = ((goff + numel - 1) >> 3) - (goff >> 3) + 1;
+            const uint64_t nblk = blocks_spanned(numel, goff);
             const uint32_t nch = (uint32_t)((nblk + per_chunk - 1) / per_chunk);
             if (nb == kMaxBatch || (uint64_t)chunks_in_batch + nch > mg) {
                 const hipError_t e = flush();
