@@ -376,6 +376,31 @@ def _mode_run(flags, fp32, make_aux, steps=5, clip=None):
     return pair
 
 
+@pytest.mark.parametrize("fp32", [False, True])
+def test_adamw_counter_indices_at_the_top_of_their_range(fp32):
+    """elem_offset + numel may reach 2^64 - 9 (the last counter block must not wrap): slices that end on
+    the largest index the library accepts, aligned and mid-block, several chunks long, against the
+    oracle; one element further is refused."""
+    top = (1 << 64) - 1
+    sizes = [5, 8, 1000, 3 * 512 + 77, 20000]
+    params, grads, ms, vs, offs = [], [], [], [], []
+    for i, n in enumerate(sizes):
+        p, g, m, v = _random_state(n, 900 + i, fp32)
+        params.append(p); grads.append(g); ms.append(m); vs.append(v)
+        end = top - 8 - (0, 1, 7, 8, 13)[i]                  # elem_offset + numel
+        offs.append(end - n)
+    pair = Pair(params, ms, vs, fp32, tensor_ids=[11 * i + 2 for i in range(len(sizes))], elem_offsets=offs)
+    for gd, gs in zip(pair.g, grads):
+        gd.copy_(gs)
+    hyper = dict(lr=3e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    for t in (1, 2):
+        pair.step(hyper, t, 0xFEDCBA9876543210)
+        pair.compare(f"top-of-range offsets (fp32 moments {fp32}) step {t}")
+    bad = B.TensorList(params[:1], pair.g[:1], ms[:1], vs[:1], fp32, [2], [top - 8 - sizes[0] + 1])
+    with pytest.raises(B.SrError):
+        B.sr_adamw_step(bad, hyper, 3, 1, B.SR_FLAG_FP32_MOMENTS if fp32 else 0)
+
+
 def test_adamw_all_nearest_bf16_strategy():
     # Section 5.1's "BF16" strategy: every write-back rounded to nearest, no random bits
     a = _mode_run(B.SR_FLAG_RNE_PARAMS | B.SR_FLAG_RNE_MOMENTS, False, None)
