@@ -642,6 +642,33 @@ def test_grad_accumulate_micro_batches_bit_exact_with_fused_norm():
         assert bool(np.all(to_np(accs[i]) == h))
 
 
+def test_grad_accumulate_counter_indices_at_the_top_of_their_range():
+    """Accumulation on slices that end on the largest counter index the library accepts
+    (elem_offset + numel = 2^64 - 9 and a little below, aligned and mid-block), with the fused norm."""
+    top = (1 << 64) - 1
+    sizes = [3, 8, 513, 4 * 512 + 31, 30000]
+    accs = [(torch.randn(n, device=DEV) * 1e-3).to(torch.bfloat16) for n in sizes]
+    micro = [torch.empty(n, dtype=torch.bfloat16, device=DEV) for n in sizes]
+    offs = [top - 8 - back - n for n, back in zip(sizes, (0, 3, 8, 1, 16))]
+    al = B.AccumList(accs, micro, tensor_ids=[5 * i + 1 for i in range(len(sizes))], elem_offsets=offs)
+    host = [to_np(a) for a in accs]
+    norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+    ws = torch.empty(max(al.workspace_bytes(), 256), dtype=torch.uint8, device=DEV)
+    for k in range(2):
+        W.fill_grads(micro, 950 + k, 1e-3)
+        B.sr_grad_accumulate(al, 0.5, 7 + k, 0x0123456789ABCDEF, 0, norm, ws)
+        torch.cuda.synchronize()
+        for i, h in enumerate(host):
+            ref.grad_accumulate(h, to_np(micro[i]), 0.5, 7 + k, 0x0123456789ABCDEF, tensor_id=5 * i + 1, elem_offset=offs[i])
+            assert bool(np.all(to_np(accs[i]) == h)), f"micro-batch {k} tensor {i}"
+        want = ref.grad_global_norm(host)
+        got = float(norm.item())
+        assert got == want or abs(got - want) <= 1e-6 * want
+    bad = B.AccumList(accs[:1], micro[:1], tensor_ids=[1], elem_offsets=[top - 8 - sizes[0] + 1])
+    with pytest.raises(B.SrError):
+        B.sr_grad_accumulate(bad, 0.5, 9, 1, 0)
+
+
 def test_grad_accumulate_norm_feeds_a_clipped_step():
     cfg = W.config(3)
     shapes = W.gpt_shapes(64, 2, 256, 5003, 64)
