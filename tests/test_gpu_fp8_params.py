@@ -175,6 +175,24 @@ def test_fp8_params_cut_into_many_launches():
         B.lib().sr_debug_set(B.SR_DEBUG_LAUNCH_LIMIT, 0)
 
 
+@pytest.mark.parametrize("fp8m", [None, (12, 30)])
+def test_fp8_params_counter_indices_up_to_their_limit(fp8m):
+    """An 8-bit parameter draws a 32-bit word per element, so its stream counts blocks of four
+    elements and elem_offset + numel may reach 2^63: slices that end there and a little below,
+    aligned and mid-block, against the oracle; one element further is refused."""
+    exps = lambda k: None if fp8m is None else [fp8m] * k
+    lim = 1 << 63
+    sizes = [5, 8, 1000, 3 * 512 + 77]
+    offs = [lim - back - n for n, back in zip(sizes, (0, 1, 4, 13))]
+    st = State(sizes, [11, 10, 11, 9], seed=21, fp8m=exps(4), offsets=offs, ids=[3, 9, 27, 81], codes="weights")
+    for t in (1, 2):
+        st.step(t, 0xFEDCBA9876543210, g_std=1e-3)
+        st.check(f"offsets ending at 2^63, step {t}")
+    over = State([5], [11], seed=22, fp8m=exps(1), offsets=[lim - 4], ids=[3], codes="weights")
+    with pytest.raises(B.SrError):
+        B.sr_adamw_step(over.tl, HYP, 1, 0, FP8P | (B.SR_FLAG_FP8_MOMENTS if fp8m else 0))
+
+
 def test_fp8_params_arguments():
     st = State([64], [11], seed=1)
     for bad in (FP8P | B.SR_FLAG_RNE_PARAMS, FP8P | B.SR_FLAG_RNE_MOMENTS, FP8P | B.SR_FLAG_KAHAN):
