@@ -4,7 +4,8 @@ of their 10 steps.  Configs 4 and 5: the GPU updates the whole parameter set; th
 seeded windows of it -- the first and last 2^20 elements of every tensor and 64 random windows of
 2^20 elements, for config 5 also windows that straddle element index 2^32 -- through every step from
 step 1, compared after every step (the update is element-wise and the RNG is random-access, so a
-window with its element offset is self-contained).
+window with its element offset is self-contained).  Configs 4 and 5 in addition: one step (the third) of the
+whole parameter set, every element.
 """
 import numpy as np
 import pytest
@@ -171,6 +172,35 @@ def test_config4_full_size_windows_fp32_moments_clip():
         assert win.mismatches(params, ms, vs) == 0, f"config 4 step {t}"
 
 
+def test_config4_every_element_of_one_step():
+    """All 2 651 591 680 elements of the 388-tensor list with binary32 moments and clipping: three
+    steps on the GPU, the state before the third kept on the device, and the oracle redoes that
+    step tensor by tensor (in slabs of 2^27 elements, each a slice with its element offset) with
+    the norm the device computed; p and the binary32 m and v must come out bit for bit."""
+    cfg = W.config(4)
+    params, grads, ms, vs, tl, norm, ws = setup(cfg)
+    for t in (1, 2):
+        W.fill_grads(grads, W.data_seed(4, t), cfg.grad_std)
+        gpu_step(cfg, tl, t, norm, ws)
+    W.fill_grads(grads, W.data_seed(4, 3), cfg.grad_std)
+    before = [[x.clone() for x in arr] for arr in (params, ms, vs)]
+    nv = gpu_step(cfg, tl, 3, norm, ws)
+    slab, done = 1 << 27, 0
+    for i in range(len(params)):
+        n = params[i].numel()
+        for lo in range(0, n, slab):
+            k = min(slab, n - lo)
+            h = dict(p=to_np(before[0][i][lo:lo + k]), m=to_np(before[1][i][lo:lo + k]), v=to_np(before[2][i][lo:lo + k]),
+                     g=to_np(grads[i][lo:lo + k]), tensor_id=i, elem_offset=lo)
+            ref.sr_adamw_step([h], cfg.hyper, 3, cfg.seed, ref.FLAG_FP32_MOMENTS, norm=nv, max_norm=cfg.clip)
+            bad = same_bf16(to_np(params[i][lo:lo + k]), h["p"])
+            bad += int((to_np(ms[i][lo:lo + k]).view(np.uint32) != h["m"].view(np.uint32)).sum())
+            bad += int((to_np(vs[i][lo:lo + k]).view(np.uint32) != h["v"].view(np.uint32)).sum())
+            assert bad == 0, f"config 4, whole list: mismatches in tensor {i} at element {lo}"
+            done += k
+    assert done == 2651591680
+
+
 def test_config5_full_size_windows_through_warm_start():
     """The 6.7B flat buffer through its 100 warm steps and the timed step 101: the oracle follows
     the first and last 2^20 elements, windows that straddle element index 2^32 (where the counter's
@@ -194,6 +224,34 @@ def test_config5_full_size_windows_through_warm_start():
     # after the warm start the second moment is alive and updates are far below a BF16 spacing
     v_end = ref.bf16_bits_to_f32(win.host[0]["v"])
     assert float((v_end > 0).mean()) > 0.99
+
+
+def test_config5_every_element_of_one_step():
+    """The whole 6.7B flat buffer, every one of its 6 658 465 792 elements: three steps on the GPU
+    (so that the moments are alive), the state before the third kept on the device, and the oracle
+    redoes that step slab by slab (2^27 elements, each a slice with its element offset) on the
+    host; p, m and v of every slab must come out bit for bit."""
+    cfg = W.config(5)
+    params, grads, ms, vs, tl, norm, ws = setup(cfg)
+    n = params[0].numel()
+    for t in (1, 2):
+        W.fill_grads(grads, W.data_seed(5, t), cfg.grad_std)
+        gpu_step(cfg, tl, t, norm, ws)
+    W.fill_grads(grads, W.data_seed(5, 3), cfg.grad_std)
+    before = [params[0].clone(), ms[0].clone(), vs[0].clone()]
+    gpu_step(cfg, tl, 3, norm, ws)
+    slab, bad, moved = 1 << 27, 0, 0
+    for lo in range(0, n, slab):
+        k = min(slab, n - lo)
+        h = dict(p=to_np(before[0][lo:lo + k]), m=to_np(before[1][lo:lo + k]), v=to_np(before[2][lo:lo + k]),
+                 g=to_np(grads[0][lo:lo + k]), tensor_id=0, elem_offset=lo)
+        p0 = h["p"].copy()
+        ref.sr_adamw_step([h], cfg.hyper, 3, cfg.seed, 0)
+        moved += int((h["p"] != p0).sum())
+        bad += same_bf16(to_np(params[0][lo:lo + k]), h["p"])
+        bad += same_bf16(to_np(ms[0][lo:lo + k]), h["m"]) + same_bf16(to_np(vs[0][lo:lo + k]), h["v"])
+        assert bad == 0, f"config 5, whole buffer: mismatches in the slab at element {lo}"
+    assert moved > n // 100                                   # the step did move parameters
 
 
 def test_config5_full_size_windows_8_bit_moments():
